@@ -1,0 +1,339 @@
+/*
+ * KVCapsule CPU oracle  --  TEST INFRASTRUCTURE, NOT PART OF THE PRODUCT PATH.
+ *
+ * A plain, slow, double-precision statement of what the KVCapsule hot path
+ * computes, written from the paper (arxiv 2605.16439).  Only the test-suite,
+ * the smoke check and the benchmark's cpu_baseline leg may call it.  It shares
+ * no code, header, table or helper with the HIP library and never imports it.
+ *
+ * Every function takes HOST pointers to dense row-major double arrays (the
+ * caller up-casts dtype-rounded inputs exactly) and follows the paper's
+ * definitional order: compress (Sec. 3.1), reconstruct (Sec. 3.1), then the
+ * backbone's softmax attention over [reconstructed vision ; text] (Sec. 3.1
+ * attention equation, Sec. 3.2 "Decoding Stage").  The one exception is
+ * kvc_oracle_fused_order, which takes Algorithm 1's steps in the printed order
+ * and exists only so a test can check that the two orders agree.
+ *
+ * Notation (paper's): B batch, H_q query heads, H_kv KV heads, G = H_q/H_kv,
+ * d = d_head, n vision tokens per image block, I image blocks (vision span
+ * N = I*n), m = ceil(l_r * n) compressed length, t text tokens in the cache.
+ *
+ * Readings of the paper used here (each listed in the design notes):
+ *  - l_r = 1 - compression ratio; the same per-layer M, theta, U, mu are applied
+ *    to each of the I blocks of n tokens and to every batch element.
+ *  - f_theta is taken in its inference form, the score reconstruction matrix
+ *    theta in R^{H_kv x m x n} of App. C:  K_hat = theta^T K_tilde.
+ *  - softmax is joint over vision and text keys (Sec. 3.2); Algorithm 1's
+ *    "P mu" is (sum of vision probabilities) * mu.
+ *  - mu is a fixed per-KV-head parameter at inference (Sec. 3.2).
+ *
+ * Parity pins: every function below is pinned by tests/test_oracle_pins.py
+ * (closed forms, invariants, library SDPA, SVD/Eckart-Young, brute force).
+ * Accuracy-type claims of the paper (cosine-similarity tables, benchmark
+ * scores, the L~626 break-even) need trained parameters: parity unpinned.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_STORE_NONE (-1)
+#define ORACLE_STORE_F32 0
+#define ORACLE_STORE_BF16 1
+
+/* ---- compressed length: |M_l| = ceil(l_r n), l_r = 1 - c  (Sec. 3.1, Keys) ---- */
+int32_t kvc_oracle_compressed_len(int32_t n, double compression_ratio)
+{
+    if (n <= 0) return 0;
+    double x = (1.0 - compression_ratio) * (double)n;
+    /* the tiny backoff keeps products that are integers in exact arithmetic
+       (0.5*576) from being pushed up by the rounding of (1-c) */
+    double m = ceil(x - 1e-9);
+    if (m < 1.0) m = 1.0;
+    if (m > (double)n) m = (double)n;
+    return (int32_t)m;
+}
+
+/* ---- round-to-nearest-even to the storage type of the capsule ---- */
+static double round_bf16(double x)
+{
+    if (x == 0.0 || isnan(x) || isinf(x)) return x;
+    int e;
+    (void)frexp(x, &e);          /* |x| = f * 2^e, f in [0.5,1)  => exponent of x is e-1 */
+    int ex = e - 1;
+    if (ex < -126) ex = -126;    /* subnormal range of an 8-bit-exponent format */
+    /* bf16 keeps 8 significant bits: quantum is 2^(ex-7) */
+    double q = ldexp(1.0, ex - 7);
+    double r = nearbyint(x / q) * q;   /* default rounding mode: ties to even */
+    if (fabs(r) > 3.3895313892515355e38) r = copysign(INFINITY, x);
+    return r;
+}
+
+double kvc_oracle_round_to(double x, int store_dtype)
+{
+    if (store_dtype == ORACLE_STORE_F32) return (double)(float)x;
+    if (store_dtype == ORACLE_STORE_BF16) return round_bf16(x);
+    return x;
+}
+
+/*
+ * Compress (Sec. 3.1; Sec. 3.2 "Prefilling Stage").
+ *   K_tilde[b,h,i,j,:] = K[b,h, vis_start + i n + M[j], :]                 (row selection)
+ *   V_tilde[b,h,i,j,:] = sum_p U[h,j,p] (V[b,h, vis_start + i n + p, :] - mu[h,:])
+ * K,V: [B][H_kv][S][d];  key_idx: [m];  U: [H_kv][m][n];  mu: [H_kv][d]
+ * Kc,Vc out: [B][H_kv][I][m][d];  V_tilde is rounded to store_dtype, K_tilde is a copy.
+ */
+void kvc_oracle_compress(int32_t B, int32_t Hkv, int32_t S, int32_t d, int32_t n, int32_t I,
+                         int32_t m, int32_t vis_start, const double *K, const double *V,
+                         const int32_t *key_idx, const double *U, const double *mu,
+                         int store_dtype, double *Kc, double *Vc)
+{
+    long units = (long)B * Hkv * I;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long u = 0; u < units; ++u) {
+        int i = (int)(u % I);
+        int h = (int)((u / I) % Hkv);
+        int b = (int)(u / ((long)I * Hkv));
+        const double *Kb = K + (((long)b * Hkv + h) * S + vis_start + (long)i * n) * d;
+        const double *Vb = V + (((long)b * Hkv + h) * S + vis_start + (long)i * n) * d;
+        double *Kout = Kc + u * (long)m * d;
+        double *Vout = Vc + u * (long)m * d;
+        const double *Uh = U + (long)h * m * n;
+        const double *muh = mu + (long)h * d;
+        for (int j = 0; j < m; ++j) {
+            for (int c = 0; c < d; ++c) Kout[(long)j * d + c] = Kb[(long)key_idx[j] * d + c];
+            for (int c = 0; c < d; ++c) {
+                double acc = 0.0;
+                for (int p = 0; p < n; ++p)
+                    acc += Uh[(long)j * n + p] * (Vb[(long)p * d + c] - muh[c]);
+                Vout[(long)j * d + c] = kvc_oracle_round_to(acc, store_dtype);
+            }
+        }
+    }
+}
+
+/*
+ * Reconstruct (Sec. 3.1; Sec. 3.2 "Decoding Stage"), from the stored capsule:
+ *   K_hat[b,h,i,p,:] = sum_j theta[h,j,p] K_tilde[b,h,i,j,:]
+ *   V_hat[b,h,i,p,:] = sum_j U[h,j,p]     V_tilde[b,h,i,j,:] + mu[h,:]
+ * Khat,Vhat out: [B][H_kv][I*n][d], not rounded.
+ */
+void kvc_oracle_reconstruct(int32_t B, int32_t Hkv, int32_t d, int32_t n, int32_t I, int32_t m,
+                            const double *Kc, const double *Vc, const double *theta,
+                            const double *U, const double *mu, double *Khat, double *Vhat)
+{
+    long units = (long)B * Hkv * I;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long u = 0; u < units; ++u) {
+        int h = (int)((u / I) % Hkv);
+        const double *Kt = Kc + u * (long)m * d;
+        const double *Vt = Vc + u * (long)m * d;
+        const double *Th = theta + (long)h * m * n;
+        const double *Uh = U + (long)h * m * n;
+        const double *muh = mu + (long)h * d;
+        double *Ko = Khat + u * (long)n * d;   /* [B][Hkv][I][n][d] == [B][Hkv][I*n][d] */
+        double *Vo = Vhat + u * (long)n * d;
+        for (int p = 0; p < n; ++p) {
+            double *kr = Ko + (long)p * d;
+            double *vr = Vo + (long)p * d;
+            for (int c = 0; c < d; ++c) { kr[c] = 0.0; vr[c] = 0.0; }
+            for (int j = 0; j < m; ++j) {
+                double th = Th[(long)j * n + p];
+                double uu = Uh[(long)j * n + p];
+                const double *ks = Kt + (long)j * d;
+                const double *vs = Vt + (long)j * d;
+                for (int c = 0; c < d; ++c) { kr[c] += th * ks[c]; vr[c] += uu * vs[c]; }
+            }
+            for (int c = 0; c < d; ++c) vr[c] += muh[c];
+        }
+    }
+}
+
+/*
+ * Softmax attention of one query row per head over [vision ; text] keys
+ * (attention equation of Sec. 3.1; GQA: query head g reads KV head g / G).
+ *   s_x = scale * <q[b,g], k_x>,  p = softmax(s),  out[b,g,:] = sum_x p_x v_x
+ * Kvis,Vvis: [B][H_kv][Nvis][d];  Ktxt,Vtxt: [B][H_kv][Tcap][d] (first t rows valid)
+ * q,out: [B][H_q][d];  lse (optional): [B][H_q];  probs (optional): [B][H_q][Nvis+t]
+ */
+void kvc_oracle_attend(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t Nvis,
+                       const double *Kvis, const double *Vvis, int32_t t, int32_t Tcap,
+                       const double *Ktxt, const double *Vtxt, const double *q, double scale,
+                       double *out, double *lse, double *probs)
+{
+    int G = Hq / Hkv;
+    long rows = (long)B * Hq;
+    long X = (long)Nvis + t;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long r = 0; r < rows; ++r) {
+        int g = (int)(r % Hq);
+        int b = (int)(r / Hq);
+        int h = g / G;
+        const double *qr = q + r * d;
+        const double *Kv = Kvis + ((long)b * Hkv + h) * (long)Nvis * d;
+        const double *Vv = Vvis + ((long)b * Hkv + h) * (long)Nvis * d;
+        const double *Kt = Ktxt ? Ktxt + ((long)b * Hkv + h) * (long)Tcap * d : 0;
+        const double *Vt = Vtxt ? Vtxt + ((long)b * Hkv + h) * (long)Tcap * d : 0;
+        double *s = (double *)malloc(sizeof(double) * (size_t)(X > 0 ? X : 1));
+        double smax = -INFINITY;
+        for (long x = 0; x < X; ++x) {
+            const double *kr = x < Nvis ? Kv + x * d : Kt + (x - Nvis) * d;
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) acc += qr[c] * kr[c];
+            s[x] = acc * scale;
+            if (s[x] > smax) smax = s[x];
+        }
+        double den = 0.0;
+        for (long x = 0; x < X; ++x) { s[x] = exp(s[x] - smax); den += s[x]; }
+        double *o = out + r * d;
+        for (int c = 0; c < d; ++c) o[c] = 0.0;
+        for (long x = 0; x < X; ++x) {
+            double p = s[x] / den;
+            const double *vr = x < Nvis ? Vv + x * d : Vt + (x - Nvis) * d;
+            for (int c = 0; c < d; ++c) o[c] += p * vr[c];
+            if (probs) probs[r * X + x] = p;
+        }
+        if (lse) lse[r] = X > 0 ? smax + log(den) : -INFINITY;
+        free(s);
+    }
+}
+
+/*
+ * One decode step of one layer (Sec. 3.2 "Decoding Stage"): optionally append
+ * the new token's k,v to the text cache at row t, reconstruct the vision K/V
+ * from the capsule, attend over [vision ; text].  Returns 0, or -1 when the
+ * temporaries cannot be allocated or the append does not fit.
+ * k_new,v_new: [B][H_kv][d] or NULL.  Ktxt/Vtxt are modified when appending.
+ */
+int kvc_oracle_reconstruct_attend_decode(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t n,
+                                         int32_t I, int32_t m, const double *Kc, const double *Vc,
+                                         const double *theta, const double *U, const double *mu,
+                                         double *Ktxt, double *Vtxt, int32_t t, int32_t Tcap,
+                                         const double *k_new, const double *v_new,
+                                         const double *q, double scale, double *out, double *lse)
+{
+    if (k_new && v_new) {
+        if (t + 1 > Tcap) return -1;
+        for (long bh = 0; bh < (long)B * Hkv; ++bh) {
+            memcpy(Ktxt + (bh * Tcap + t) * d, k_new + bh * d, sizeof(double) * d);
+            memcpy(Vtxt + (bh * Tcap + t) * d, v_new + bh * d, sizeof(double) * d);
+        }
+        t += 1;
+    }
+    size_t elems = (size_t)B * Hkv * (size_t)I * n * d;
+    double *Khat = (double *)malloc(sizeof(double) * (elems ? elems : 1));
+    double *Vhat = (double *)malloc(sizeof(double) * (elems ? elems : 1));
+    if (!Khat || !Vhat) { free(Khat); free(Vhat); return -1; }
+    kvc_oracle_reconstruct(B, Hkv, d, n, I, m, Kc, Vc, theta, U, mu, Khat, Vhat);
+    kvc_oracle_attend(B, Hq, Hkv, d, I * n, Khat, Vhat, t, Tcap, Ktxt, Vtxt, q, scale, out, lse, 0);
+    free(Khat);
+    free(Vhat);
+    return 0;
+}
+
+/*
+ * Algorithm 1 ("Fused KVCapsule for Layer l"), steps in the printed order, with
+ * the softmax taken jointly with the text keys (Sec. 3.2) -- Algorithm 1 itself
+ * is the t = 0 case:
+ *   S_comp = (q K_tilde^T) sigma                      [per image block, length m]
+ *   L_img  = S_comp theta                             [length n]
+ *   P      = softmax([L_img of all blocks ; text logits])
+ *   W      = P_img U^T                                [length m]
+ *   Y      = sum_blocks W V_tilde + (sum P_img) mu + P_txt V_txt
+ * Used only by the test that checks it against the definitional order.
+ */
+void kvc_oracle_fused_order(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t n, int32_t I,
+                            int32_t m, const double *Kc, const double *Vc, const double *theta,
+                            const double *U, const double *mu, const double *Ktxt,
+                            const double *Vtxt, int32_t t, int32_t Tcap, const double *q,
+                            double scale, double *out)
+{
+    int G = Hq / Hkv;
+    long X = (long)I * n + t;
+    for (int b = 0; b < B; ++b)
+        for (int g = 0; g < Hq; ++g) {
+            int h = g / G;
+            const double *qr = q + ((long)b * Hq + g) * d;
+            const double *Th = theta + (long)h * m * n;
+            const double *Uh = U + (long)h * m * n;
+            double *L = (double *)malloc(sizeof(double) * (size_t)(X > 0 ? X : 1));
+            double *Scomp = (double *)malloc(sizeof(double) * (size_t)m);
+            double *W = (double *)malloc(sizeof(double) * (size_t)m);
+            for (int i = 0; i < I; ++i) {
+                const double *Kt = Kc + ((((long)b * Hkv + h) * I + i) * m) * d;
+                for (int j = 0; j < m; ++j) {
+                    double acc = 0.0;
+                    for (int c = 0; c < d; ++c) acc += qr[c] * Kt[(long)j * d + c];
+                    Scomp[j] = acc * scale;
+                }
+                for (int p = 0; p < n; ++p) {
+                    double acc = 0.0;
+                    for (int j = 0; j < m; ++j) acc += Scomp[j] * Th[(long)j * n + p];
+                    L[(long)i * n + p] = acc;
+                }
+            }
+            for (int x = 0; x < t; ++x) {
+                const double *kr = Ktxt + (((long)b * Hkv + h) * Tcap + x) * d;
+                double acc = 0.0;
+                for (int c = 0; c < d; ++c) acc += qr[c] * kr[c];
+                L[(long)I * n + x] = acc * scale;
+            }
+            double lmax = -INFINITY, den = 0.0;
+            for (long x = 0; x < X; ++x) if (L[x] > lmax) lmax = L[x];
+            for (long x = 0; x < X; ++x) { L[x] = exp(L[x] - lmax); den += L[x]; }
+            for (long x = 0; x < X; ++x) L[x] /= den;
+            double *o = out + ((long)b * Hq + g) * d;
+            for (int c = 0; c < d; ++c) o[c] = 0.0;
+            double pvis = 0.0;
+            for (int i = 0; i < I; ++i) {
+                const double *Vt = Vc + ((((long)b * Hkv + h) * I + i) * m) * d;
+                for (int j = 0; j < m; ++j) {
+                    double acc = 0.0;
+                    for (int p = 0; p < n; ++p) acc += L[(long)i * n + p] * Uh[(long)j * n + p];
+                    W[j] = acc;
+                }
+                for (int j = 0; j < m; ++j)
+                    for (int c = 0; c < d; ++c) o[c] += W[j] * Vt[(long)j * d + c];
+                for (int p = 0; p < n; ++p) pvis += L[(long)i * n + p];
+            }
+            for (int c = 0; c < d; ++c) o[c] += pvis * mu[(long)h * d + c];
+            for (int x = 0; x < t; ++x) {
+                const double *vr = Vtxt + (((long)b * Hkv + h) * Tcap + x) * d;
+                for (int c = 0; c < d; ++c) o[c] += L[(long)I * n + x] * vr[c];
+            }
+            free(L);
+            free(Scomp);
+            free(W);
+        }
+}
+
+/*
+ * Persistent memory of one layer (App. C, eqs. 1 and 2), in bytes:
+ *   S_base = 2 B H_kv (c + n_vis + t) d b_kv
+ *   S_ours = 2 B H_kv (c + m_vis + t) d b_kv + S_recon(theta) + S_PCA(U, mu)
+ * n_vis = I*n stored vision tokens, m_vis = I*m compressed ones; the parameter
+ * overhead is theta [H_kv][m][n] + U [H_kv][m][n] + mu [H_kv][d] in b_param bytes.
+ */
+void kvc_oracle_memory_footprint(int64_t B, int64_t Hkv, int64_t c_prompt, int64_t n, int64_t I,
+                                 int64_t m, int64_t t, int64_t d, int64_t b_kv, int64_t b_param,
+                                 int64_t *S_base, int64_t *S_ours)
+{
+    *S_base = 2 * B * Hkv * (c_prompt + I * n + t) * d * b_kv;
+    int64_t kv = 2 * B * Hkv * (c_prompt + I * m + t) * d * b_kv;
+    int64_t s_recon = Hkv * m * n * b_param;
+    int64_t s_pca = Hkv * m * n * b_param + Hkv * d * b_param;
+    *S_ours = kv + s_recon + s_pca;
+}
+
+/* threads the OpenMP loops above will use (1 when built without OpenMP) */
+int kvc_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
