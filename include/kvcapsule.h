@@ -1,0 +1,172 @@
+/*
+ * kvcapsule.h -- C ABI of the KVCapsule hot path on AMD MI355X (gfx950).
+ *
+ * KVCapsule (arxiv 2605.16439) keeps, per transformer layer, the vision-token
+ * part of the KV cache in a compact "capsule": keys by row selection with a
+ * learned mask M, values by a projection onto a sequence-axis PCA basis U after
+ * centring with mu (Sec. 3.1).  At every decode step the full-length vision K/V
+ * is reconstructed (keys with the reconstructor theta, values with U^T and mu)
+ * and the unmodified softmax attention runs over [vision ; text] (Sec. 3.2).
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *    never allocates, frees or keeps them; scratch memory comes in through the
+ *    `workspace` argument (size from kvc_workspace_bytes).
+ *  - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream) and return without synchronising.  Calls that share a
+ *    workspace must be ordered on one stream.
+ *  - Tensors are dense row-major with head_dim fastest unless strides are
+ *    passed.  Every pointer must be 16-byte aligned.
+ *  - The return value is a kvc_status; a negative value means nothing was
+ *    launched.  No exception crosses the boundary.
+ *  - Notation follows the paper: B batch, H_q query heads, H_kv KV heads,
+ *    G = H_q / H_kv (query head g reads KV head g / G), d = head_dim, n vision
+ *    tokens per image block, I image blocks (the vision span is I*n contiguous
+ *    tokens; the same per-layer parameters serve every block and every batch
+ *    element), m = ceil((1 - c) n) compressed length for compression ratio c,
+ *    t text tokens in the cache.
+ */
+#ifndef KVCAPSULE_H
+#define KVCAPSULE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KVC_OK = 0,
+    KVC_ERR_NULL = -1,        /* a required pointer is NULL                          */
+    KVC_ERR_SHAPE = -2,       /* a size or index is out of range or inconsistent     */
+    KVC_ERR_DTYPE = -3,       /* unknown element type                                */
+    KVC_ERR_ALIGN = -4,       /* a pointer or stride breaks the 16-byte rule         */
+    KVC_ERR_WORKSPACE = -5,   /* workspace missing or smaller than required          */
+    KVC_ERR_UNSUPPORTED = -6, /* valid but not implemented (e.g. head_dim > 256)     */
+    KVC_ERR_HIP = -7          /* the HIP runtime reported a launch error             */
+} kvc_status;
+
+typedef enum { KVC_F32 = 0, KVC_BF16 = 1 } kvc_dtype;
+
+/* One LAYER's problem. */
+typedef struct {
+    int32_t batch;         /* B >= 1                                                 */
+    int32_t n_q_heads;     /* H_q, a multiple of n_kv_heads                          */
+    int32_t n_kv_heads;    /* H_kv >= 1                                              */
+    int32_t head_dim;      /* d, a multiple of 8, at most 256                        */
+    int32_t n_img_tokens;  /* n >= 1: vision tokens of one image block               */
+    int32_t n_images;      /* I >= 0: number of blocks in the vision span            */
+    int32_t m;             /* compressed length, 1 <= m <= n (per layer, so a        */
+                           /* pyramid schedule is a sequence of calls with own m)    */
+    int32_t dtype;         /* kvc_dtype of K, V, q, out, capsule and parameters;     */
+                           /* accumulation is always fp32                            */
+} kvc_shape;
+
+/* Per-layer learned parameters, fixed at inference (Sec. 3.2). */
+typedef struct {
+    const int32_t *key_idx; /* M : [m] strictly ascending indices in [0, n); shared  */
+                            /* by heads, blocks and batch (Sec. 3.1, Keys).  Not     */
+                            /* validated on the device: out-of-range entries are the */
+                            /* caller's error.  Unused by the decode call.           */
+    const void *theta;      /* theta : [H_kv][m][n] key / score reconstructor        */
+                            /* (App. C; applied to scores in Alg. 1 step 2)          */
+    const void *U;          /* U : [H_kv][m][n] value PCA basis (Sec. 3.1, Values)   */
+    const void *mu;         /* mu : [H_kv][d] value centre (Sec. 3.1, Values)        */
+} kvc_params;
+
+/* |M| = ceil(l_r n) with retention l_r = 1 - compression_ratio (Sec. 3.1, Keys),
+ * clamped to [1, n]; products that are integers in exact arithmetic do not round
+ * up.  Host arithmetic only.  Returns 0 for n <= 0. */
+int32_t kvc_compressed_len(int32_t n, double compression_ratio);
+
+/* Bytes of scratch that kvc_compress and kvc_reconstruct_attend_decode need for
+ * this shape with up to max_text_len cached text rows (new token included).
+ * Host arithmetic only.  Returns 0 if the shape is invalid. */
+size_t kvc_workspace_bytes(const kvc_shape *shape, int32_t max_text_len);
+
+/* Persistent bytes of one layer, App. C eq. (1) (full cache) and eq. (2) (capsule
+ * + parameter overhead), for c_prompt + t text rows around the I*n vision tokens.
+ * Host arithmetic only; either output pointer may be NULL. */
+kvc_status kvc_memory_footprint(const kvc_shape *shape, int64_t c_prompt, int64_t t,
+                                int64_t *bytes_full_cache, int64_t *bytes_capsule);
+
+/* Compress one layer's vision K/V into the capsule (Sec. 3.1; Sec. 3.2
+ * "Prefilling Stage"):
+ *     Kc[b,h,i,j,:] = K[b,h, vis_start + i n + M[j], :]            (bit-exact copy)
+ *     Vc[b,h,i,j,:] = sum_p U[h,j,p] (V[b,h, vis_start + i n + p, :] - mu[h,:])
+ * with fp32 accumulation and one round-to-nearest-even to the storage type.
+ *  K, V  in : [B][H_kv][S][d] with element strides stride_b / stride_h / stride_s
+ *             (d contiguous; strides multiples of 8 elements); rows outside the
+ *             span [vis_start, vis_start + I n) are not touched -- text K/V stays
+ *             where the backbone keeps it.
+ *  Kc, Vc out: [B][H_kv][I][m][d] dense.
+ * Errors: NULL pointers, bad shape/dtype, vis_start < 0, misalignment. */
+kvc_status kvc_compress(const kvc_shape *shape, const kvc_params *params,
+                        const void *K, const void *V,
+                        int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                        int32_t vis_start,
+                        void *Kc, void *Vc,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* One decode step of one layer (Sec. 3.2 "Decoding Stage"): attention of one new
+ * query token per sequence over the reconstructed vision K/V and the text cache,
+ *     K_hat[b,h,i] = theta[h]^T Kc[b,h,i]            V_hat[b,h,i] = U[h]^T Vc[b,h,i] + 1 mu[h]^T
+ *     out[b,g,:]   = softmax(scale * q[b,g] . [K_hat[b,g/G] ; K_text[b,g/G]]^T) [V_hat ; V_text]
+ * evaluated in the score-space order of Alg. 1 (scores on the compressed keys,
+ * expanded with theta, probabilities folded through U^T), which never forms
+ * K_hat / V_hat in memory; the softmax is joint over vision and text keys.
+ *  q        in : [B][H_q][d]
+ *  Kc, Vc   in : capsule written by kvc_compress
+ *  K_text, V_text in/out: [B][H_kv][text_cap][d], first text_len rows valid; may
+ *             be NULL when text_cap == 0
+ *  k_new, v_new in (optional, both or neither): [B][H_kv][d]; if given they are
+ *             stored at row text_len of the text cache and attended, which needs
+ *             text_len + 1 <= text_cap
+ *  softmax_scale: sigma of Alg. 1; 0 selects 1/sqrt(d)
+ *  out      out: [B][H_q][d]
+ *  lse_out  out (optional): [B][H_q] float, log of the softmax denominator -- what a
+ *             caller needs to merge partial results of a sequence split
+ * Errors: NULL pointers, bad shape/dtype, text_len outside [0, text_cap], no key at
+ * all (I == 0 and no text row), misalignment, workspace too small. */
+kvc_status kvc_reconstruct_attend_decode(const kvc_shape *shape, const kvc_params *params,
+                                         const void *q, const void *Kc, const void *Vc,
+                                         void *K_text, void *V_text,
+                                         int32_t text_len, int32_t text_cap,
+                                         const void *k_new, const void *v_new,
+                                         float softmax_scale,
+                                         void *out, float *lse_out,
+                                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* The same operation and contract as kvc_reconstruct_attend_decode, forced onto
+ * the shape-agnostic scalar kernels (any n, m, d <= 256, either dtype).  The
+ * main entry point uses these for shapes its matrix-core kernels do not cover;
+ * this symbol exists so both code paths can be checked against each other. */
+kvc_status kvc_reconstruct_attend_decode_generic(const kvc_shape *shape, const kvc_params *params,
+                                                 const void *q, const void *Kc, const void *Vc,
+                                                 void *K_text, void *V_text,
+                                                 int32_t text_len, int32_t text_cap,
+                                                 const void *k_new, const void *v_new,
+                                                 float softmax_scale,
+                                                 void *out, float *lse_out,
+                                                 void *workspace, size_t workspace_bytes,
+                                                 void *stream);
+
+/* Same contract as kvc_compress, forced onto the scalar kernels. */
+kvc_status kvc_compress_generic(const kvc_shape *shape, const kvc_params *params,
+                                const void *K, const void *V,
+                                int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                                int32_t vis_start,
+                                void *Kc, void *Vc,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/* Static string for a status code. */
+const char *kvc_status_string(int32_t status);
+
+/* Library version, "major.minor". */
+const char *kvc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVCAPSULE_H */

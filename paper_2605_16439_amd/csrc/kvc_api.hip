@@ -1,0 +1,246 @@
+// C ABI of libkvcapsule.so: argument validation, host-side closed forms and dispatch.
+// Every check happens before the first HIP call, so a negative status means that
+// nothing touched the device.
+#include <math.h>
+
+#include "kvc_internal.h"
+
+using namespace kvc;
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+kvc_status check_shape(const kvc_shape *s)
+{
+    if (!s) return KVC_ERR_NULL;
+    if (s->dtype != KVC_F32 && s->dtype != KVC_BF16) return KVC_ERR_DTYPE;
+    if (s->batch < 1 || s->n_kv_heads < 1 || s->n_q_heads < 1) return KVC_ERR_SHAPE;
+    if (s->n_q_heads % s->n_kv_heads != 0) return KVC_ERR_SHAPE;
+    if (s->head_dim < 8 || s->head_dim % 8 != 0) return KVC_ERR_SHAPE;
+    if (s->n_img_tokens < 1 || s->n_images < 0) return KVC_ERR_SHAPE;
+    if (s->m < 1 || s->m > s->n_img_tokens) return KVC_ERR_SHAPE;
+    if (s->head_dim > 256) return KVC_ERR_UNSUPPORTED;
+    // launch-grid limits of the kernels (grid.y / grid.z carry these products)
+    if (static_cast<int64_t>(s->batch) * s->n_q_heads > 65535) return KVC_ERR_UNSUPPORTED;
+    if (s->n_images > 65535) return KVC_ERR_UNSUPPORTED;
+    // 32-bit row counters inside the kernels
+    if (static_cast<int64_t>(s->n_images) * s->n_img_tokens > (1 << 30)) return KVC_ERR_UNSUPPORTED;
+    return KVC_OK;
+}
+
+kvc_status check_params(const kvc_params *p, bool need_idx, bool need_theta)
+{
+    if (!p) return KVC_ERR_NULL;
+    if (!p->U || !p->mu) return KVC_ERR_NULL;
+    if (need_idx && !p->key_idx) return KVC_ERR_NULL;
+    if (need_theta && !p->theta) return KVC_ERR_NULL;
+    if (!aligned16(p->U) || !aligned16(p->mu)) return KVC_ERR_ALIGN;
+    if (need_theta && !aligned16(p->theta)) return KVC_ERR_ALIGN;
+    if (need_idx && (reinterpret_cast<uintptr_t>(p->key_idx) & 3u)) return KVC_ERR_ALIGN;
+    return KVC_OK;
+}
+
+kvc_status prepare_decode(DecodeCall &c, const kvc_shape *shape, const kvc_params *params,
+                          const void *q, const void *Kc, const void *Vc, void *K_text,
+                          void *V_text, int32_t text_len, int32_t text_cap, const void *k_new,
+                          const void *v_new, float softmax_scale, void *out, float *lse_out,
+                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    kvc_status st = check_shape(shape);
+    if (st != KVC_OK) return st;
+    st = check_params(params, false, true);
+    if (st != KVC_OK) return st;
+    if (!q || !out) return KVC_ERR_NULL;
+    if (shape->n_images > 0 && (!Kc || !Vc)) return KVC_ERR_NULL;
+    if (text_cap < 0 || text_len < 0 || text_len > text_cap) return KVC_ERR_SHAPE;
+    if ((k_new == nullptr) != (v_new == nullptr)) return KVC_ERR_NULL;
+    if (k_new && text_len + 1 > text_cap) return KVC_ERR_SHAPE;
+    if (text_cap > 0 && (!K_text || !V_text)) return KVC_ERR_NULL;
+    const int32_t t = text_len + (k_new ? 1 : 0);
+    if (shape->n_images == 0 && t == 0) return KVC_ERR_SHAPE;   // softmax over no key
+    if (!(softmax_scale >= 0.f) || isinf(softmax_scale)) return KVC_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(out) || !aligned16(Kc) || !aligned16(Vc) ||
+        !aligned16(K_text) || !aligned16(V_text) || !aligned16(k_new) || !aligned16(v_new) ||
+        (reinterpret_cast<uintptr_t>(lse_out) & 3u))
+        return KVC_ERR_ALIGN;
+    if (!workspace) return KVC_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return KVC_ERR_ALIGN;
+    c.s = *shape;
+    c.theta = params->theta;
+    c.U = params->U;
+    c.mu = params->mu;
+    c.q = q;
+    c.Kc = Kc;
+    c.Vc = Vc;
+    c.Kt = K_text;
+    c.Vt = V_text;
+    c.t = t;
+    c.t_in = text_len;
+    c.cap = text_cap;
+    c.k_new = k_new;
+    c.v_new = v_new;
+    c.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf(static_cast<float>(shape->head_dim));
+    c.out = out;
+    c.lse = lse_out;
+    c.ws = workspace;
+    c.ws_bytes = workspace_bytes;
+    c.stream = static_cast<hipStream_t>(stream);
+    return KVC_OK;
+}
+
+kvc_status prepare_compress(CompressCall &c, const kvc_shape *shape, const kvc_params *params,
+                            const void *K, const void *V, int64_t stride_b, int64_t stride_h,
+                            int64_t stride_s, int32_t vis_start, void *Kc, void *Vc,
+                            void *workspace, size_t workspace_bytes, void *stream)
+{
+    kvc_status st = check_shape(shape);
+    if (st != KVC_OK) return st;
+    st = check_params(params, true, false);
+    if (st != KVC_OK) return st;
+    if (shape->n_images > 0 && (!K || !V || !Kc || !Vc)) return KVC_ERR_NULL;
+    if (vis_start < 0) return KVC_ERR_SHAPE;
+    if (stride_s < shape->head_dim || stride_h < 0 || stride_b < 0) return KVC_ERR_SHAPE;
+    if (stride_s % 8 || stride_h % 8 || stride_b % 8) return KVC_ERR_ALIGN;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(Kc) || !aligned16(Vc)) return KVC_ERR_ALIGN;
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 255u)) return KVC_ERR_ALIGN;
+    c.s = *shape;
+    c.key_idx = params->key_idx;
+    c.U = params->U;
+    c.mu = params->mu;
+    c.K = K;
+    c.V = V;
+    c.stride_b = stride_b;
+    c.stride_h = stride_h;
+    c.stride_s = stride_s;
+    c.vis_start = vis_start;
+    c.Kc = Kc;
+    c.Vc = Vc;
+    c.ws = workspace;
+    c.ws_bytes = workspace_bytes;
+    c.stream = static_cast<hipStream_t>(stream);
+    return KVC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t kvc_compressed_len(int32_t n, double compression_ratio)
+{
+    if (n <= 0) return 0;
+    // ceil((1 - c) n); the small backoff keeps exact-integer products such as
+    // 0.5 * 576 from rounding up because (1 - c) is not exact in binary
+    double v = ceil((1.0 - compression_ratio) * static_cast<double>(n) - 1e-9);
+    if (!(v >= 1.0)) v = 1.0;
+    if (v > static_cast<double>(n)) v = static_cast<double>(n);
+    return static_cast<int32_t>(v);
+}
+
+size_t kvc_workspace_bytes(const kvc_shape *shape, int32_t max_text_len)
+{
+    if (check_shape(shape) != KVC_OK || max_text_len < 0) return 0;
+    size_t need = generic_decode_ws_bytes(*shape, max_text_len);
+    if (fast_decode_supported(*shape)) {
+        size_t f = fast_decode_ws_bytes(*shape, max_text_len);
+        if (f > need) need = f;
+    }
+    if (fast_compress_supported(*shape)) {
+        size_t f = fast_compress_ws_bytes(*shape);
+        if (f > need) need = f;
+    }
+    return need;
+}
+
+kvc_status kvc_memory_footprint(const kvc_shape *shape, int64_t c_prompt, int64_t t,
+                                int64_t *bytes_full_cache, int64_t *bytes_capsule)
+{
+    kvc_status st = check_shape(shape);
+    if (st != KVC_OK) return st;
+    if (c_prompt < 0 || t < 0) return KVC_ERR_SHAPE;
+    const int64_t b = shape->dtype == KVC_F32 ? 4 : 2;
+    const int64_t B = shape->batch, H = shape->n_kv_heads, d = shape->head_dim;
+    const int64_t n = shape->n_img_tokens, I = shape->n_images, m = shape->m;
+    if (bytes_full_cache) *bytes_full_cache = 2 * B * H * (c_prompt + I * n + t) * d * b;
+    if (bytes_capsule)
+        *bytes_capsule = 2 * B * H * (c_prompt + I * m + t) * d * b   // compressed KV cache
+                         + H * m * n * b                               // theta
+                         + H * m * n * b + H * d * b;                  // U and mu
+    return KVC_OK;
+}
+
+kvc_status kvc_compress(const kvc_shape *shape, const kvc_params *params, const void *K,
+                        const void *V, int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                        int32_t vis_start, void *Kc, void *Vc, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    CompressCall c;
+    kvc_status st = prepare_compress(c, shape, params, K, V, stride_b, stride_h, stride_s,
+                                     vis_start, Kc, Vc, workspace, workspace_bytes, stream);
+    if (st != KVC_OK) return st;
+    if (fast_compress_supported(c.s)) return fast_compress(c);
+    return generic_compress(c);
+}
+
+kvc_status kvc_compress_generic(const kvc_shape *shape, const kvc_params *params, const void *K,
+                                const void *V, int64_t stride_b, int64_t stride_h,
+                                int64_t stride_s, int32_t vis_start, void *Kc, void *Vc,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    CompressCall c;
+    kvc_status st = prepare_compress(c, shape, params, K, V, stride_b, stride_h, stride_s,
+                                     vis_start, Kc, Vc, workspace, workspace_bytes, stream);
+    if (st != KVC_OK) return st;
+    return generic_compress(c);
+}
+
+kvc_status kvc_reconstruct_attend_decode(const kvc_shape *shape, const kvc_params *params,
+                                         const void *q, const void *Kc, const void *Vc,
+                                         void *K_text, void *V_text, int32_t text_len,
+                                         int32_t text_cap, const void *k_new, const void *v_new,
+                                         float softmax_scale, void *out, float *lse_out,
+                                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    DecodeCall c;
+    kvc_status st = prepare_decode(c, shape, params, q, Kc, Vc, K_text, V_text, text_len, text_cap,
+                                   k_new, v_new, softmax_scale, out, lse_out, workspace,
+                                   workspace_bytes, stream);
+    if (st != KVC_OK) return st;
+    if (fast_decode_supported(c.s)) return fast_decode(c);
+    return generic_decode(c);
+}
+
+kvc_status kvc_reconstruct_attend_decode_generic(const kvc_shape *shape, const kvc_params *params,
+                                                 const void *q, const void *Kc, const void *Vc,
+                                                 void *K_text, void *V_text, int32_t text_len,
+                                                 int32_t text_cap, const void *k_new,
+                                                 const void *v_new, float softmax_scale, void *out,
+                                                 float *lse_out, void *workspace,
+                                                 size_t workspace_bytes, void *stream)
+{
+    DecodeCall c;
+    kvc_status st = prepare_decode(c, shape, params, q, Kc, Vc, K_text, V_text, text_len, text_cap,
+                                   k_new, v_new, softmax_scale, out, lse_out, workspace,
+                                   workspace_bytes, stream);
+    if (st != KVC_OK) return st;
+    return generic_decode(c);
+}
+
+const char *kvc_status_string(int32_t status)
+{
+    switch (status) {
+    case KVC_OK: return "ok";
+    case KVC_ERR_NULL: return "a required pointer is NULL";
+    case KVC_ERR_SHAPE: return "size or index out of range or inconsistent";
+    case KVC_ERR_DTYPE: return "unknown element type";
+    case KVC_ERR_ALIGN: return "pointer or stride not aligned as required";
+    case KVC_ERR_WORKSPACE: return "workspace missing or too small";
+    case KVC_ERR_UNSUPPORTED: return "valid but unsupported shape";
+    case KVC_ERR_HIP: return "HIP runtime error at launch";
+    default: return "unknown status";
+    }
+}
+
+const char *kvc_version(void) { return "0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,93 @@
+// Internal declarations shared by the translation units of libkvcapsule.so.
+// Nothing here is part of the C ABI (include/kvcapsule.h is).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/kvcapsule.h"
+
+namespace kvc {
+
+// ---- element types -------------------------------------------------------------
+struct bf16_t {
+    uint16_t v;
+};
+
+__host__ __device__ inline float to_f(float x) { return x; }
+__device__ inline float to_f(bf16_t x) { return __uint_as_float(static_cast<uint32_t>(x.v) << 16); }
+
+// round-to-nearest-even fp32 -> bf16 bits
+__device__ inline uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);  // NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+
+template <class T> __device__ inline T from_f(float f);
+template <> __device__ inline float from_f<float>(float f) { return f; }
+template <> __device__ inline bf16_t from_f<bf16_t>(float f) { return bf16_t{f32_to_bf16_bits(f)}; }
+
+// ---- wavefront (64 lanes) reductions --------------------------------------------
+__device__ inline float wave_sum(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
+    return x;
+}
+__device__ inline float wave_max(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
+    return x;
+}
+
+// ---- one decode call, validated ----------------------------------------------------
+struct DecodeCall {
+    kvc_shape s;
+    const void *theta, *U, *mu;
+    const void *q, *Kc, *Vc;
+    void *Kt, *Vt;
+    int32_t t;        // text rows attended (new token included when appended)
+    int32_t t_in;     // rows valid before the call; the new token goes to this row
+    int32_t cap;
+    const void *k_new, *v_new;
+    float scale;
+    void *out;
+    float *lse;
+    void *ws;
+    size_t ws_bytes;
+    hipStream_t stream;
+};
+
+struct CompressCall {
+    kvc_shape s;
+    const int32_t *key_idx;
+    const void *U, *mu;
+    const void *K, *V;
+    int64_t stride_b, stride_h, stride_s;
+    int32_t vis_start;
+    void *Kc, *Vc;
+    void *ws;
+    size_t ws_bytes;
+    hipStream_t stream;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// scalar (shape-agnostic) path
+size_t generic_decode_ws_bytes(const kvc_shape &s, int32_t max_text);
+kvc_status generic_decode(const DecodeCall &c);
+kvc_status generic_compress(const CompressCall &c);
+
+// matrix-core path for bf16, head_dim 128
+bool fast_decode_supported(const kvc_shape &s);
+size_t fast_decode_ws_bytes(const kvc_shape &s, int32_t max_text);
+kvc_status fast_decode(const DecodeCall &c);
+bool fast_compress_supported(const kvc_shape &s);
+size_t fast_compress_ws_bytes(const kvc_shape &s);
+kvc_status fast_compress(const CompressCall &c);
+
+}  // namespace kvc
