@@ -1,21 +1,24 @@
 // Matrix-core decode path of KVCapsule for gfx950: bf16 storage, head_dim 128.
 //
-// One decode step of one layer = three launches that follow Alg. 1 of the paper
+// One decode step of one layer = four launches that follow Alg. 1 of the paper
 // (score-space order), with the softmax taken jointly over vision and text keys
 // (Sec. 3.2) by carrying (max, sum) statistics per tile and merging them at the end:
 //
-//   fa_scores  streams the compressed keys Kc and the text keys from HBM once,
-//              S = sigma q Kc^T (Alg. 1 step 1) and the text logits, one 16x16x32 MFMA
-//              tile per 16 key rows; also stores the new token's k, v in the text cache.
-//   fb_expand  per (KV head, 64 query rows, chunk of PC positions of an image block):
-//              L = S theta (step 2), P = exp(L - tile max), W_part = P U^T (step 3).  theta
-//              and U chunks are staged in LDS (theta transposed on the way in) and shared
-//              by the four wavefronts; the P tile goes from the accumulator layout of the
-//              first MFMA straight into the operand layout of the second.
-//   fc_output  streams the compressed values Vc and the text values once:
-//              out = sum_blocks W Vc + (sum P_vis) mu + P_txt V_text (step 4), W merged from
-//              the chunk partials with the global softmax statistics; partial outputs are
-//              summed by the last workgroup to finish each (batch, KV head).
+//   fa_scores   streams the compressed keys Kc and the text keys from HBM once,
+//               S = sigma q Kc^T (Alg. 1 step 1) and the text logits, one 16x16x32 MFMA
+//               tile per 16 key rows; also stores the new token's k, v in the text cache.
+//   fb_expand   per (KV head, 64 query rows, chunk of PC positions of an image block):
+//               L = S theta (step 2), P = exp(L - tile max), W_part = P U^T (step 3).  theta
+//               and U chunks are staged in LDS (theta transposed on the way in) and shared
+//               by the four wavefronts; the P tile goes from the accumulator layout of the
+//               first MFMA straight into the operand layout of the second.
+//   fc_output   streams the compressed values Vc and the text values once (step 4 and the
+//               text part): each workgroup merges the chunk partials of W for its rows and
+//               emits an un-normalised partial output with its own (max, sum).
+//   fd_finalize merges the partial outputs of each (batch, KV head) with the joint softmax
+//               statistics, adds (sum P_vis) mu, writes out and lse.
+// Kernel boundaries are the only grid-wide synchronisation: device-scope fences inside a
+// kernel write back and invalidate the L2 of an XCD and cost far more than a launch.
 //
 // Query rows of one KV head are ordered r = (b*I + i)*G + g, so the G query heads of a
 // group and all image blocks of a batch element share MFMA tiles.
@@ -33,6 +36,7 @@ constexpr int kTPW = 2;         // 16-row key tiles per wavefront in fa_scores
 constexpr int kXC = 128;        // text rows per fc_output workgroup
 constexpr int kMaxRowsPart = 256;
 constexpr int kMaxNC = 64;
+constexpr int kMaxParts = 256;
 constexpr size_t kLdsBudget = 150 * 1024;
 
 struct Plan {
@@ -47,9 +51,7 @@ struct Plan {
     float *Wp;
     float2 *stats;
     float *St;
-    float2 *tstats;
     float *Ypart;
-    int *cnt;
     size_t bytes;
 };
 
@@ -71,9 +73,6 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
-    if (blockIdx.x == 0)
-        for (int i = threadIdx.x; i < p.B * p.Hkv; i += 256) p.cnt[i] = 0;
-
     const int tile0 = (blockIdx.x * 4 + wave) * kTPW;
     uint4 kf[kTPW][4], qf[kTPW][4];
     bool live[kTPW];
@@ -155,8 +154,7 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
 }
 
 // ------------------------------------------------------------------------------------------
-// fb_expand: Alg. 1 steps 2 and 3 for one (KV head, 64 rows, PC positions) tile, plus the
-// per-(b, head) statistics of the text logits in trailing workgroups.
+// fb_expand: Alg. 1 steps 2 and 3 for one (KV head, 64 rows, PC positions) tile.
 // ------------------------------------------------------------------------------------------
 template <int PC>
 __global__ __launch_bounds__(256) void fb_expand(Plan p, const uint16_t *__restrict__ theta,
@@ -166,23 +164,6 @@ __global__ __launch_bounds__(256) void fb_expand(Plan p, const uint16_t *__restr
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
 
-    if (static_cast<int>(blockIdx.x) >= p.nvis_b) {
-        // text logits of one (batch, KV head): max and sum of exponentials per query head
-        const int bh = blockIdx.x - p.nvis_b;
-        const int b = bh / p.Hkv, h = bh - b * p.Hkv;
-        for (int g = wave; g < p.G; g += 4) {
-            const size_t bg = static_cast<size_t>(b) * p.Hq + h * p.G + g;
-            const float *row = p.St + bg * p.ld_t;
-            float mx = -INFINITY;
-            for (int x = lane; x < p.t; x += 64) mx = fmaxf(mx, row[x]);
-            mx = wave_max(mx);
-            float s = 0.f;
-            for (int x = lane; x < p.t; x += 64) s += __expf(row[x] - mx);
-            s = wave_sum(s);
-            if (lane == 0) p.tstats[bg] = make_float2(mx, s);
-        }
-        return;
-    }
     // rb is the slow index and its stride is a multiple of 8, so the workgroups that share a
     // (head, chunk) slice of theta and U land on the same XCD and share its L2
     const int rb = blockIdx.x / p.nvis_b_stride;
@@ -193,24 +174,59 @@ __global__ __launch_bounds__(256) void fb_expand(Plan p, const uint16_t *__restr
     const int LDT = p.m_pad + 8, LDU = PC + 8;
     uint16_t *ThT = lds;                 // [PC][LDT]   theta chunk, transposed: ThT[pos][j]
     uint16_t *Ul = lds + PC * LDT;       // [m16][LDU]  U chunk: Ul[j][pos]
-    constexpr int SEGS = PC / 8;
-    const int seg = threadIdx.x % SEGS, jj = threadIdx.x / SEGS;
-    constexpr int JSTEP = 256 / SEGS;
+
+    // scores of this wave's 16 rows: first batch of fragments in flight during the LDS fill
+    const int r0 = rb * kRB + wave * 16;
+    const bool wave_live = r0 < p.R;
+    const int r = r0 + r16;
+    const uint16_t *srow = p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + 8 * kg;
+    const int KS = p.m_pad / 32;
+    constexpr int SB = 8;
+    uint4 sfr[SB];
+#pragma unroll
+    for (int k = 0; k < SB; ++k)
+        sfr[k] = (wave_live && k < KS) ? *reinterpret_cast<const uint4 *>(srow + 32 * k) : make_uint4(0, 0, 0, 0);
+
+    // ---- stage the theta chunk (transposed) and the U chunk in LDS ------------------------------
+    // a thread owns a pair of consecutive rows j, j+1 and 8 positions; the pair is packed so the
+    // transposed store is one 32-bit word per position
+    constexpr int SEGS = PC / 8;                 // 16-byte segments per chunk row
+    constexpr int SPW = SEGS / 2;                // segments covered by one wave
+    const int seg = (lane / (64 / SPW)) + SPW * (wave & 1);
+    const int jp = (lane % (64 / SPW)) + (64 / SPW) * (wave >> 1);
+    constexpr int JPAIRS = 2 * (64 / SPW);       // row pairs per pass
     {
         const uint16_t *th = theta + static_cast<size_t>(h) * p.m * p.n + pc * PC + 8 * seg;
         const uint16_t *uh = U + static_cast<size_t>(h) * p.m * p.n + pc * PC + 8 * seg;
-        for (int j = jj; j < p.m16; j += JSTEP) {
-            uint4 tv = make_uint4(0, 0, 0, 0), uv = make_uint4(0, 0, 0, 0);
-            if (j < p.m) {
-                tv = *reinterpret_cast<const uint4 *>(th + static_cast<size_t>(j) * p.n);
-                uv = *reinterpret_cast<const uint4 *>(uh + static_cast<size_t>(j) * p.n);
-            }
-            *reinterpret_cast<uint4 *>(Ul + j * LDU + 8 * seg) = uv;
-            const uint32_t w[4] = {tv.x, tv.y, tv.z, tv.w};
+        constexpr int FB = 4;                    // passes per batch: 16 loads of 16 B in flight
+        for (int j0 = 2 * jp; j0 < p.m16; j0 += 2 * JPAIRS * FB) {
+            uint4 tv[FB][2], uv[FB][2];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                ThT[(8 * seg + 2 * e) * LDT + j] = static_cast<uint16_t>(w[e] & 0xffffu);
-                ThT[(8 * seg + 2 * e + 1) * LDT + j] = static_cast<uint16_t>(w[e] >> 16);
+            for (int k = 0; k < FB; ++k)
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int j = j0 + 2 * JPAIRS * k + e;
+                    tv[k][e] = make_uint4(0, 0, 0, 0);
+                    uv[k][e] = make_uint4(0, 0, 0, 0);
+                    if (j < p.m) {
+                        tv[k][e] = *reinterpret_cast<const uint4 *>(th + static_cast<size_t>(j) * p.n);
+                        uv[k][e] = *reinterpret_cast<const uint4 *>(uh + static_cast<size_t>(j) * p.n);
+                    }
+                }
+#pragma unroll
+            for (int k = 0; k < FB; ++k) {
+                const int j = j0 + 2 * JPAIRS * k;
+                if (j >= p.m16) break;
+                *reinterpret_cast<uint4 *>(Ul + j * LDU + 8 * seg) = uv[k][0];
+                *reinterpret_cast<uint4 *>(Ul + (j + 1) * LDU + 8 * seg) = uv[k][1];
+                const uint32_t a[4] = {tv[k][0].x, tv[k][0].y, tv[k][0].z, tv[k][0].w};
+                const uint32_t c[4] = {tv[k][1].x, tv[k][1].y, tv[k][1].z, tv[k][1].w};
+                uint32_t *dst = reinterpret_cast<uint32_t *>(ThT + (8 * seg) * LDT + j);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    dst[(2 * e) * (LDT / 2)] = (a[e] & 0xffffu) | (c[e] << 16);
+                    dst[(2 * e + 1) * (LDT / 2)] = (a[e] >> 16) | (c[e] & 0xffff0000u);
+                }
             }
         }
         // zero the k padding of the transposed theta chunk: columns [m16, m_pad)
@@ -221,36 +237,40 @@ __global__ __launch_bounds__(256) void fb_expand(Plan p, const uint16_t *__restr
         }
     }
     __syncthreads();
-
-    const int r0 = rb * kRB + wave * 16;
-    if (r0 >= p.R) return;
-    const int r = r0 + r16;
+    if (!wave_live) return;
 
     // ---- step 2: L^T[pos][row] = sum_j theta[j][pos] S[row][j] --------------------------------
     f32x4 acc[PC / 16];
 #pragma unroll
     for (int mt = 0; mt < PC / 16; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const uint16_t *srow = p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + 8 * kg;
-    const int KS = p.m_pad / 32;
-    uint4 sv = *reinterpret_cast<const uint4 *>(srow);
-    for (int ks = 0; ks < KS; ++ks) {
-        uint4 cur = sv;
-        if (ks + 1 < KS) sv = *reinterpret_cast<const uint4 *>(srow + 32 * (ks + 1));
-        const int jb = 32 * ks + 8 * kg;
-        if (jb + 8 > p.m) {     // scores beyond the compressed length do not exist
-            uint32_t w[4] = {cur.x, cur.y, cur.z, cur.w};
+    for (int ks0 = 0; ks0 < KS; ks0 += SB) {
+        uint4 cur[SB];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (jb + 2 * e >= p.m) w[e] = 0;
-                else if (jb + 2 * e + 1 >= p.m) w[e] &= 0xffffu;
+        for (int k = 0; k < SB; ++k) cur[k] = sfr[k];
+#pragma unroll
+        for (int k = 0; k < SB; ++k)
+            if (ks0 + SB + k < KS) sfr[k] = *reinterpret_cast<const uint4 *>(srow + 32 * (ks0 + SB + k));
+#pragma unroll
+        for (int k = 0; k < SB; ++k) {
+            const int ks = ks0 + k;
+            if (ks >= KS) break;
+            uint4 c4 = cur[k];
+            const int jb = 32 * ks + 8 * kg;
+            if (jb + 8 > p.m) {     // scores beyond the compressed length do not exist
+                uint32_t w[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (jb + 2 * e >= p.m) w[e] = 0;
+                    else if (jb + 2 * e + 1 >= p.m) w[e] &= 0xffffu;
+                }
+                c4 = make_uint4(w[0], w[1], w[2], w[3]);
             }
-            cur = make_uint4(w[0], w[1], w[2], w[3]);
-        }
-        const bf16x8 bfrag = as_bf16x8(cur);
+            const bf16x8 bfrag = as_bf16x8(c4);
 #pragma unroll
-        for (int mt = 0; mt < PC / 16; ++mt) {
-            const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(ThT + (16 * mt + r16) * LDT + 32 * ks + 8 * kg);
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[mt], 0, 0, 0);
+            for (int mt = 0; mt < PC / 16; ++mt) {
+                const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(ThT + (16 * mt + r16) * LDT + 32 * ks + 8 * kg);
+                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[mt], 0, 0, 0);
+            }
         }
     }
 
@@ -304,29 +324,30 @@ __global__ __launch_bounds__(256) void fb_expand(Plan p, const uint16_t *__restr
 }
 
 // ------------------------------------------------------------------------------------------
-// fc_output: Alg. 1 step 4 and the text part, streaming Vc / V_text once.
+// fc_output: Alg. 1 step 4 and the text part, streaming Vc / V_text once.  A workgroup owns
+// a run of value rows (part of one image block, or a chunk of the text cache) and produces an
+// un-normalised partial output relative to its OWN maximum, plus (max, sum): it needs no
+// statistic from any other workgroup, so its loads are all independent of each other.
+// Part record: [GT][D] floats of output, then [GT] maxima, then [GT] sums.
 // ------------------------------------------------------------------------------------------
 template <int GT>
 __global__ __launch_bounds__(256) void fc_output(Plan p, const uint16_t *__restrict__ Vc,
-                                                 const uint16_t *__restrict__ Vt,
-                                                 const uint16_t *__restrict__ mu,
-                                                 uint16_t *__restrict__ out,
-                                                 float *__restrict__ lse)
+                                                 const uint16_t *__restrict__ Vt)
 {
-    __shared__ float sM[16], sZ[16], sPv[16];
+    __shared__ float sM[GT], sS[GT];
     __shared__ float sAlpha[GT][kMaxNC];
     __shared__ float sW[GT][kMaxRowsPart];
     __shared__ float red[4][GT][D];
-    __shared__ int sLast;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rg = lane >> 4, cs = lane & 15;
 
     const int nvis = p.B * p.Hkv * p.I * p.JS;
-    int bh, i = 0, lo, hi, part;
+    int bh, i = 0, s = 0, lo, hi, part;
     const uint16_t *src;
     const bool vis = static_cast<int>(blockIdx.x) < nvis;
     if (vis) {
-        const int u = blockIdx.x / p.JS, s = blockIdx.x - u * p.JS;
+        const int u = blockIdx.x / p.JS;
+        s = blockIdx.x - u * p.JS;
         bh = u / p.I;
         i = u - bh * p.I;
         lo = s * p.rpp;
@@ -343,7 +364,7 @@ __global__ __launch_bounds__(256) void fc_output(Plan p, const uint16_t *__restr
         part = p.I * p.JS + xc;
     }
     const int b = bh / p.Hkv, h = bh - b * p.Hkv;
-    const int nrows = max(hi - lo, 0);
+    const int nrows = hi - lo;                 // >= 1 by construction of the grid
     const int niter = (nrows + 15) / 16;
 
     // start the HBM stream before the bookkeeping below
@@ -353,67 +374,76 @@ __global__ __launch_bounds__(256) void fc_output(Plan p, const uint16_t *__restr
     const int rowl = wave * 4 + rg;
 #pragma unroll
     for (int k = 0; k < PF; ++k) {
-        const int row = min(lo + rowl + 16 * k, max(hi - 1, lo));
+        const int row = min(lo + rowl + 16 * k, hi - 1);
         buf[k] = (k < niter) ? sp[static_cast<size_t>(row) * (D / 8)] : make_uint4(0, 0, 0, 0);
     }
 
-    // ---- joint softmax statistics of the G query heads of (b, h) --------------------------------
-    const int nent = p.I * p.NC;
-    for (int g = wave; g < p.G; g += 4) {
-        const size_t bg = static_cast<size_t>(b) * p.Hq + h * p.G + g;
-        float mx = -INFINITY;
-        for (int e = lane; e < nent; e += 64) {
-            const int i2 = e / p.NC, pc = e - i2 * p.NC;
-            const int r = (b * p.I + i2) * p.G + g;
-            mx = fmaxf(mx, p.stats[(static_cast<size_t>(h) * p.NC + pc) * p.R_pad + r].x);
-        }
-        const float2 ts = p.tstats[bg];
-        mx = wave_max(fmaxf(mx, ts.x));
-        float zv = 0.f;
-        for (int e = lane; e < nent; e += 64) {
-            const int i2 = e / p.NC, pc = e - i2 * p.NC;
-            const int r = (b * p.I + i2) * p.G + g;
-            const float2 st = p.stats[(static_cast<size_t>(h) * p.NC + pc) * p.R_pad + r];
-            zv += st.y * __expf(st.x - mx);
-        }
-        zv = wave_sum(zv);
-        const float zt = ts.y > 0.f ? ts.y * __expf(ts.x - mx) : 0.f;
-        if (lane == 0) { sM[g] = mx; sZ[g] = zv + zt; sPv[g] = zv / (zv + zt); }
-    }
-    __syncthreads();
-
-    // ---- weights of this workgroup's rows: merged W (vision) or text probabilities --------------
     if (vis) {
-        for (int idx = threadIdx.x; idx < p.G * p.NC; idx += 256) {
-            const int g = idx / p.NC, pc = idx - g * p.NC;
+        // tile statistics of this block's own rows: alpha = exp(tile max - block max)
+        for (int g = wave; g < p.G; g += 4) {
             const int r = (b * p.I + i) * p.G + g;
-            const float mxe = p.stats[(static_cast<size_t>(h) * p.NC + pc) * p.R_pad + r].x;
-            sAlpha[g][pc] = __expf(mxe - sM[g]) / sZ[g];
+            float2 st = make_float2(-INFINITY, 0.f);
+            if (lane < p.NC) st = p.stats[(static_cast<size_t>(h) * p.NC + lane) * p.R_pad + r];
+            const float mx = wave_max(st.x);
+            const float a = lane < p.NC ? __expf(st.x - mx) : 0.f;
+            const float sm = wave_sum(st.y * a);
+            if (lane < p.NC) sAlpha[g][lane] = a;
+            if (lane == 0) { sM[g] = mx; sS[g] = s == 0 ? sm : 0.f; }
+        }
+        // partial W of the chunks, fetched while the statistics settle
+        const int j = min(lo + static_cast<int>(threadIdx.x), hi - 1);
+        const size_t cstride = static_cast<size_t>(p.R_pad) * p.m_pad;
+        float wv[GT];
+#pragma unroll
+        for (int g = 0; g < GT; ++g) wv[g] = 0.f;
+        for (int pc0 = 0; pc0 < p.NC; pc0 += 8) {
+            float v[GT][8];
+#pragma unroll
+            for (int g = 0; g < GT; ++g) {
+                const int r = (b * p.I + i) * p.G + min(g, p.G - 1);
+                const float *wp = p.Wp + (static_cast<size_t>(h) * p.NC * p.R_pad + r) * p.m_pad + j;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[g][k] = wp[min(pc0 + k, p.NC - 1) * cstride];
+            }
+            if (pc0 == 0) __syncthreads();     // sAlpha ready
+#pragma unroll
+            for (int g = 0; g < GT; ++g)
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (pc0 + k < p.NC) wv[g] += sAlpha[min(g, p.G - 1)][pc0 + k] * v[g][k];
+        }
+        const bool on = lo + static_cast<int>(threadIdx.x) < hi;
+#pragma unroll
+        for (int g = 0; g < GT; ++g) sW[g][threadIdx.x] = (on && g < p.G) ? wv[g] : 0.f;
+    } else {
+        // text rows: probabilities relative to the chunk's own maximum
+        const int x = lo + threadIdx.x;
+        float sc[GT];
+#pragma unroll
+        for (int g = 0; g < GT; ++g) {
+            const size_t bg = static_cast<size_t>(b) * p.Hq + h * p.G + min(g, p.G - 1);
+            sc[g] = (x < hi) ? p.St[bg * p.ld_t + x] : -INFINITY;
+        }
+#pragma unroll
+        for (int g = 0; g < GT; ++g) {
+            const float wm = wave_max(sc[g]);
+            if (lane == 0) red[wave][g][0] = wm;
         }
         __syncthreads();
-        const int j = lo + threadIdx.x;
+        float e[GT];
 #pragma unroll
         for (int g = 0; g < GT; ++g) {
-            float w = 0.f;
-            if (g < p.G && j < hi) {
-                const int r = (b * p.I + i) * p.G + g;
-                const float *wp = p.Wp + (static_cast<size_t>(h) * p.NC * p.R_pad + r) * p.m_pad + j;
-                const size_t cstride = static_cast<size_t>(p.R_pad) * p.m_pad;
-                for (int pc = 0; pc < p.NC; ++pc) w += sAlpha[g][pc] * wp[pc * cstride];
-            }
-            sW[g][threadIdx.x] = w;
+            const float mx = fmaxf(fmaxf(red[0][g][0], red[1][g][0]), fmaxf(red[2][g][0], red[3][g][0]));
+            e[g] = (x < hi) ? __expf(sc[g] - mx) : 0.f;
+            sW[g][threadIdx.x] = g < p.G ? e[g] : 0.f;
+            const float ws = wave_sum(e[g]);
+            if (lane == 0) red[wave][g][1] = ws;
+            if (threadIdx.x == 0) sM[g] = mx;
         }
-    } else {
-        const int x = lo + threadIdx.x;
-#pragma unroll
-        for (int g = 0; g < GT; ++g) {
-            float w = 0.f;
-            if (g < p.G && x < hi) {
-                const size_t bg = static_cast<size_t>(b) * p.Hq + h * p.G + g;
-                w = __expf(p.St[bg * p.ld_t + x] - sM[g]) / sZ[g];
-            }
-            sW[g][threadIdx.x] = w;
-        }
+        __syncthreads();
+        if (threadIdx.x < GT)
+            sS[threadIdx.x] = red[0][threadIdx.x][1] + red[1][threadIdx.x][1] +
+                              red[2][threadIdx.x][1] + red[3][threadIdx.x][1];
     }
     __syncthreads();
 
@@ -449,6 +479,7 @@ __global__ __launch_bounds__(256) void fc_output(Plan p, const uint16_t *__restr
             }
         }
     }
+    __syncthreads();        // red[] was used as scratch by the text branch
 #pragma unroll
     for (int g = 0; g < GT; ++g)
 #pragma unroll
@@ -460,27 +491,57 @@ __global__ __launch_bounds__(256) void fc_output(Plan p, const uint16_t *__restr
         }
     __syncthreads();
     const int c = threadIdx.x & (D - 1), gh = threadIdx.x >> 7;
-    float *yp = p.Ypart + (static_cast<size_t>(bh) * p.nparts + part) * GT * D;
+    float *yp = p.Ypart + (static_cast<size_t>(bh) * p.nparts + part) * (GT * D + 2 * GT);
     for (int g = gh; g < p.G; g += 2)
         yp[g * D + c] = red[0][g][c] + red[1][g][c] + red[2][g][c] + red[3][g][c];
+    if (threadIdx.x < p.G) {
+        yp[GT * D + threadIdx.x] = sM[threadIdx.x];
+        yp[GT * D + GT + threadIdx.x] = sS[threadIdx.x];
+    }
+}
 
-    // ---- the last workgroup of (b, h) sums the partial outputs ----------------------------------------
-    __threadfence();
+// ------------------------------------------------------------------------------------------
+// fd_finalize: joint softmax over all parts of one (batch, KV head): rescale the partial
+// outputs to the global maximum, normalise, add (sum P_vis) mu, store out and lse.
+// ------------------------------------------------------------------------------------------
+template <int GT>
+__global__ __launch_bounds__(256) void fd_finalize(Plan p, const uint16_t *__restrict__ mu,
+                                                   uint16_t *__restrict__ out,
+                                                   float *__restrict__ lse)
+{
+    __shared__ float sScale[GT][kMaxParts + 4];
+    __shared__ float sPv[GT], sLse[GT];
+    const int bh = blockIdx.x, b = bh / p.Hkv, h = bh - b * p.Hkv;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int rec = GT * D + 2 * GT;
+    const float *yb = p.Ypart + static_cast<size_t>(bh) * p.nparts * rec;
+    const int nvp = p.I * p.JS;
+    for (int g = wave; g < p.G; g += 4) {
+        float mx = -INFINITY;
+        for (int pt = lane; pt < p.nparts; pt += 64) mx = fmaxf(mx, yb[static_cast<size_t>(pt) * rec + GT * D + g]);
+        mx = wave_max(mx);
+        float z = 0.f, zv = 0.f;
+        for (int pt = lane; pt < p.nparts; pt += 64) {
+            const float a = __expf(yb[static_cast<size_t>(pt) * rec + GT * D + g] - mx);
+            const float sm = yb[static_cast<size_t>(pt) * rec + GT * D + GT + g] * a;
+            z += sm;
+            if (pt < nvp) zv += sm;
+        }
+        z = wave_sum(z);
+        zv = wave_sum(zv);
+        for (int pt = lane; pt < p.nparts; pt += 64)
+            sScale[g][pt] = __expf(yb[static_cast<size_t>(pt) * rec + GT * D + g] - mx) / z;
+        if (lane == 0) { sPv[g] = zv / z; sLse[g] = mx + __logf(z); }
+    }
     __syncthreads();
-    if (threadIdx.x == 0)
-        sLast = __hip_atomic_fetch_add(p.cnt + bh, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == p.nparts - 1;
-    __syncthreads();
-    if (!sLast) return;
-    __threadfence();
-    const float *yb = p.Ypart + static_cast<size_t>(bh) * p.nparts * GT * D;
+    const int c = threadIdx.x & (D - 1), gh = threadIdx.x >> 7;
     for (int g = gh; g < p.G; g += 2) {
         float y = 0.f;
-        for (int pt = 0; pt < p.nparts; ++pt)
-            y += __builtin_nontemporal_load(yb + (static_cast<size_t>(pt) * GT + g) * D + c);
+        for (int pt = 0; pt < p.nparts; ++pt) y += sScale[g][pt] * yb[static_cast<size_t>(pt) * rec + g * D + c];
         y += sPv[g] * bf_lo(mu[static_cast<size_t>(h) * D + c]);
         const size_t bg = static_cast<size_t>(b) * p.Hq + h * p.G + g;
         out[bg * D + c] = f32_to_bf16_bits(y);
-        if (c == 0 && lse) lse[bg] = sM[g] + __logf(sZ[g]);
+        if (c == 0 && lse) lse[bg] = sLse[g];
     }
 }
 
@@ -540,9 +601,8 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.Wp = reinterpret_cast<float *>(take(static_cast<size_t>(p.Hkv) * p.NC * p.R_pad * p.m_pad * 4));
     p.stats = reinterpret_cast<float2 *>(take(static_cast<size_t>(p.Hkv) * p.NC * p.R_pad * 8));
     p.St = reinterpret_cast<float *>(take(static_cast<size_t>(p.B) * p.Hq * p.ld_t * 4));
-    p.tstats = reinterpret_cast<float2 *>(take(static_cast<size_t>(p.B) * p.Hq * 8));
-    p.Ypart = reinterpret_cast<float *>(take(static_cast<size_t>(p.B) * p.Hkv * (p.I * p.JS + nxc_max) * p.GT * D * 4));
-    p.cnt = reinterpret_cast<int *>(take(static_cast<size_t>(p.B) * p.Hkv * 4));
+    p.Ypart = reinterpret_cast<float *>(take(static_cast<size_t>(p.B) * p.Hkv * (p.I * p.JS + nxc_max) *
+                                             (p.GT * D + 2 * p.GT) * 4));
     p.bytes = off;
     return p;
 }
@@ -558,18 +618,18 @@ template <int PC> kvc_status launch_b(const Plan &p, const DecodeCall &c)
             return KVC_ERR_HIP;
         attr_set = true;
     }
-    fb_expand<PC><<<p.nvis_b + p.B * p.Hkv, 256, lds, c.stream>>>(
+    fb_expand<PC><<<p.nvis_b, 256, lds, c.stream>>>(
         p, static_cast<const uint16_t *>(c.theta), static_cast<const uint16_t *>(c.U));
     return KVC_OK;
 }
 
-template <int GT> void launch_c(const Plan &p, const DecodeCall &c)
+template <int GT> void launch_cd(const Plan &p, const DecodeCall &c)
 {
     const int grid = p.B * p.Hkv * (p.I * p.JS + p.NXC);
     fc_output<GT><<<grid, 256, 0, c.stream>>>(p, static_cast<const uint16_t *>(c.Vc),
-                                             static_cast<const uint16_t *>(c.Vt),
-                                             static_cast<const uint16_t *>(c.mu),
-                                             static_cast<uint16_t *>(c.out), c.lse);
+                                             static_cast<const uint16_t *>(c.Vt));
+    fd_finalize<GT><<<p.B * p.Hkv, 256, 0, c.stream>>>(p, static_cast<const uint16_t *>(c.mu),
+                                                      static_cast<uint16_t *>(c.out), c.lse);
 }
 
 }  // namespace
@@ -589,20 +649,23 @@ size_t fast_decode_ws_bytes(const kvc_shape &s, int32_t max_text)
 kvc_status fast_decode(const DecodeCall &c)
 {
     Plan p = make_plan(c.s, c.t, c.t_in, c.cap, c.scale, c.ws);
+    if (p.nparts > kMaxParts) return generic_decode(c);   // fd_finalize keeps one scale per part in LDS
     if (p.bytes > c.ws_bytes) return KVC_ERR_WORKSPACE;
     const int waves = (p.total_tiles + kTPW - 1) / kTPW;
-    fa_scores<<<(waves + 3) / 4 > 0 ? (waves + 3) / 4 : 1, 256, 0, c.stream>>>(
+    fa_scores<<<(waves + 3) / 4, 256, 0, c.stream>>>(
         p, static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc),
         static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt),
         static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new));
-    kvc_status st = p.PC == 64 ? launch_b<64>(p, c) : launch_b<32>(p, c);
-    if (st != KVC_OK) return st;
+    if (p.nvis_b > 0) {
+        kvc_status st = p.PC == 64 ? launch_b<64>(p, c) : launch_b<32>(p, c);
+        if (st != KVC_OK) return st;
+    }
     switch (p.GT) {
-    case 1: launch_c<1>(p, c); break;
-    case 2: launch_c<2>(p, c); break;
-    case 4: launch_c<4>(p, c); break;
-    case 8: launch_c<8>(p, c); break;
-    default: launch_c<16>(p, c); break;
+    case 1: launch_cd<1>(p, c); break;
+    case 2: launch_cd<2>(p, c); break;
+    case 4: launch_cd<4>(p, c); break;
+    case 8: launch_cd<8>(p, c); break;
+    default: launch_cd<16>(p, c); break;
     }
     return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
 }
