@@ -100,7 +100,12 @@ kvc_status kvc_memory_footprint(const kvc_shape *shape, int64_t c_prompt, int64_
  *             (d contiguous; strides multiples of 8 elements); rows outside the
  *             span [vis_start, vis_start + I n) are not touched -- text K/V stays
  *             where the backbone keeps it.
- *  Kc, Vc out: [B][H_kv][I][m][d] dense.
+ *  Kc out  : [B][H_kv][I][m][d] dense.
+ *  Vc out  : [B][H_kv][I] records of m*d elements (no padding).  Inside a record the m rows
+ *            are grouped in blocks of 8 and a block is stored channel-major, [d][w] with
+ *            w = 8 (w = m % 8 for a shorter last block): element (row j, channel c) sits at
+ *            (j/8)*8*d + c*w + j%8.  Eight consecutive rows of one channel are then 16
+ *            contiguous bytes, which is the matrix-core operand of the decode kernel.
  * Errors: NULL pointers, bad shape/dtype, vis_start < 0, misalignment. */
 kvc_status kvc_compress(const kvc_shape *shape, const kvc_params *params,
                         const void *K, const void *V,
@@ -117,7 +122,7 @@ kvc_status kvc_compress(const kvc_shape *shape, const kvc_params *params,
  * expanded with theta, probabilities folded through U^T), which never forms
  * K_hat / V_hat in memory; the softmax is joint over vision and text keys.
  *  q        in : [B][H_q][d]
- *  Kc, Vc   in : capsule written by kvc_compress
+ *  Kc, Vc   in : capsule written by kvc_compress (Vc in its blocked layout)
  *  K_text, V_text in/out: [B][H_kv][text_cap][d], first text_len rows valid; may
  *             be NULL when text_cap == 0
  *  k_new, v_new in (optional, both or neither): [B][H_kv][d]; if given they are

@@ -139,8 +139,8 @@ template <class T>
 __global__ void g_output(const float *__restrict__ W, const float *__restrict__ Stxt,
                          const float *__restrict__ stats, const T *__restrict__ Vc,
                          const T *__restrict__ Vt, const T *__restrict__ mu, T *__restrict__ out,
-                         float *__restrict__ lse, int Hq, int Hkv, int d, int Im, int t, int cap,
-                         int tstride)
+                         float *__restrict__ lse, int Hq, int Hkv, int d, int Im, int m, int t,
+                         int cap, int tstride)
 {
     __shared__ float red[kThreads];
     const size_t bg = blockIdx.x;
@@ -151,8 +151,10 @@ __global__ void g_output(const float *__restrict__ W, const float *__restrict__ 
     const float mx = stats[bg * 4 + 0], inv = 1.f / stats[bg * 4 + 1];
     float acc = 0.f;
     if (sl < slices) {
-        for (int r = sl; r < Im; r += slices)
-            acc += W[bg * Im + r] * to_f(Vc[(bh * Im + r) * d + c]);
+        for (int r = sl; r < Im; r += slices) {
+            const int i = r / m, j = r - i * m;
+            acc += W[bg * Im + r] * to_f(Vc[(bh * Im + static_cast<size_t>(i) * m) * d + vc_offset(j, c, m, d)]);
+        }
         for (int x = sl; x < t; x += slices)
             acc += __expf(Stxt[bg * tstride + x] - mx) * inv * to_f(Vt[(bh * cap + x) * d + c]);
     }
@@ -208,7 +210,7 @@ __global__ void g_vproject(const T *__restrict__ V, const T *__restrict__ U,
             if (jj < jn) acc[jj] += to_f(Ub[static_cast<size_t>(jj) * n + p]) * v;
     }
     for (int jj = 0; jj < jn; ++jj)
-        Vc[((bh * I + i) * m + j0 + jj) * d + c] = from_f<T>(acc[jj]);
+        Vc[(bh * I + i) * m * d + vc_offset(j0 + jj, c, m, d)] = from_f<T>(acc[jj]);
 }
 
 struct GenericWs {
@@ -266,7 +268,7 @@ template <class T> kvc_status decode_t(const DecodeCall &c)
     }
     g_output<T><<<B * Hq, kThreads, 0, c.stream>>>(
         w.W, w.Stxt, w.stats, static_cast<const T *>(c.Vc), static_cast<const T *>(c.Vt),
-        static_cast<const T *>(c.mu), static_cast<T *>(c.out), c.lse, Hq, Hkv, d, Im, t, c.cap,
+        static_cast<const T *>(c.mu), static_cast<T *>(c.out), c.lse, Hq, Hkv, d, Im, m, t, c.cap,
         tstride);
     return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
 }

@@ -30,6 +30,18 @@ template <class T> __device__ inline T from_f(float f);
 template <> __device__ inline float from_f<float>(float f) { return f; }
 template <> __device__ inline bf16_t from_f<bf16_t>(float f) { return bf16_t{f32_to_bf16_bits(f)}; }
 
+// ---- layout of the compressed values of one image block --------------------------------
+// The m rows are grouped in blocks of 8; a block holds [d][w] with w = 8 (w = m % 8 for a
+// last, shorter block), i.e. 8 consecutive rows of one channel are 16 contiguous bytes in
+// bf16: exactly the operand a 16x16x32 MFMA lane needs for out = W Vc.  No padding: the
+// record has m*d elements.  Offset of (row j, channel c):
+__host__ __device__ inline size_t vc_offset(int j, int c, int m, int d)
+{
+    const int jb = j >> 3;
+    const int w = (m - 8 * jb) < 8 ? (m - 8 * jb) : 8;
+    return static_cast<size_t>(jb) * 8 * d + static_cast<size_t>(c) * w + (j & 7);
+}
+
 // ---- wavefront (64 lanes) reductions --------------------------------------------
 __device__ inline float wave_sum(float x)
 {

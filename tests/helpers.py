@@ -34,3 +34,16 @@ def block_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     num = np.sqrt(((got - ref) ** 2).sum(axis=(-1, -2)))
     den = np.sqrt((ref ** 2).sum(axis=(-1, -2)))
     return float((num / np.maximum(den, 1e-30)).max())
+
+
+def unpack_vc(vc: torch.Tensor, m: int, d: int) -> np.ndarray:
+    """Compressed values as the library stores them ([..., m*d] records: rows in blocks of 8,
+    each block channel-major [d][w]) -> dense float64 [..., m, d].  Index shuffling only."""
+    flat = f64(vc).reshape(vc.shape[:-2] + (m * d,)) if vc.dim() >= 2 else f64(vc)
+    lead = flat.shape[:-1]
+    out = np.empty(lead + (m, d), dtype=np.float64)
+    for jb in range((m + 7) // 8):
+        w = min(8, m - 8 * jb)
+        blk = flat[..., jb * 8 * d: jb * 8 * d + d * w].reshape(lead + (d, w))
+        out[..., 8 * jb: 8 * jb + w, :] = np.swapaxes(blk, -1, -2)
+    return out

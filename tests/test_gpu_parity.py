@@ -14,7 +14,7 @@ from oracle import kvc_oracle as orc
 from paper_2605_16439_amd import kvcapsule as kv
 from paper_2605_16439_amd import synth
 
-from helpers import block_rel_err, f64, row_rel_err, store_code, tol
+from helpers import block_rel_err, f64, row_rel_err, store_code, tol, unpack_vc
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
@@ -78,7 +78,7 @@ def check_layer(w, m, layer=0, pre=0, post=0, generic=False, steps=(0,), bs=None
     L.compress()
     Kc_ref, Vc_ref = orc.compress(f64(L.K)[sel], f64(L.V)[sel], idx, U, mu, n, I, pre,
                                   store_code(w))
-    gKc, gVc = f64(L.gKc)[sel], f64(L.gVc)[sel]
+    gKc, gVc = f64(L.gKc)[sel], unpack_vc(L.gVc, m, w.head_dim)[sel]
     assert np.array_equal(gKc, Kc_ref), "compressed keys must be a bit-exact row selection"
     if I > 0:
         e = block_rel_err(gVc, Vc_ref)
@@ -169,7 +169,8 @@ def test_text_only_and_vision_only():
     kv.kvc_reconstruct_attend_decode(L.shape, L.params, q.to(DEV), L.gKc, L.gVc, None, None, 0, 0,
                                      None, None, 0.0, L.out, L.lse, L.ws)
     torch.cuda.synchronize()
-    ref, _ = orc.reconstruct_attend_decode(f64(q), f64(L.gKc), f64(L.gVc), f64(L.p["theta"]),
+    ref, _ = orc.reconstruct_attend_decode(f64(q), f64(L.gKc), unpack_vc(L.gVc, 16, w.head_dim),
+                                           f64(L.p["theta"]),
                                            f64(L.p["U"]), f64(L.p["mu"]), w.n_img_tokens, None,
                                            None, 0)
     assert row_rel_err(f64(L.out), ref) <= tol(w)
@@ -190,7 +191,7 @@ def test_strided_prefill_kv():
     Kc_ref, Vc_ref = orc.compress(f64(L.K), f64(L.V), L.p["key_idx"].numpy(), f64(L.p["U"]),
                                   f64(L.p["mu"]), w.n_img_tokens, w.n_images, 4, store_code(w))
     assert np.array_equal(f64(L.gKc), Kc_ref)
-    assert block_rel_err(f64(L.gVc), Vc_ref) <= tol(w)
+    assert block_rel_err(unpack_vc(L.gVc, m, w.head_dim), Vc_ref) <= tol(w)
 
 
 def test_config1_tiny_fp32_full():
