@@ -43,10 +43,10 @@ constexpr int kRB = 64;         // query rows per fb_probs workgroup (4 waves x 
 constexpr int kPC = 64;         // positions per fb_probs workgroup (one softmax tile)
 constexpr int kTPW = 2;         // 16-row key tiles per wavefront in fa_scores
 constexpr int kJC = 64;         // capsule rows per fc_fused workgroup (one 16-row tile per wave)
-constexpr int kXC = 64;         // text rows per fc_fused text workgroup
+constexpr int kXC = 128;        // text rows per fc_fused text workgroup
 constexpr int kMaxN = 1024;     // fc_fused stages 16 rows of P (n bf16 each) in LDS
 constexpr int kMaxParts = 256;  // fd_finalize keeps one scale per part in LDS
-constexpr int kSWLD = kJC + 8;  // padded row (bf16) of the W tile / text probabilities in LDS
+constexpr int kSWLD = kXC + 8;  // padded row (bf16) of the W tile / text probabilities in LDS
 constexpr int kLDV = kXC + 8;   // padded row (bf16) of the transposed text values in LDS
 constexpr size_t kLdsBudget = 150 * 1024;
 
@@ -59,6 +59,7 @@ struct Plan {
     int nvis_b, b_stride, nvis_c, c_stride;
     float scale;
     int dbg;
+    unsigned long long *dbgbuf;
     uint16_t *S;
     uint16_t *P;
     float2 *stats;
@@ -66,6 +67,13 @@ struct Plan {
     float *Ypart;
     size_t bytes;
 };
+
+// debug timestamps: kernel id, slot
+#define TS(KID, K)                                                                        \
+    do {                                                                                  \
+        if (p.dbgbuf && threadIdx.x == 0)                                                 \
+            p.dbgbuf[((KID) * 1024 + (blockIdx.x < 1024 ? blockIdx.x : 1023)) * 8 + (K)] = wall_clock64(); \
+    } while (0)
 
 __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 __device__ inline float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -85,6 +93,7 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
+    TS(0, 0);
     const int tile0 = (blockIdx.x * 4 + wave) * kTPW;
     uint4 kf[kTPW][4], qf[kTPW][4];
     bool live[kTPW];
@@ -131,6 +140,7 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) qf[tt][ks] = qp[4 * ks];
     }
+    TS(0, 1);
 #pragma unroll
     for (int tt = 0; tt < kTPW; ++tt) {
         if (!live[tt]) continue;
@@ -154,7 +164,10 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
                 const uint32_t hi = (j + e + 1 < p.m) ? f32_to_bf16_bits(acc[e + 1] * p.scale) : 0u;
                 w[e >> 1] = lo | (hi << 16);
             }
-            *reinterpret_cast<uint2 *>(p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + j) = make_uint2(w[0], w[1]);
+            uint16_t *srow = p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + j;
+            *reinterpret_cast<uint2 *>(srow) = make_uint2(w[0], w[1]);
+            // the consumer reads whole 32-wide k-steps: keep the padding [m16, m_pad) at zero
+            if (jt == p.tiles_per_unit - 1 && p.m_pad > p.m16) *reinterpret_cast<uint2 *>(srow + 16) = make_uint2(0u, 0u);
         } else {
             const int tx = tile - p.vis_tiles;
             const int bh = tx / p.txt_tiles_per_bh, xt = tx - bh * p.txt_tiles_per_bh;
@@ -163,6 +176,7 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
             *reinterpret_cast<float4 *>(p.St + (static_cast<size_t>(b) * p.Hq + h * p.G + g) * p.ld_t + xt * 16 + 4 * kg) = o;
         }
     }
+    TS(0, 4);
 }
 
 
@@ -186,6 +200,7 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
     if (hc >= p.Hkv * p.NC) return;
     const int h = hc / p.NC, pc = hc - h * p.NC;
 
+    TS(1, 0);
     const int LDT = p.m_pad + 8;
     uint16_t *ThT = lds;                 // [PC][LDT]   theta chunk, transposed: ThT[pos][j]
 
@@ -195,7 +210,7 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
     const int r = r0 + r16;
     const uint16_t *srow = p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + 8 * kg;
     const int KS = p.m_pad / 32;
-    constexpr int SB = 8;
+    constexpr int SB = 20;                       // m <= 640: every fragment in one batch
     uint4 sfr[SB];
 #pragma unroll
     for (int k = 0; k < SB; ++k)
@@ -208,7 +223,7 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
     const int jp = (lane & 15) + 16 * (wave >> 1);         // row pair within a pass of 64 rows
     {
         const uint16_t *th = theta + static_cast<size_t>(h) * p.m * p.n + pc * PC + 8 * seg;
-        constexpr int FB = 4;                    // passes per batch: 8 loads of 16 B in flight
+        constexpr int FB = 10;                   // passes per batch: m <= 640 is one batch
         for (int j0 = 2 * jp; j0 < p.m16; j0 += 64 * FB) {
             uint4 tv[FB][2];
 #pragma unroll
@@ -242,6 +257,7 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
         }
     }
     __syncthreads();
+    TS(1, 2);
     if (!wave_live) return;
 
     f32x4 acc[PC / 16];
@@ -258,18 +274,8 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
         for (int k = 0; k < SB; ++k) {
             const int ks = ks0 + k;
             if (ks < KS) {
-                uint4 c4 = cur[k];
-                const int jb = 32 * ks + 8 * kg;
-                if (jb + 8 > p.m) {     // scores beyond the compressed length do not exist
-                    uint32_t w[4] = {c4.x, c4.y, c4.z, c4.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (jb + 2 * e >= p.m) w[e] = 0;
-                        else if (jb + 2 * e + 1 >= p.m) w[e] &= 0xffffu;
-                    }
-                    c4 = make_uint4(w[0], w[1], w[2], w[3]);
-                }
-                const bf16x8 bfrag = as_bf16x8(c4);
+                // scores beyond the compressed length are zeros written by fa_scores
+                const bf16x8 bfrag = as_bf16x8(cur[k]);
 #pragma unroll
                 for (int mt = 0; mt < PC / 16; ++mt) {
                     const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(ThT + (16 * mt + r16) * LDT + 32 * ks + 8 * kg);
@@ -279,6 +285,7 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
         }
     }
 
+    TS(1, 3);
     // ---- tile-local softmax numerators of row r over the 64 positions ------------------------------
     float mx = -INFINITY;
 #pragma unroll
@@ -299,6 +306,7 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
     sum += __shfl_xor(sum, 16, 64);
     sum += __shfl_xor(sum, 32, 64);
     if (kg == 0 && r < p.R) p.stats[(static_cast<size_t>(h) * p.R_pad + r) * p.NC + pc] = make_float2(mx, sum);
+    TS(1, 4);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -324,6 +332,7 @@ __global__ __launch_bounds__(256) void fc_fused(Plan p, const uint16_t *__restri
 
     if (static_cast<int>(blockIdx.x) >= p.nvis_c) {
         // ---------------- text rows: one chunk of kXC rows of one (batch, KV head) ----------------
+        TS(2, 0);
         const int id = blockIdx.x - p.nvis_c;
         const int bh = id / p.NXC, xc = id - bh * p.NXC;
         const int b = bh / p.Hkv, h = bh - b * p.Hkv;
@@ -332,11 +341,11 @@ __global__ __launch_bounds__(256) void fc_fused(Plan p, const uint16_t *__restri
         {
             const int rowl = wave * 4 + kg, cs = r16;
             const uint4 *sp = reinterpret_cast<const uint4 *>(Vt + static_cast<size_t>(bh) * p.cap * D) + cs;
-            uint4 vb[4];
+            uint4 vb[kXC / 16];
 #pragma unroll
-            for (int it = 0; it < 4; ++it) vb[it] = sp[static_cast<size_t>(min(lo + rowl + 16 * it, hi - 1)) * (D / 8)];
+            for (int it = 0; it < kXC / 16; ++it) vb[it] = sp[static_cast<size_t>(min(lo + rowl + 16 * it, hi - 1)) * (D / 8)];
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
+            for (int it = 0; it < kXC / 16; ++it) {
                 const uint32_t w4[4] = {vb[it].x, vb[it].y, vb[it].z, vb[it].w};
                 uint16_t *dst = dyn + (8 * cs) * kLDV + rowl + 16 * it;
 #pragma unroll
@@ -346,25 +355,26 @@ __global__ __launch_bounds__(256) void fc_fused(Plan p, const uint16_t *__restri
                 }
             }
         }
-        // probabilities relative to the chunk's own maximum: 4 lanes per row
-        const int xl = threadIdx.x >> 2, x = lo + xl, gsub = threadIdx.x & 3;
-        float sc[(G + 3) / 4];
+        // probabilities relative to the chunk's own maximum: LPR lanes per row
+        constexpr int LPR = 256 / kXC, NG = (G + LPR - 1) / LPR;
+        const int xl = threadIdx.x / LPR, x = lo + xl, gsub = threadIdx.x % LPR;
+        float sc[NG];
 #pragma unroll
-        for (int k = 0; k < (G + 3) / 4; ++k) {
-            const int g = gsub + 4 * k;
+        for (int k = 0; k < NG; ++k) {
+            const int g = gsub + LPR * k;
             sc[k] = (g < G && x < hi) ? p.St[(static_cast<size_t>(b) * p.Hq + h * G + g) * p.ld_t + x] : -INFINITY;
         }
 #pragma unroll
-        for (int k = 0; k < (G + 3) / 4; ++k) {
-            float mx = sc[k];                       // max over rows = lanes with equal (lane & 3)
+        for (int k = 0; k < NG; ++k) {
+            float mx = sc[k];                       // max over rows = lanes with equal (lane % LPR)
 #pragma unroll
-            for (int o = 4; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-            if (lane < 4 && lane + 4 * k < G) sRed[wave][lane + 4 * k][0] = mx;
+            for (int o = LPR; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+            if (lane < LPR && lane + LPR * k < G) sRed[wave][lane + LPR * k][0] = mx;
         }
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < (G + 3) / 4; ++k) {
-            const int g = gsub + 4 * k;
+        for (int k = 0; k < NG; ++k) {
+            const int g = gsub + LPR * k;
             float e = 0.f, mx = 0.f;
             if (g < G) {
                 mx = fmaxf(fmaxf(sRed[0][g][0], sRed[1][g][0]), fmaxf(sRed[2][g][0], sRed[3][g][0]));
@@ -374,9 +384,9 @@ __global__ __launch_bounds__(256) void fc_fused(Plan p, const uint16_t *__restri
             }
             float sm = e;
 #pragma unroll
-            for (int o = 4; o < 64; o <<= 1) sm += __shfl_xor(sm, o, 64);
-            if (lane < 4 && g < G) sRed[wave][g][1] = sm;
-            if (threadIdx.x < 4 && g < G) sMx[g] = mx;
+            for (int o = LPR; o < 64; o <<= 1) sm += __shfl_xor(sm, o, 64);
+            if (lane < LPR && g < G) sRed[wave][g][1] = sm;
+            if (threadIdx.x < LPR && g < G) sMx[g] = mx;
         }
         for (int idx = threadIdx.x; idx < (16 - G) * kXC; idx += 256) sWb[G + idx / kXC][idx % kXC] = 0;
         __syncthreads();
@@ -399,12 +409,14 @@ __global__ __launch_bounds__(256) void fc_fused(Plan p, const uint16_t *__restri
             yp[G * D + G + threadIdx.x] = sRed[0][threadIdx.x][1] + sRed[1][threadIdx.x][1] +
                                           sRed[2][threadIdx.x][1] + sRed[3][threadIdx.x][1];
         }
+        TS(2, 4);
         return;
     }
 
     // ---------------- vision: (row group ug, KV head h, slice s of the capsule rows) ----------------
     // ug is the slow index with a stride that is a multiple of 8: workgroups that stream the same
     // rows of U[h] sit on one XCD and share its L2
+    TS(2, 0);
     const int ug = blockIdx.x / p.c_stride;
     const int hs = blockIdx.x - ug * p.c_stride;
     if (hs >= p.Hkv * p.JS) return;
@@ -447,6 +459,8 @@ __global__ __launch_bounds__(256) void fc_fused(Plan p, const uint16_t *__restri
     // batches of UBATCH; the first batch is requested here.
     constexpr int UBATCH = UP < 4 ? UP : 4;
     const int jb0 = lo / 8;
+    // a shorter last block ([D][w], w = m % 8) exists only in the last slice: uniform branch
+    const bool has_tail = (p.m & 7) != 0 && hi == p.m;
     auto load_values = [&](int un0, uint4 (&dst)[UBATCH][2][2]) {
 #pragma unroll
         for (int a = 0; a < UBATCH; ++a) {
@@ -458,24 +472,32 @@ __global__ __launch_bounds__(256) void fc_fused(Plan p, const uint16_t *__restri
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) {
                     const int jb = jb0 + 4 * ks + kg, c = 16 * (2 * wave + ct2) + r16;
-                    uint4 v = make_uint4(0, 0, 0, 0);
-                    if (8 * jb + 8 <= p.m) {
-                        v = *reinterpret_cast<const uint4 *>(vbase + static_cast<size_t>(jb) * 8 * D + c * 8);
-                    } else if (8 * jb < p.m) {          // shorter last block: [D][w], w = m - 8 jb
-                        const int w = p.m - 8 * jb;
-                        const uint16_t *tp = vbase + static_cast<size_t>(jb) * 8 * D + c * w;
-                        uint32_t e[8];
-#pragma unroll
-                        for (int q2 = 0; q2 < 8; ++q2) e[q2] = q2 < w ? tp[q2] : 0u;
-                        v = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
-                    }
-                    dst[a][ct2][ks] = v;
+                    dst[a][ct2][ks] = (8 * jb + 8 <= p.m)
+                                          ? *reinterpret_cast<const uint4 *>(vbase + static_cast<size_t>(jb) * 8 * D + c * 8)
+                                          : make_uint4(0, 0, 0, 0);
                 }
+            if (has_tail) {
+#pragma unroll
+                for (int ct2 = 0; ct2 < 2; ++ct2)
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        const int jb = jb0 + 4 * ks + kg, c = 16 * (2 * wave + ct2) + r16;
+                        if (8 * jb < p.m && 8 * jb + 8 > p.m) {
+                            const int w = p.m - 8 * jb;
+                            const uint16_t *tp = vbase + static_cast<size_t>(jb) * 8 * D + c * w;
+                            uint32_t e[8];
+#pragma unroll
+                            for (int q2 = 0; q2 < 8; ++q2) e[q2] = q2 < w ? tp[q2] : 0u;
+                            dst[a][ct2][ks] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+                        }
+                    }
+            }
         }
     };
     uint4 vfr[UBATCH][2][2];
     load_values(0, vfr);
 
+    TS(2, 1);
     // ---- block statistics: alpha[row][tile] = exp(tile max - block max) ----------------------------------
     if (wave == 0 && kg == 0) {
         float mx = -INFINITY;
@@ -499,6 +521,7 @@ __global__ __launch_bounds__(256) void fc_fused(Plan p, const uint16_t *__restri
             if (16 * k + sub < n / 8) dst[16 * k] = pfr[k];
     }
     __syncthreads();
+    TS(2, 2);
 
     // ---- step 3: W^T[j][row] = sum_tiles alpha[row][tile] sum_pos U[j][pos] P[row][pos] ------------------
     {
@@ -532,6 +555,7 @@ __global__ __launch_bounds__(256) void fc_fused(Plan p, const uint16_t *__restri
         *reinterpret_cast<uint2 *>(&sWb[r16][jl]) = make_uint2(w0 | (w1 << 16), w2 | (w3 << 16));
     }
     __syncthreads();
+    TS(2, 3);
 
     // ---- step 4: out_part^T[c][row] = sum_j Vc^T[c][j] W[row][j], per image block of the group -----------
     const bf16x8 wb0 = *reinterpret_cast<const bf16x8 *>(&sWb[r16][8 * kg]);
@@ -568,6 +592,7 @@ __global__ __launch_bounds__(256) void fc_fused(Plan p, const uint16_t *__restri
             }
         }
     }
+    TS(2, 4);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -580,6 +605,7 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
 {
     __shared__ float sSc[kMaxParts];
     __shared__ float sRed[2][3];
+    TS(3, 0);
     const int bg = blockIdx.x, b = bg / p.Hq, gq = bg - b * p.Hq;
     const int h = gq / p.G, g = gq - h * p.G;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -589,7 +615,7 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
     const int c = threadIdx.x;
     const float *yc = yb + g * D + c;
     // first batch of partial outputs in flight together with the statistics
-    constexpr int PB = 32;
+    constexpr int PB = 64;
     float v[PB];
 #pragma unroll
     for (int k = 0; k < PB; ++k) v[k] = yc[static_cast<size_t>(min(k, p.nparts - 1)) * rec];
@@ -640,6 +666,7 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
     y += (zv / z) * bf_lo(mu[static_cast<size_t>(h) * D + c]);
     out[static_cast<size_t>(bg) * D + c] = f32_to_bf16_bits(y);
     if (c == 0 && lse) lse[bg] = mx + __logf(z);
+    TS(3, 4);
 }
 
 size_t lds_b(int m_pad) { return static_cast<size_t>(kPC) * (m_pad + 8) * sizeof(uint16_t); }
@@ -668,6 +695,7 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.B = s.batch; p.Hq = s.n_q_heads; p.Hkv = s.n_kv_heads; p.G = p.Hq / p.Hkv;
     p.n = s.n_img_tokens; p.I = s.n_images; p.m = s.m;
     p.t = t; p.t_in = t_in; p.cap = cap; p.scale = scale;
+    { const char *e = getenv("KVC_DBG"); p.dbg = e ? atoi(e) : 0; }
     p.R = p.B * p.I * p.G;
     p.R_pad = static_cast<int>(align_up(p.R > 0 ? p.R : 1, kRB));
     p.NRB = p.I > 0 ? p.R_pad / kRB : 0;
@@ -703,6 +731,7 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.St = reinterpret_cast<float *>(take(static_cast<size_t>(p.B) * p.Hq * p.ld_t * 4));
     p.Ypart = reinterpret_cast<float *>(take(static_cast<size_t>(p.B) * p.Hkv * (p.I * p.JS + nxc_max) * p.rec * 4));
     p.bytes = off;
+    p.dbgbuf = nullptr;
     return p;
 }
 
@@ -735,6 +764,9 @@ kvc_status fast_decode(const DecodeCall &c)
     Plan p = make_plan(c.s, c.t, c.t_in, c.cap, c.scale, c.ws);
     if (p.nparts > kMaxParts) return generic_decode(c);
     if (p.bytes > c.ws_bytes) return KVC_ERR_WORKSPACE;
+    p.dbgbuf = (p.dbg & 256) && c.ws_bytes >= p.bytes + (1 << 20)
+                   ? reinterpret_cast<unsigned long long *>(static_cast<char *>(c.ws) + ((c.ws_bytes - (1 << 20)) & ~size_t(255)))
+                   : nullptr;
     const int waves = (p.total_tiles + kTPW - 1) / kTPW;
     fa_scores<<<(waves + 3) / 4, 256, 0, c.stream>>>(
         p, static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc),
