@@ -1,7 +1,191 @@
-// Matrix-core compress path (bf16) -- placeholder until the kernels land.
+// Matrix-core compress path of KVCapsule for gfx950: bf16 storage, head_dim 128.
+//
+// Values (Sec. 3.1, "Sequence-Level Low-Rank Compression for Values"):
+//     Vc[b,h,i] = U[h] (V[b,h,block i] - 1 mu[h]^T) = U[h] V - (U[h] 1) mu[h]^T
+// is one GEMM per image block, [m x n] . [n x d].  A workgroup owns 64 rows j of one block:
+// each of its 4 wavefronts keeps 16 rows x 128 channels of accumulators, streams its 16 rows
+// of U straight from memory as the A operand (k = position p is contiguous in U), and shares
+// the V tile with the other waves through LDS, where it is transposed on the way in (V is
+// stored position-major, the B operand needs 8 consecutive positions of one channel per
+// lane).  The row sums U 1 come out of the same pass as one extra MFMA against a tile of
+// ones, already in the accumulator layout, so the centring costs no extra read of V.
+// The result is rounded once to bf16 and stored in the blocked channel-major layout that the
+// decode kernel reads as MFMA operands.
+//
+// Keys (Sec. 3.1, "Selective Retention and Reconstruction for Keys"): trailing workgroups of
+// the same launch copy the rows selected by the mask, 16 bytes per lane.
 #include "kvc_internal.h"
+
 namespace kvc {
-bool fast_compress_supported(const kvc_shape &) { return false; }
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int D = 128;
+constexpr int kJT = 64;        // rows j per workgroup
+constexpr int kKT = 64;        // positions per LDS tile
+constexpr int kLD = kKT + 8;   // padded row of the transposed V tile (bf16 elements)
+
+struct CPlan {
+    int B, Hkv, n, I, m, vis0;
+    int JT, nproj, ngather;
+    int64_t sb, sh, ss;
+};
+
+__device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// element (channel c, position p of the tile) of the transposed tile; 16-byte chunks of a row
+// are XOR-swizzled with the channel group so the transposing stores spread over the banks
+__device__ inline int sv_index(int c, int p) { return c * kLD + ((((p >> 3) ^ (c >> 3)) & 7) << 3) + (p & 7); }
+
+__global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__restrict__ K,
+                                                   const uint16_t *__restrict__ V,
+                                                   const int32_t *__restrict__ idx,
+                                                   const uint16_t *__restrict__ U,
+                                                   const uint16_t *__restrict__ mu,
+                                                   uint16_t *__restrict__ Kc,
+                                                   uint16_t *__restrict__ Vc)
+{
+    __shared__ __align__(16) uint16_t sVt[2][D * kLD];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r16 = lane & 15, kg = lane >> 4;
+
+    if (static_cast<int>(blockIdx.x) >= p.nproj) {
+        // ---------------- keys: Kc[u][j][:] = K[b,h, vis0 + i n + M[j], :] ----------------
+        const int id = blockIdx.x - p.nproj;
+        const int u = id / p.JT, jt = id - u * p.JT;
+        const int bh = u / p.I, i = u - bh * p.I;
+        const int b = bh / p.Hkv, h = bh - b * p.Hkv;
+        const uint16_t *src = K + b * p.sb + h * p.sh + (static_cast<int64_t>(p.vis0) + static_cast<int64_t>(i) * p.n) * p.ss;
+        // 16 lanes per row, 16 rows per pass, 4 passes
+        const int rl = threadIdx.x >> 4, cs = threadIdx.x & 15;
+        uint4 v[4];
+        int jj[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            jj[q] = jt * kJT + 16 * q + rl;
+            const int j = min(jj[q], p.m - 1);
+            v[q] = *(reinterpret_cast<const uint4 *>(src + static_cast<int64_t>(idx[j]) * p.ss) + cs);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (jj[q] < p.m) *(reinterpret_cast<uint4 *>(Kc + (static_cast<size_t>(u) * p.m + jj[q]) * D) + cs) = v[q];
+        return;
+    }
+
+    // ---------------- values: 64 rows j of one image block ----------------
+    const int u = blockIdx.x / p.JT, jt = blockIdx.x - u * p.JT;
+    const int bh = u / p.I, i = u - bh * p.I;
+    const int b = bh / p.Hkv, h = bh - b * p.Hkv;
+    const int j0 = jt * kJT + wave * 16;
+    const bool wave_live = j0 < p.m;
+    const uint16_t *urow = U + (static_cast<size_t>(h) * p.m + min(j0 + r16, p.m - 1)) * p.n + 8 * kg;
+    const uint16_t *vsrc = V + b * p.sb + h * p.sh + (static_cast<int64_t>(p.vis0) + static_cast<int64_t>(i) * p.n) * p.ss;
+    // V tile loads: item = (pair of positions, 8 channels); 512 items, two per thread
+    const int pair0 = threadIdx.x >> 4, cs = threadIdx.x & 15;      // second item: pair0 + 16
+
+    f32x4 acc[8], accs = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint32_t one2 = 0x3f803f80u;
+    const bf16x8 ones = as_bf16x8(make_uint4(one2, one2, one2, one2));
+
+    uint4 va[2][2], ua[2];
+    auto load_tile = [&](int kt) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int pp = kt * kKT + 2 * (pair0 + 16 * q) + e;
+                va[q][e] = *(reinterpret_cast<const uint4 *>(vsrc + static_cast<int64_t>(pp) * p.ss) + cs);
+            }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+            ua[ks] = wave_live ? *reinterpret_cast<const uint4 *>(urow + kt * kKT + 32 * ks) : make_uint4(0, 0, 0, 0);
+    };
+    load_tile(0);
+    const int NK = p.n / kKT;
+    for (int kt = 0; kt < NK; ++kt) {
+        uint16_t *buf = sVt[kt & 1];
+        // transposed store: positions (2 pair, 2 pair + 1) of channel c share one 32-bit word
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int pl = 2 * (pair0 + 16 * q);
+            const uint32_t a[4] = {va[q][0].x, va[q][0].y, va[q][0].z, va[q][0].w};
+            const uint32_t c2[4] = {va[q][1].x, va[q][1].y, va[q][1].z, va[q][1].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                *reinterpret_cast<uint32_t *>(buf + sv_index(8 * cs + 2 * e, pl)) = (a[e] & 0xffffu) | (c2[e] << 16);
+                *reinterpret_cast<uint32_t *>(buf + sv_index(8 * cs + 2 * e + 1, pl)) = (a[e] >> 16) | (c2[e] & 0xffff0000u);
+            }
+        }
+        const uint4 u0 = ua[0], u1 = ua[1];
+        __syncthreads();
+        if (kt + 1 < NK) load_tile(kt + 1);
+        if (wave_live) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const bf16x8 afrag = as_bf16x8(ks == 0 ? u0 : u1);
+#pragma unroll
+                for (int nt = 0; nt < 8; ++nt) {
+                    const int c = 16 * nt + r16;
+                    const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(buf + sv_index(c, 32 * ks + 8 * kg));
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[nt], 0, 0, 0);
+                }
+                accs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, ones, accs, 0, 0, 0);
+            }
+        }
+    }
+    if (!wave_live) return;
+
+    // ---- epilogue: centre, round once, store in the blocked layout -----------------------------------
+    // lane holds rows j = j0 + 4 kg + e (e = 0..3) of channel c = 16 nt + r16; accs[e] = sum_p U[j][p]
+    const int jb = (j0 + 4 * kg) >> 3, jr = (j0 + 4 * kg) & 7;
+    const int w = min(8, p.m - 8 * jb);                     // width of the block these rows sit in
+    uint16_t *vout = Vc + static_cast<size_t>(u) * p.m * D + static_cast<size_t>(jb) * 8 * D;
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) {
+        const int c = 16 * nt + r16;
+        const float muc = __uint_as_float(static_cast<uint32_t>(mu[static_cast<size_t>(h) * D + c]) << 16);
+        uint32_t o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_bits(acc[nt][e] - accs[e] * muc);
+        if (w == 8) {
+            *reinterpret_cast<uint2 *>(vout + c * 8 + jr) = make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
+        } else if (w > 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (jr + e < w) vout[c * w + jr + e] = static_cast<uint16_t>(o[e]);
+        }
+    }
+}
+
+}  // namespace
+
+bool fast_compress_supported(const kvc_shape &s)
+{
+    return s.dtype == KVC_BF16 && s.head_dim == D && s.n_img_tokens % kKT == 0;
+}
+
 size_t fast_compress_ws_bytes(const kvc_shape &) { return 0; }
-kvc_status fast_compress(const CompressCall &) { return KVC_ERR_UNSUPPORTED; }
+
+kvc_status fast_compress(const CompressCall &c)
+{
+    const kvc_shape &s = c.s;
+    if (s.n_images == 0) return KVC_OK;
+    CPlan p;
+    p.B = s.batch; p.Hkv = s.n_kv_heads; p.n = s.n_img_tokens; p.I = s.n_images; p.m = s.m;
+    p.vis0 = c.vis_start;
+    p.JT = (s.m + kJT - 1) / kJT;
+    p.nproj = p.B * p.Hkv * p.I * p.JT;
+    p.ngather = p.nproj;
+    p.sb = c.stride_b; p.sh = c.stride_h; p.ss = c.stride_s;
+    fk_compress<<<p.nproj + p.ngather, 256, 0, c.stream>>>(
+        p, static_cast<const uint16_t *>(c.K), static_cast<const uint16_t *>(c.V), c.key_idx,
+        static_cast<const uint16_t *>(c.U), static_cast<const uint16_t *>(c.mu),
+        static_cast<uint16_t *>(c.Kc), static_cast<uint16_t *>(c.Vc));
+    return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
+}
+
 }  // namespace kvc
