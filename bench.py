@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--generic", action="store_true", help="force the scalar kernels")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
+                    help="also run 3 plain device copies of this many MiB (counter calibration "
+                         "for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -157,6 +160,13 @@ def main():
             pairs.append((e0, e1))
     torch.cuda.synchronize()
     call_us = sum(a.elapsed_time(b) for a, b in pairs) * 1e3 / len(pairs)
+
+    if args.copy_probe:
+        src = torch.empty(args.copy_probe << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     t_avg = w.text_len + (K + 1) / 2.0      # rows attended, new token included
     abytes = algorithmic_bytes(w, m, t_avg)
