@@ -4,28 +4,35 @@
 // (score-space order), with the softmax taken jointly over vision and text keys
 // (Sec. 3.2) by carrying (max, sum) statistics per part and merging them at the end:
 //
-//   fa_scores   streams the compressed keys Kc and the text keys from HBM once:
-//               S = sigma q Kc^T (Alg. 1 step 1) and the text logits, one 16x16x32 MFMA
-//               tile per 16 key rows; also stores the new token's k, v in the text cache.
+//   fa_scores   vision workgroups stream the compressed keys Kc from HBM once:
+//               S = sigma q Kc^T (Alg. 1 step 1), one 16x16x32 MFMA tile per 16 key rows.
+//               Text workgroups handle 128 rows of the text cache each, completely: logits,
+//               exp relative to the chunk's own maximum, P V_text (V_text transposed through
+//               LDS), and write a finished part record; the one that owns row text_len also
+//               stores the new token's k, v (Sec. 3.2: text KV is kept as it is).
 //   fb_probs    L = S theta (step 2) as a skinny GEMM per KV head, 64 query rows x 64
 //               positions per workgroup with the theta chunk transposed into LDS on the way
 //               in; emits P = exp(L - tile max) in bf16 and the tile's (max, sum) per row.
-//   fc_fused    per (KV head, group of up to 16 query rows = whole image blocks, 64 rows j
+//   fc_fused    per (KV head, group of up to 32 query rows = whole image blocks, 64 rows j
 //               of the capsule): W = sum_tiles alpha_tile (P_tile U_tile^T) with
-//               alpha = exp(tile max - block max) (step 3; U streamed straight into MFMA
-//               operands, P staged in LDS), then out_part = W Vc over the same 64 rows of
-//               the compressed values (step 4; Vc's blocked layout is the MFMA operand),
-//               un-normalised, with the block's (max, sum).  Text rows are handled by
-//               trailing workgroups of the same launch (V_text transposed through LDS).
+//               alpha = exp(tile max - block max) (step 3), then out_part = W Vc over the same
+//               64 rows of the compressed values (step 4; Vc's blocked layout is the MFMA
+//               operand), un-normalised, with the block's (max, sum).
 //   fd_finalize merges the parts of each (batch, query head) with the joint softmax
 //               statistics, adds (sum P_vis) mu, writes out and lse.
 //
 // Only S and P (bf16), the tile statistics and the part records cross kernel boundaries;
-// K_hat, V_hat and W never exist in memory.  Kernel boundaries are the only grid-wide synchronisation: a
-// device-scope fence inside a kernel writes back and invalidates an XCD's whole L2 and costs
-// far more than a launch.  Every kernel issues its independent loads in batches before the
-// first use, because at these sizes the chain of dependent memory round trips, not bandwidth,
-// sets the duration.
+// K_hat, V_hat and W never exist in memory.
+//
+// What the measurements on this chip dictate:
+//  * kernel boundaries are the only grid-wide synchronisation: a device-scope fence inside a
+//    kernel writes back and invalidates an XCD's whole L2 and costs far more than a launch;
+//  * a load whose lanes use only half of each 128-byte line (what an MFMA operand fetched
+//    straight from a row-major matrix does: 16 rows x 64 bytes) runs at half the L2->CU rate,
+//    so operands that are re-read from L2 (U in fc_fused) are fetched with fully coalesced
+//    loads and handed to the MFMA through a wave-private LDS buffer;
+//  * every kernel requests its independent data up front, stores MFMA results directly
+//    (no cross-lane reductions) and stays small in code (cold instruction cache per launch).
 //
 // Query rows of one KV head are ordered r = (b*I + i)*G + g, so the G query heads of a
 // group and consecutive image blocks share MFMA tiles.
@@ -37,33 +44,38 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+// 16-byte and 8-byte register images as native vectors (HIP's u32x4 / f32x2 structs turn plain
+// copies into memcpy through private memory, which ends up in scratch)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int D = 128;          // head_dim of this path
 constexpr int kRB = 64;         // query rows per fb_probs workgroup (4 waves x 16)
 constexpr int kPC = 64;         // positions per fb_probs workgroup (one softmax tile)
 constexpr int kTPW = 2;         // 16-row key tiles per wavefront in fa_scores
 constexpr int kJC = 64;         // capsule rows per fc_fused workgroup (one 16-row tile per wave)
-constexpr int kXC = 128;        // text rows per fc_fused text workgroup
-constexpr int kMaxN = 1024;     // fc_fused stages 16 rows of P (n bf16 each) in LDS
+constexpr int kXC = 128;        // text rows per fa_scores text workgroup
+constexpr int kMaxN = 1024;     // fc_fused stages its rows of P (n bf16 each) in LDS
 constexpr int kMaxParts = 256;  // fd_finalize keeps one scale per part in LDS
-constexpr int kSWLD = kXC + 8;  // padded row (bf16) of the W tile / text probabilities in LDS
+constexpr int kSWLD = kXC + 8;  // padded row (bf16) of the text probabilities in LDS
 constexpr int kLDV = kXC + 8;   // padded row (bf16) of the transposed text values in LDS
+constexpr int kWLD = kJC + 8;   // padded row (bf16) of the W tile in LDS
+constexpr int kULD = kPC + 8;   // padded row (bf16) of a staged U chunk in LDS
 constexpr size_t kLdsBudget = 150 * 1024;
 
 struct Plan {
     int B, Hq, Hkv, G, n, I, m, t, t_in, cap;
     int R, R_pad, NRB, m_pad, m16, NC;
-    int tiles_per_unit, vis_tiles, txt_tiles_per_bh, total_tiles;
-    int ld_t;
-    int UP, NG, JS, NXC, nparts, rec;
+    int tiles_per_unit, vis_tiles, nvis_a;
+    int UP, NT, NG, JS, NXC, nparts, rec;
     int nvis_b, b_stride, nvis_c, c_stride;
     float scale;
     int dbg;
     unsigned long long *dbgbuf;
     uint16_t *S;
     uint16_t *P;
-    float2 *stats;
-    float *St;
+    f32x2 *stats;
     float *Ypart;
     size_t bytes;
 };
@@ -75,15 +87,25 @@ struct Plan {
             p.dbgbuf[((KID) * 1024 + (blockIdx.x < 1024 ? blockIdx.x : 1023)) * 8 + (K)] = wall_clock64(); \
     } while (0)
 
-__device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__host__ __device__ inline u32x4 u32x4_mk(unsigned a, unsigned b, unsigned c, unsigned d) { return u32x4{a, b, c, d}; }
+__host__ __device__ inline u32x2 u32x2_mk(unsigned a, unsigned b) { return u32x2{a, b}; }
+__host__ __device__ inline f32x4 f32x4_mk(float a, float b, float c, float d) { return f32x4{a, b, c, d}; }
+__host__ __device__ inline f32x2 f32x2_mk(float a, float b) { return f32x2{a, b}; }
+__device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 __device__ inline float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ inline float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// element (channel c, row x) of the transposed text-value tile; the 16-byte chunks of a channel
+// row are XOR-swizzled with the channel group so the transposing stores spread over the banks
+__device__ inline int vt_index(int c, int x) { return c * kLDV + ((((x >> 3) ^ (c >> 3)) & (kXC / 8 - 1)) << 3) + (x & 7); }
 
 // ------------------------------------------------------------------------------------------
-// fa_scores: Alg. 1 step 1 on the compressed keys, and the text logits.
+// fa_scores: Alg. 1 step 1 on the compressed keys (vision workgroups), and the complete
+// attention part of 128 text rows (text workgroups).
 // MFMA tile: A = 16 key rows x 32 channels, B = 32 channels x 16 query heads of the group,
 // D[key row][head]; a lane ends up with 4 consecutive key rows of one head.
+// Part record in Ypart: [G][D] floats of un-normalised output, [G] maxima, [G] sums.
 // ------------------------------------------------------------------------------------------
+template <int G>
 __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restrict__ q,
                                                  const uint16_t *__restrict__ Kc,
                                                  uint16_t *__restrict__ Kt,
@@ -94,49 +116,151 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
     TS(0, 0);
+
+    if (static_cast<int>(blockIdx.x) >= p.nvis_a) {
+        // ---------------- text rows: one chunk of kXC rows of one (batch, KV head) ----------------
+        __shared__ __align__(16) float sS[16][kXC + 4];          // logits [head][row]
+        __shared__ __align__(16) uint16_t sWb[16][kSWLD];        // probabilities, bf16
+        __shared__ __align__(16) uint16_t sVt[D * kLDV];         // V^T [channel][row]
+        __shared__ float sRed[4][16][2];
+        __shared__ float sMx[16];
+        const int id = blockIdx.x - p.nvis_a;
+        const int bh = id / p.NXC, xc = id - bh * p.NXC;
+        const int b = bh / p.Hkv, h = bh - b * p.Hkv;
+        const int lo = xc * kXC, hi = min(p.t, lo + kXC);
+        const bool fresh = k_new != nullptr;                       // row t_in comes from k_new / v_new
+        // value rows of the chunk (16 lanes per row, a lane takes pairs of consecutive rows) and key
+        // rows of this wave's two 16-row tiles
+        const int rowl = wave * 4 + kg, cs = r16;
+        u32x4 vb[kXC / 32][2], kf[2][4], qf[4];
+#pragma unroll
+        for (int it = 0; it < kXC / 32; ++it)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int xr = lo + 2 * (rowl + 16 * it) + e, x = min(xr, hi - 1);
+                const uint16_t *vrow = (fresh && x == p.t_in) ? v_new + static_cast<size_t>(bh) * D
+                                                              : Vt + (static_cast<size_t>(bh) * p.cap + x) * D;
+                vb[it][e] = *(reinterpret_cast<const u32x4 *>(vrow) + cs);
+                if (fresh && x == p.t_in && xr == x)      // keep the cache up to date
+                    *(reinterpret_cast<u32x4 *>(Vt + (static_cast<size_t>(bh) * p.cap + x) * D) + cs) = vb[it][e];
+            }
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            const int xr = lo + 32 * wave + 16 * tt + r16, x = min(xr, hi - 1);
+            const uint16_t *krow = (fresh && x == p.t_in) ? k_new + static_cast<size_t>(bh) * D
+                                                          : Kt + (static_cast<size_t>(bh) * p.cap + x) * D;
+            const u32x4 *kp = reinterpret_cast<const u32x4 *>(krow) + kg;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) kf[tt][ks] = kp[4 * ks];
+            if (fresh && x == p.t_in && xr == x) {
+                u32x4 *kd = reinterpret_cast<u32x4 *>(Kt + (static_cast<size_t>(bh) * p.cap + x) * D) + kg;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) kd[4 * ks] = kf[tt][ks];
+            }
+        }
+        {
+            const u32x4 *qp = reinterpret_cast<const u32x4 *>(q + (static_cast<size_t>(b) * p.Hq + h * G + min(r16, G - 1)) * D) + kg;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) qf[ks] = qp[4 * ks];
+        }
+        // logits of the two tiles -> LDS
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[tt][ks]), as_bf16x8(qf[ks]), acc, 0, 0, 0);
+            *reinterpret_cast<f32x4 *>(&sS[r16][32 * wave + 16 * tt + 4 * kg]) =
+                f32x4_mk(acc[0] * p.scale, acc[1] * p.scale, acc[2] * p.scale, acc[3] * p.scale);
+        }
+        // value rows -> LDS transposed: rows (x, x+1) of channel c share one 32-bit word
+#pragma unroll
+        for (int it = 0; it < kXC / 32; ++it) {
+            const int xl2 = 2 * (rowl + 16 * it);
+            const uint32_t a[4] = {vb[it][0].x, vb[it][0].y, vb[it][0].z, vb[it][0].w};
+            const uint32_t c2[4] = {vb[it][1].x, vb[it][1].y, vb[it][1].z, vb[it][1].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                *reinterpret_cast<uint32_t *>(sVt + vt_index(8 * cs + 2 * e, xl2)) = (a[e] & 0xffffu) | (c2[e] << 16);
+                *reinterpret_cast<uint32_t *>(sVt + vt_index(8 * cs + 2 * e + 1, xl2)) = (a[e] >> 16) | (c2[e] & 0xffff0000u);
+            }
+        }
+        __syncthreads();
+        // probabilities relative to the chunk's own maximum: LPR lanes per row
+        constexpr int LPR = 256 / kXC, NGR = (G + LPR - 1) / LPR;
+        const int xl = threadIdx.x / LPR, x = lo + xl, gsub = threadIdx.x % LPR;
+        float sc[NGR];
+#pragma unroll
+        for (int k = 0; k < NGR; ++k) {
+            const int g = gsub + LPR * k;
+            sc[k] = (g < G && x < hi) ? sS[g][xl] : -INFINITY;
+        }
+#pragma unroll
+        for (int k = 0; k < NGR; ++k) {
+            float mx = sc[k];                       // max over rows = lanes with equal (lane % LPR)
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+            if (lane < LPR && lane + LPR * k < G) sRed[wave][lane + LPR * k][0] = mx;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < NGR; ++k) {
+            const int g = gsub + LPR * k;
+            float e = 0.f, mx = 0.f;
+            if (g < G) {
+                mx = fmaxf(fmaxf(sRed[0][g][0], sRed[1][g][0]), fmaxf(sRed[2][g][0], sRed[3][g][0]));
+                const uint32_t eb = x < hi ? f32_to_bf16_bits(__expf(sc[k] - mx)) : 0u;
+                e = __uint_as_float(eb << 16);
+                sWb[g][xl] = static_cast<uint16_t>(eb);
+            }
+            float sm = e;
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) sm += __shfl_xor(sm, o, 64);
+            if (lane < LPR && g < G) sRed[wave][g][1] = sm;
+            if (threadIdx.x < LPR && g < G) sMx[g] = mx;
+        }
+        for (int idx = threadIdx.x; idx < (16 - G) * kXC; idx += 256) sWb[G + idx / kXC][idx % kXC] = 0;
+        __syncthreads();
+        // out_part^T[c][g] = sum_x V^T[c][x] P[g][x]; each wave owns two 16-channel tiles
+        float *yp = p.Ypart + (static_cast<size_t>(bh) * p.nparts + p.I * p.JS + xc) * p.rec;
+#pragma unroll
+        for (int ct2 = 0; ct2 < 2; ++ct2) {
+            const int ct = 2 * wave + ct2;
+            f32x4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < kXC / 32; ++ks) {
+                const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(sVt + vt_index(16 * ct + r16, 32 * ks + 8 * kg));
+                const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(&sWb[r16][32 * ks + 8 * kg]);
+                o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, o, 0, 0, 0);
+            }
+            if (r16 < G) *reinterpret_cast<f32x4 *>(yp + r16 * D + 16 * ct + 4 * kg) = f32x4_mk(o[0], o[1], o[2], o[3]);
+        }
+        if (threadIdx.x < G) {
+            yp[G * D + threadIdx.x] = sMx[threadIdx.x];
+            yp[G * D + G + threadIdx.x] = sRed[0][threadIdx.x][1] + sRed[1][threadIdx.x][1] +
+                                          sRed[2][threadIdx.x][1] + sRed[3][threadIdx.x][1];
+        }
+        TS(0, 4);
+        return;
+    }
+
+    // ---------------- vision: kTPW tiles of 16 compressed key rows per wave ----------------
     const int tile0 = (blockIdx.x * 4 + wave) * kTPW;
-    uint4 kf[kTPW][4], qf[kTPW][4];
+    u32x4 kf[kTPW][4], qf[kTPW][4];
     bool live[kTPW];
 #pragma unroll
     for (int tt = 0; tt < kTPW; ++tt) {
         const int tile = tile0 + tt;
-        live[tt] = tile < p.total_tiles;
+        live[tt] = tile < p.vis_tiles;
         if (!live[tt]) continue;
-        const uint16_t *krow;
-        int b, h;
-        if (tile < p.vis_tiles) {
-            const int u = tile / p.tiles_per_unit, jt = tile - u * p.tiles_per_unit;
-            const int bh = u / p.I;
-            b = bh / p.Hkv;
-            h = bh - b * p.Hkv;
-            const int row = min(jt * 16 + r16, p.m - 1);
-            krow = Kc + (static_cast<size_t>(u) * p.m + row) * D;
-        } else {
-            const int tx = tile - p.vis_tiles;
-            const int bh = tx / p.txt_tiles_per_bh, xt = tx - bh * p.txt_tiles_per_bh;
-            b = bh / p.Hkv;
-            h = bh - b * p.Hkv;
-            const int x = min(xt * 16 + r16, p.t - 1);
-            if (k_new && x == p.t_in) {
-                // the new token: attend to it and store it in the text cache (Sec. 3.2)
-                krow = k_new + static_cast<size_t>(bh) * D;
-                const uint4 *ks = reinterpret_cast<const uint4 *>(krow) + kg;
-                const uint4 *vs = reinterpret_cast<const uint4 *>(v_new + static_cast<size_t>(bh) * D) + kg;
-                uint4 *kd = reinterpret_cast<uint4 *>(Kt + (static_cast<size_t>(bh) * p.cap + x) * D) + kg;
-                uint4 *vd = reinterpret_cast<uint4 *>(Vt + (static_cast<size_t>(bh) * p.cap + x) * D) + kg;
-                if (xt * 16 + r16 == x) {
-#pragma unroll
-                    for (int ks4 = 0; ks4 < 4; ++ks4) { kd[4 * ks4] = ks[4 * ks4]; vd[4 * ks4] = vs[4 * ks4]; }
-                }
-            } else {
-                krow = Kt + (static_cast<size_t>(bh) * p.cap + x) * D;
-            }
-        }
-        const uint4 *kp = reinterpret_cast<const uint4 *>(krow) + kg;
+        const int u = tile / p.tiles_per_unit, jt = tile - u * p.tiles_per_unit;
+        const int bh = u / p.I;
+        const int b = bh / p.Hkv, h = bh - b * p.Hkv;
+        const int row = min(jt * 16 + r16, p.m - 1);
+        const u32x4 *kp = reinterpret_cast<const u32x4 *>(Kc + (static_cast<size_t>(u) * p.m + row) * D) + kg;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) kf[tt][ks] = kp[4 * ks];
-        const int g = min(r16, p.G - 1);
-        const uint4 *qp = reinterpret_cast<const uint4 *>(q + (static_cast<size_t>(b) * p.Hq + h * p.G + g) * D) + kg;
+        const u32x4 *qp = reinterpret_cast<const u32x4 *>(q + (static_cast<size_t>(b) * p.Hq + h * G + min(r16, G - 1)) * D) + kg;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) qf[tt][ks] = qp[4 * ks];
     }
@@ -149,36 +273,26 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks)
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[tt][ks]), as_bf16x8(qf[tt][ks]), acc, 0, 0, 0);
-        if (r16 >= p.G) continue;      // columns beyond the group are copies of head G-1
-        const int g = r16;
-        if (tile < p.vis_tiles) {
-            const int u = tile / p.tiles_per_unit, jt = tile - u * p.tiles_per_unit;
-            const int bh = u / p.I, i = u - bh * p.I;
-            const int b = bh / p.Hkv, h = bh - b * p.Hkv;
-            const int r = (b * p.I + i) * p.G + g;
-            const int j = jt * 16 + 4 * kg;
-            uint32_t w[2];
+        if (r16 >= G) continue;      // columns beyond the group are copies of head G-1
+        const int u = tile / p.tiles_per_unit, jt = tile - u * p.tiles_per_unit;
+        const int bh = u / p.I, i = u - bh * p.I;
+        const int b = bh / p.Hkv, h = bh - b * p.Hkv;
+        const int r = (b * p.I + i) * G + r16;
+        const int j = jt * 16 + 4 * kg;
+        uint32_t w[2];
 #pragma unroll
-            for (int e = 0; e < 4; e += 2) {
-                const uint32_t lo = (j + e < p.m) ? f32_to_bf16_bits(acc[e] * p.scale) : 0u;
-                const uint32_t hi = (j + e + 1 < p.m) ? f32_to_bf16_bits(acc[e + 1] * p.scale) : 0u;
-                w[e >> 1] = lo | (hi << 16);
-            }
-            uint16_t *srow = p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + j;
-            *reinterpret_cast<uint2 *>(srow) = make_uint2(w[0], w[1]);
-            // the consumer reads whole 32-wide k-steps: keep the padding [m16, m_pad) at zero
-            if (jt == p.tiles_per_unit - 1 && p.m_pad > p.m16) *reinterpret_cast<uint2 *>(srow + 16) = make_uint2(0u, 0u);
-        } else {
-            const int tx = tile - p.vis_tiles;
-            const int bh = tx / p.txt_tiles_per_bh, xt = tx - bh * p.txt_tiles_per_bh;
-            const int b = bh / p.Hkv, h = bh - b * p.Hkv;
-            float4 o = make_float4(acc[0] * p.scale, acc[1] * p.scale, acc[2] * p.scale, acc[3] * p.scale);
-            *reinterpret_cast<float4 *>(p.St + (static_cast<size_t>(b) * p.Hq + h * p.G + g) * p.ld_t + xt * 16 + 4 * kg) = o;
+        for (int e = 0; e < 4; e += 2) {
+            const uint32_t lo = (j + e < p.m) ? f32_to_bf16_bits(acc[e] * p.scale) : 0u;
+            const uint32_t hi = (j + e + 1 < p.m) ? f32_to_bf16_bits(acc[e + 1] * p.scale) : 0u;
+            w[e >> 1] = lo | (hi << 16);
         }
+        uint16_t *srow = p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + j;
+        *reinterpret_cast<u32x2 *>(srow) = u32x2_mk(w[0], w[1]);
+        // the consumer reads whole 32-wide k-steps: keep the padding [m16, m_pad) at zero
+        if (jt == p.tiles_per_unit - 1 && p.m_pad > p.m16) *reinterpret_cast<u32x2 *>(srow + 16) = u32x2_mk(0u, 0u);
     }
     TS(0, 4);
 }
-
 
 // ------------------------------------------------------------------------------------------
 // fb_probs: Alg. 1 step 2 and the numerator of the softmax for one tile of 64 rows x 64
@@ -211,10 +325,10 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
     const uint16_t *srow = p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + 8 * kg;
     const int KS = p.m_pad / 32;
     constexpr int SB = 20;                       // m <= 640: every fragment in one batch
-    uint4 sfr[SB];
+    u32x4 sfr[SB];
 #pragma unroll
     for (int k = 0; k < SB; ++k)
-        sfr[k] = (wave_live && k < KS) ? *reinterpret_cast<const uint4 *>(srow + 32 * k) : make_uint4(0, 0, 0, 0);
+        sfr[k] = (wave_live && k < KS) ? *reinterpret_cast<const u32x4 *>(srow + 32 * k) : u32x4_mk(0, 0, 0, 0);
 
     // ---- stage the theta chunk, transposed, in LDS -------------------------------------------------
     // a thread owns a pair of consecutive rows j, j+1 and 8 positions; the pair is packed so the
@@ -225,14 +339,14 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
         const uint16_t *th = theta + static_cast<size_t>(h) * p.m * p.n + pc * PC + 8 * seg;
         constexpr int FB = 10;                   // passes per batch: m <= 640 is one batch
         for (int j0 = 2 * jp; j0 < p.m16; j0 += 64 * FB) {
-            uint4 tv[FB][2];
+            u32x4 tv[FB][2];
 #pragma unroll
             for (int k = 0; k < FB; ++k)
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
                     const int j = j0 + 64 * k + e;
-                    tv[k][e] = make_uint4(0, 0, 0, 0);
-                    if (j < p.m) tv[k][e] = *reinterpret_cast<const uint4 *>(th + static_cast<size_t>(j) * p.n);
+                    tv[k][e] = u32x4_mk(0, 0, 0, 0);
+                    if (j < p.m) tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(j) * p.n);
                 }
 #pragma unroll
             for (int k = 0; k < FB; ++k) {
@@ -264,12 +378,12 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
 #pragma unroll
     for (int mt = 0; mt < PC / 16; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int ks0 = 0; ks0 < KS; ks0 += SB) {
-        uint4 cur[SB];
+        u32x4 cur[SB];
 #pragma unroll
         for (int k = 0; k < SB; ++k) cur[k] = sfr[k];
 #pragma unroll
         for (int k = 0; k < SB; ++k)
-            if (ks0 + SB + k < KS) sfr[k] = *reinterpret_cast<const uint4 *>(srow + 32 * (ks0 + SB + k));
+            if (ks0 + SB + k < KS) sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * (ks0 + SB + k));
 #pragma unroll
         for (int k = 0; k < SB; ++k) {
             const int ks = ks0 + k;
@@ -301,119 +415,48 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
         const uint32_t a0 = f32_to_bf16_bits(__expf(acc[mt][0] - mx)), a1 = f32_to_bf16_bits(__expf(acc[mt][1] - mx));
         const uint32_t a2 = f32_to_bf16_bits(__expf(acc[mt][2] - mx)), a3 = f32_to_bf16_bits(__expf(acc[mt][3] - mx));
         sum += __uint_as_float(a0 << 16) + __uint_as_float(a1 << 16) + __uint_as_float(a2 << 16) + __uint_as_float(a3 << 16);
-        if (r < p.R) *reinterpret_cast<uint2 *>(prow + 16 * mt) = make_uint2(a0 | (a1 << 16), a2 | (a3 << 16));
+        if (r < p.R) *reinterpret_cast<u32x2 *>(prow + 16 * mt) = u32x2_mk(a0 | (a1 << 16), a2 | (a3 << 16));
     }
     sum += __shfl_xor(sum, 16, 64);
     sum += __shfl_xor(sum, 32, 64);
-    if (kg == 0 && r < p.R) p.stats[(static_cast<size_t>(h) * p.R_pad + r) * p.NC + pc] = make_float2(mx, sum);
+    if (kg == 0 && r < p.R) p.stats[(static_cast<size_t>(h) * p.R_pad + r) * p.NC + pc] = f32x2_mk(mx, sum);
     TS(1, 4);
 }
 
 // ------------------------------------------------------------------------------------------
-// fc_fused: Alg. 1 steps 3 and 4 on 64 rows of U / Vc for a group of query rows, and the
-// text rows.  G query heads per KV head, UP image blocks per workgroup (G * UP <= 16 rows
-// share the MFMA tile).
+// fc_fused: Alg. 1 steps 3 and 4 on 64 rows of U / Vc for a group of query rows.
+// G query heads per KV head; a workgroup handles NT MFMA tiles of 16 query rows, each tile
+// holding UP whole image blocks (G * UP <= 16); NC = n / 64 softmax tiles per image block
+// (compile time, so that every loop below is free of bounds checks).
+// 8 waves: wave w = (kh, jt) owns rows j = lo + 16 jt .. + 15 of U and the tiles
+// [kh ? KH0 : 0, kh ? NC : KH0) of the positions for step 3 (the two halves are added through
+// LDS), and channels 16 w .. 16 w + 15 for step 4.
 // Part record in Ypart: [G][D] floats of un-normalised output, [G] maxima, [G] sums.
 // ------------------------------------------------------------------------------------------
-template <int G, int UP>
-__global__ __launch_bounds__(256) void fc_fused(Plan p, const uint16_t *__restrict__ U,
-                                                const uint16_t *__restrict__ Vc,
-                                                const uint16_t *__restrict__ Vt)
+template <int NC> struct KSplit;          // tiles of k-half 0, tiles staged per step
+template <> struct KSplit<16> { static constexpr int KH0 = 8, UCH = 4; };
+template <> struct KSplit<9> { static constexpr int KH0 = 6, UCH = 3; };
+template <> struct KSplit<4> { static constexpr int KH0 = 2, UCH = 2; };
+
+template <int G, int UP, int NT, int NC>
+__global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restrict__ U,
+                                                const uint16_t *__restrict__ Vc)
 {
-    static_assert(G * UP <= 16, "a row group must fit one MFMA tile");
-    extern __shared__ __align__(16) uint16_t dyn[];      // vision: P [16][n + 8]; text: V^T [D][kLDV]
-    __shared__ __align__(16) uint16_t sWb[16][kSWLD];    // W tile / text probabilities, bf16
-    __shared__ float sAl[16][17];                        // alpha[row][tile]
-    __shared__ float sMx[16], sSm[16];
-    __shared__ float sRed[4][16][2];
+    static_assert(G * UP <= 16, "the rows of a tile must fit one MFMA tile");
+    constexpr int n = NC * kPC, LDP = n + 8;
+    constexpr int NR = 16 * NT;
+    constexpr int NU = NT * UP;                          // image blocks per workgroup
+    constexpr int KH0 = KSplit<NC>::KH0, UCH = KSplit<NC>::UCH;
+    constexpr int NSTEP = KH0 / UCH;                     // steps of the longer k-half
+    constexpr int USTG = UCH * 16 * kULD;                // staging elements per wave
+    extern __shared__ __align__(16) uint16_t dyn[];      // P [NR][LDP], then U staging [8][UCH][16][kULD]
+    __shared__ __align__(16) uint16_t sWb[NR][kWLD];     // W tile, bf16
+    __shared__ float sAl[NR][NC + 1];                    // alpha[row][tile]
+    __shared__ float sMx[NR], sSm[NR];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
-    const int rec = p.rec;
+    const int jt = wave & 3, kh = wave >> 2;
 
-    if (static_cast<int>(blockIdx.x) >= p.nvis_c) {
-        // ---------------- text rows: one chunk of kXC rows of one (batch, KV head) ----------------
-        TS(2, 0);
-        const int id = blockIdx.x - p.nvis_c;
-        const int bh = id / p.NXC, xc = id - bh * p.NXC;
-        const int b = bh / p.Hkv, h = bh - b * p.Hkv;
-        const int lo = xc * kXC, hi = min(p.t, lo + kXC);
-        // value rows -> LDS transposed: sVt[c][x]
-        {
-            const int rowl = wave * 4 + kg, cs = r16;
-            const uint4 *sp = reinterpret_cast<const uint4 *>(Vt + static_cast<size_t>(bh) * p.cap * D) + cs;
-            uint4 vb[kXC / 16];
-#pragma unroll
-            for (int it = 0; it < kXC / 16; ++it) vb[it] = sp[static_cast<size_t>(min(lo + rowl + 16 * it, hi - 1)) * (D / 8)];
-#pragma unroll
-            for (int it = 0; it < kXC / 16; ++it) {
-                const uint32_t w4[4] = {vb[it].x, vb[it].y, vb[it].z, vb[it].w};
-                uint16_t *dst = dyn + (8 * cs) * kLDV + rowl + 16 * it;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    dst[(2 * e) * kLDV] = static_cast<uint16_t>(w4[e] & 0xffffu);
-                    dst[(2 * e + 1) * kLDV] = static_cast<uint16_t>(w4[e] >> 16);
-                }
-            }
-        }
-        // probabilities relative to the chunk's own maximum: LPR lanes per row
-        constexpr int LPR = 256 / kXC, NG = (G + LPR - 1) / LPR;
-        const int xl = threadIdx.x / LPR, x = lo + xl, gsub = threadIdx.x % LPR;
-        float sc[NG];
-#pragma unroll
-        for (int k = 0; k < NG; ++k) {
-            const int g = gsub + LPR * k;
-            sc[k] = (g < G && x < hi) ? p.St[(static_cast<size_t>(b) * p.Hq + h * G + g) * p.ld_t + x] : -INFINITY;
-        }
-#pragma unroll
-        for (int k = 0; k < NG; ++k) {
-            float mx = sc[k];                       // max over rows = lanes with equal (lane % LPR)
-#pragma unroll
-            for (int o = LPR; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-            if (lane < LPR && lane + LPR * k < G) sRed[wave][lane + LPR * k][0] = mx;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < NG; ++k) {
-            const int g = gsub + LPR * k;
-            float e = 0.f, mx = 0.f;
-            if (g < G) {
-                mx = fmaxf(fmaxf(sRed[0][g][0], sRed[1][g][0]), fmaxf(sRed[2][g][0], sRed[3][g][0]));
-                const uint32_t eb = x < hi ? f32_to_bf16_bits(__expf(sc[k] - mx)) : 0u;
-                e = __uint_as_float(eb << 16);
-                sWb[g][xl] = static_cast<uint16_t>(eb);
-            }
-            float sm = e;
-#pragma unroll
-            for (int o = LPR; o < 64; o <<= 1) sm += __shfl_xor(sm, o, 64);
-            if (lane < LPR && g < G) sRed[wave][g][1] = sm;
-            if (threadIdx.x < LPR && g < G) sMx[g] = mx;
-        }
-        for (int idx = threadIdx.x; idx < (16 - G) * kXC; idx += 256) sWb[G + idx / kXC][idx % kXC] = 0;
-        __syncthreads();
-        // out_part^T[c][g] = sum_x V^T[c][x] P[g][x]; each wave owns two 16-channel tiles
-        float *yp = p.Ypart + (static_cast<size_t>(bh) * p.nparts + p.I * p.JS + xc) * rec;
-#pragma unroll
-        for (int ct2 = 0; ct2 < 2; ++ct2) {
-            const int ct = 2 * wave + ct2;
-            f32x4 o = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < kXC / 32; ++ks) {
-                const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(dyn + (16 * ct + r16) * kLDV + 32 * ks + 8 * kg);
-                const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(&sWb[r16][32 * ks + 8 * kg]);
-                o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, o, 0, 0, 0);
-            }
-            if (r16 < G) *reinterpret_cast<float4 *>(yp + r16 * D + 16 * ct + 4 * kg) = make_float4(o[0], o[1], o[2], o[3]);
-        }
-        if (threadIdx.x < G) {
-            yp[G * D + threadIdx.x] = sMx[threadIdx.x];
-            yp[G * D + G + threadIdx.x] = sRed[0][threadIdx.x][1] + sRed[1][threadIdx.x][1] +
-                                          sRed[2][threadIdx.x][1] + sRed[3][threadIdx.x][1];
-        }
-        TS(2, 4);
-        return;
-    }
-
-    // ---------------- vision: (row group ug, KV head h, slice s of the capsule rows) ----------------
     // ug is the slow index with a stride that is a multiple of 8: workgroups that stream the same
     // rows of U[h] sit on one XCD and share its L2
     TS(2, 0);
@@ -421,174 +464,209 @@ __global__ __launch_bounds__(256) void fc_fused(Plan p, const uint16_t *__restri
     const int hs = blockIdx.x - ug * p.c_stride;
     if (hs >= p.Hkv * p.JS) return;
     const int h = hs / p.JS, s = hs - h * p.JS;
-    const int ub0 = ug * UP;
-    const int nunits = min(UP, p.B * p.I - ub0);
-    const int nrows = nunits * G, r0 = ub0 * G;
+    const int ub0 = ug * NU;
+    const int units_total = p.B * p.I;
+    const int nunits = min(NU, units_total - ub0);
     const int lo = s * kJC, hi = min(p.m, lo + kJC);
-    const int n = p.n, LDP = n + 8, NC = p.NC;
     uint16_t *sP = dyn;
+    uint16_t *sU = dyn + NR * LDP + wave * USTG;         // this wave's staging buffer
 
-    // ---- everything this workgroup reads is requested up front ------------------------------------------
-    // U rows of this wave's 16-row tile, first batch of MFMA operands
-    const bool tile_live = lo + 16 * wave < hi;
-    const uint16_t *urow = U + (static_cast<size_t>(h) * p.m + min(lo + 16 * wave + r16, p.m - 1)) * n + 8 * kg;
-    const int KS = n / 32;
-    constexpr int UBK = 8;
-    uint4 ufr[UBK];
-#pragma unroll
-    for (int k = 0; k < UBK; ++k)
-        ufr[k] = (tile_live && k < KS) ? *reinterpret_cast<const uint4 *>(urow + 32 * k) : make_uint4(0, 0, 0, 0);
-    // P rows of the group -> LDS (16 threads per row, 16 bytes each per pass)
-    uint4 pfr[kMaxN / 128];
+    // ---- everything this workgroup reads is requested up front, without bounds checks: -----------------
+    // out-of-range rows are clamped to valid ones and their results are never stored
+    // P rows -> LDS: 16 threads per row, 32 rows per pass
+    constexpr int PCH = n / 8;                           // 16-byte pieces per row
+    constexpr int KP = (PCH + 15) / 16;
+    u32x4 pfr[KP];
+    const int prow_i = threadIdx.x >> 4, psub = threadIdx.x & 15;
     {
-        const int row = threadIdx.x >> 4, sub = threadIdx.x & 15;
-        const uint4 *prow = reinterpret_cast<const uint4 *>(p.P + (static_cast<size_t>(h) * p.R_pad + r0 + min(row, nrows - 1)) * n) + sub;
+        const int pr = min(prow_i, NR - 1);
+        const int r = min(ub0 * G + (pr >> 4) * (UP * G) + (pr & 15), p.R - 1);
+        const u32x4 *prow = reinterpret_cast<const u32x4 *>(p.P + (static_cast<size_t>(h) * p.R_pad + r) * n);
 #pragma unroll
-        for (int k = 0; k < kMaxN / 128; ++k)
-            pfr[k] = (16 * k + sub < n / 8 && row < nrows) ? prow[16 * k] : make_uint4(0, 0, 0, 0);
+        for (int k = 0; k < KP; ++k) pfr[k] = prow[min(16 * k + psub, PCH - 1)];
     }
-    // tile statistics of row (lane & 15): one float2 per tile, lanes with kg > 0 idle
-    float2 st[kMaxN / kPC];
+    // tile statistics: lane (kg = MFMA tile, r16 = row) of wave 0 reads one f32x2 per softmax tile
+    f32x2 st[NC];
+#pragma unroll
+    for (int k = 0; k < NC; ++k) st[k] = f32x2_mk(0.f, 0.f);
+    if (wave == 0) {
+        const int r = min(ub0 * G + min(kg, NT - 1) * (UP * G) + r16, p.R - 1);
+        const f32x2 *sp = p.stats + (static_cast<size_t>(h) * p.R_pad + r) * NC;
+#pragma unroll
+        for (int k = 0; k < NC; ++k) st[k] = sp[k];
+    }
+    // U rows lo + 16 jt ... of this wave's tiles, fully coalesced: 8 lanes read the 128 bytes of one
+    // row of one tile, 8 rows per instruction; all steps stay in flight
+    const int c_begin = kh ? KH0 : 0;
+    const int nstep = kh ? (NC - KH0) / UCH : NSTEP;
+    u32x4 ul[NSTEP][2 * UCH];
     {
-        const float2 *sp = p.stats + (static_cast<size_t>(h) * p.R_pad + r0 + min(r16, nrows - 1)) * NC;
+        const int row = min(lo + 16 * jt + (lane >> 3), p.m - 1), row8 = min(lo + 16 * jt + 8 + (lane >> 3), p.m - 1);
+        const uint16_t *u0 = U + (static_cast<size_t>(h) * p.m + row) * n + c_begin * kPC + 8 * (lane & 7);
+        const uint16_t *u8 = U + (static_cast<size_t>(h) * p.m + row8) * n + c_begin * kPC + 8 * (lane & 7);
 #pragma unroll
-        for (int k = 0; k < kMaxN / kPC; ++k) st[k] = (wave == 0 && kg == 0 && k < NC) ? sp[k] : make_float2(-INFINITY, 0.f);
+        for (int step = 0; step < NSTEP; ++step) {
+            // a step the shorter k-half does not have re-reads its last tile; the result is not used
+            const int cs0 = min(step, nstep - 1) * UCH;
+#pragma unroll
+            for (int ci = 0; ci < UCH; ++ci) {
+                ul[step][2 * ci] = *reinterpret_cast<const u32x4 *>(u0 + (cs0 + ci) * kPC);
+                ul[step][2 * ci + 1] = *reinterpret_cast<const u32x4 *>(u8 + (cs0 + ci) * kPC);
+            }
+        }
     }
-    // compressed values: wave w owns channel tiles 2w, 2w+1; the operand (8 rows j of one
-    // channel) is 16 contiguous bytes in the blocked layout.  Blocks of the group are handled in
-    // batches of UBATCH; the first batch is requested here.
-    constexpr int UBATCH = UP < 4 ? UP : 4;
-    const int jb0 = lo / 8;
-    // a shorter last block ([D][w], w = m % 8) exists only in the last slice: uniform branch
-    const bool has_tail = (p.m & 7) != 0 && hi == p.m;
-    auto load_values = [&](int un0, uint4 (&dst)[UBATCH][2][2]) {
+    // compressed values: wave w owns channels 16 w ...; the operand (8 rows j of one channel) is 16
+    // contiguous bytes in the blocked layout.  Image blocks are handled in batches of UBATCH.
+    constexpr int UBATCH = NU < 4 ? NU : 4;
+    const int jb0 = lo >> 3;
+    const int nfull = p.m >> 3;                          // complete 8-row blocks of a record
+    const int wtail = p.m & 7;
+    const bool has_tail = wtail != 0 && hi == p.m;       // the shorter last block lives in the last slice
+    const int cch = 16 * wave + r16;                     // this lane's channel
+    auto load_values = [&](int un0, u32x4 (&dst)[UBATCH][2]) {
 #pragma unroll
         for (int a = 0; a < UBATCH; ++a) {
             const int ub = ub0 + min(un0 + a, nunits - 1);
             const int b = ub / p.I, i = ub - b * p.I;
             const uint16_t *vbase = Vc + (static_cast<size_t>(b * p.Hkv + h) * p.I + i) * p.m * D;
 #pragma unroll
-            for (int ct2 = 0; ct2 < 2; ++ct2)
+            for (int ks = 0; ks < 2; ++ks) {
+                // blocks beyond the record are clamped: their weights in W are zero
+                const int jb = min(jb0 + 4 * ks + kg, max(nfull - 1, 0));
+                dst[a][ks] = *reinterpret_cast<const u32x4 *>(vbase + static_cast<size_t>(jb) * 8 * D + cch * 8);
+            }
+            if (nfull == 0) { dst[a][0] = u32x4_mk(0, 0, 0, 0); dst[a][1] = u32x4_mk(0, 0, 0, 0); }
+            if (has_tail) {                              // [D][wtail] block, element granular
+                const int lb = nfull - jb0;              // its position in this slice: k-step lb / 4, lanes kg == lb % 4
+                uint32_t e[8];
+                const uint16_t *tp = vbase + static_cast<size_t>(nfull) * 8 * D + cch * wtail;
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    const int jb = jb0 + 4 * ks + kg, c = 16 * (2 * wave + ct2) + r16;
-                    dst[a][ct2][ks] = (8 * jb + 8 <= p.m)
-                                          ? *reinterpret_cast<const uint4 *>(vbase + static_cast<size_t>(jb) * 8 * D + c * 8)
-                                          : make_uint4(0, 0, 0, 0);
+                for (int q2 = 0; q2 < 8; ++q2) e[q2] = (q2 < wtail && kg == (lb & 3)) ? tp[q2] : 0u;
+                const u32x4 tv = u32x4_mk(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+                if (kg == (lb & 3)) {
+                    if ((lb >> 2) == 0) dst[a][0] = tv; else dst[a][1] = tv;
+                } else if (jb0 + 4 * (lb >> 2) + kg > nfull) {   // blocks after the tail do not exist
+                    if ((lb >> 2) == 0) dst[a][0] = u32x4_mk(0, 0, 0, 0); else dst[a][1] = u32x4_mk(0, 0, 0, 0);
                 }
-            if (has_tail) {
-#pragma unroll
-                for (int ct2 = 0; ct2 < 2; ++ct2)
-#pragma unroll
-                    for (int ks = 0; ks < 2; ++ks) {
-                        const int jb = jb0 + 4 * ks + kg, c = 16 * (2 * wave + ct2) + r16;
-                        if (8 * jb < p.m && 8 * jb + 8 > p.m) {
-                            const int w = p.m - 8 * jb;
-                            const uint16_t *tp = vbase + static_cast<size_t>(jb) * 8 * D + c * w;
-                            uint32_t e[8];
-#pragma unroll
-                            for (int q2 = 0; q2 < 8; ++q2) e[q2] = q2 < w ? tp[q2] : 0u;
-                            dst[a][ct2][ks] = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
-                        }
-                    }
             }
         }
     };
-    uint4 vfr[UBATCH][2][2];
+    u32x4 vfr[UBATCH][2];
     load_values(0, vfr);
 
     TS(2, 1);
     // ---- block statistics: alpha[row][tile] = exp(tile max - block max) ----------------------------------
-    if (wave == 0 && kg == 0) {
-        float mx = -INFINITY;
+    if (wave == 0 && kg < NT) {
+        float mx = st[0].x;
 #pragma unroll
-        for (int k = 0; k < kMaxN / kPC; ++k) mx = fmaxf(mx, st[k].x);
+        for (int k = 1; k < NC; ++k) mx = fmaxf(mx, st[k].x);
         float sm = 0.f;
 #pragma unroll
-        for (int k = 0; k < kMaxN / kPC; ++k) {
-            const float a = k < NC ? __expf(st[k].x - mx) : 0.f;
+        for (int k = 0; k < NC; ++k) {
+            const float a = __expf(st[k].x - mx);
             sm += st[k].y * a;
-            sAl[r16][k] = a;
+            sAl[16 * kg + r16][k] = a;
         }
-        sMx[r16] = mx;
-        sSm[r16] = sm;
+        sMx[16 * kg + r16] = mx;
+        sSm[16 * kg + r16] = sm;
     }
-    {
-        const int row = threadIdx.x >> 4, sub = threadIdx.x & 15;
-        uint4 *dst = reinterpret_cast<uint4 *>(sP + row * LDP) + sub;
+    if (prow_i < NR) {
+        u32x4 *dst = reinterpret_cast<u32x4 *>(sP + prow_i * LDP);
 #pragma unroll
-        for (int k = 0; k < kMaxN / 128; ++k)
-            if (16 * k + sub < n / 8) dst[16 * k] = pfr[k];
+        for (int k = 0; k < KP; ++k) dst[min(16 * k + psub, PCH - 1)] = pfr[k];   // clamped duplicates carry equal data
     }
     __syncthreads();
     TS(2, 2);
 
     // ---- step 3: W^T[j][row] = sum_tiles alpha[row][tile] sum_pos U[j][pos] P[row][pos] ------------------
+    f32x4 w[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) w[t] = f32x4{0.f, 0.f, 0.f, 0.f};
     {
-        f32x4 w = {0.f, 0.f, 0.f, 0.f};
-        if (tile_live) {
-            const uint16_t *pb = sP + r16 * LDP + 8 * kg;
-            for (int ks0 = 0; ks0 < KS; ks0 += UBK) {
-                uint4 cur[UBK];
+        const uint16_t *pb = sP + r16 * LDP + 8 * kg + c_begin * kPC;
+        // staged tile layout: [tile][row 16][kULD]; row (lane >> 3) + 8 (i & 1), 16-byte piece lane & 7
+        uint16_t *uw = sU + (lane >> 3) * kULD + 8 * (lane & 7);
+        const uint16_t *ur = sU + r16 * kULD + 8 * kg;
+        const float *al = &sAl[r16][c_begin];
 #pragma unroll
-                for (int k = 0; k < UBK; ++k) cur[k] = ufr[k];
+        for (int step = 0; step < NSTEP; ++step) {
+            if (step < nstep) {
+                __builtin_amdgcn_wave_barrier();        // the wave is done reading the previous step
 #pragma unroll
-                for (int k = 0; k < UBK; ++k)
-                    if (ks0 + UBK + k < KS) ufr[k] = *reinterpret_cast<const uint4 *>(urow + 32 * (ks0 + UBK + k));
+                for (int i = 0; i < 2 * UCH; ++i)
+                    *reinterpret_cast<u32x4 *>(uw + (i >> 1) * (16 * kULD) + (i & 1) * (8 * kULD)) = ul[step][i];
+                __builtin_amdgcn_wave_barrier();        // staging buffer is wave-private: no block barrier
 #pragma unroll
-                for (int k = 0; k < UBK; k += 2) {
-                    if (ks0 + k < KS) {            // one softmax tile = 64 positions = two k-steps
+                for (int ci = 0; ci < UCH; ++ci) {      // one softmax tile = 64 positions = two k-steps
+                    const int c = step * UCH + ci;
+                    const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(ur + ci * (16 * kULD));
+                    const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(ur + ci * (16 * kULD) + 32);
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
                         f32x4 wt = {0.f, 0.f, 0.f, 0.f};
                         wt = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            as_bf16x8(cur[k]), *reinterpret_cast<const bf16x8 *>(pb + 32 * (ks0 + k)), wt, 0, 0, 0);
+                            a0, *reinterpret_cast<const bf16x8 *>(pb + 16 * t * LDP + kPC * c), wt, 0, 0, 0);
                         wt = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                            as_bf16x8(cur[k + 1]), *reinterpret_cast<const bf16x8 *>(pb + 32 * (ks0 + k + 1)), wt, 0, 0, 0);
-                        const float al = sAl[r16][(ks0 + k) >> 1];
-                        w[0] += al * wt[0]; w[1] += al * wt[1]; w[2] += al * wt[2]; w[3] += al * wt[3];
+                            a1, *reinterpret_cast<const bf16x8 *>(pb + 16 * t * LDP + kPC * c + 32), wt, 0, 0, 0);
+                        const float a = al[16 * t * (NC + 1) + c];
+                        w[t][0] += a * wt[0]; w[t][1] += a * wt[1]; w[t][2] += a * wt[2]; w[t][3] += a * wt[3];
                     }
                 }
             }
         }
-        const int jl = 16 * wave + 4 * kg;
-        const uint32_t w0 = (lo + jl + 0 < hi) ? f32_to_bf16_bits(w[0]) : 0u, w1 = (lo + jl + 1 < hi) ? f32_to_bf16_bits(w[1]) : 0u;
-        const uint32_t w2 = (lo + jl + 2 < hi) ? f32_to_bf16_bits(w[2]) : 0u, w3 = (lo + jl + 3 < hi) ? f32_to_bf16_bits(w[3]) : 0u;
-        *reinterpret_cast<uint2 *>(&sWb[r16][jl]) = make_uint2(w0 | (w1 << 16), w2 | (w3 << 16));
+    }
+    // the two k-halves meet in LDS: half 1 parks its partial sums in its own staging buffer
+    f32x4 *park = reinterpret_cast<f32x4 *>(dyn + NR * LDP + (4 + jt) * USTG) + lane;
+    if (kh == 1) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) park[64 * t] = f32x4_mk(w[t][0], w[t][1], w[t][2], w[t][3]);
+    }
+    __syncthreads();
+    if (kh == 0) {
+        const int jl = 16 * jt + 4 * kg;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const f32x4 o = park[64 * t];
+            const float w0 = w[t][0] + o.x, w1 = w[t][1] + o.y, w2 = w[t][2] + o.z, w3 = w[t][3] + o.w;
+            const uint32_t b0 = (lo + jl + 0 < hi) ? f32_to_bf16_bits(w0) : 0u, b1 = (lo + jl + 1 < hi) ? f32_to_bf16_bits(w1) : 0u;
+            const uint32_t b2 = (lo + jl + 2 < hi) ? f32_to_bf16_bits(w2) : 0u, b3 = (lo + jl + 3 < hi) ? f32_to_bf16_bits(w3) : 0u;
+            *reinterpret_cast<u32x2 *>(&sWb[16 * t + r16][jl]) = u32x2_mk(b0 | (b1 << 16), b2 | (b3 << 16));
+        }
     }
     __syncthreads();
     TS(2, 3);
 
-    // ---- step 4: out_part^T[c][row] = sum_j Vc^T[c][j] W[row][j], per image block of the group -----------
-    const bf16x8 wb0 = *reinterpret_cast<const bf16x8 *>(&sWb[r16][8 * kg]);
-    const bf16x8 wb1 = *reinterpret_cast<const bf16x8 *>(&sWb[r16][32 + 8 * kg]);
-    const int un_mine = r16 / G, g_mine = r16 - un_mine * G;
+    // ---- step 4: out_part^T[c][row] = sum_j Vc^T[c][j] W[row][j], per image block -------------------------
+    bf16x8 wb[NT][2];
 #pragma unroll
-    for (int un0 = 0; un0 < UP; un0 += UBATCH) {
-        uint4 cur[UBATCH][2][2];
+    for (int t = 0; t < NT; ++t) {
+        wb[t][0] = *reinterpret_cast<const bf16x8 *>(&sWb[16 * t + r16][8 * kg]);
+        wb[t][1] = *reinterpret_cast<const bf16x8 *>(&sWb[16 * t + r16][32 + 8 * kg]);
+    }
+    constexpr int un_lim = UP * G;
+    const int un_mine = r16 / G, g_mine = r16 - un_mine * G;     // image block (within a tile) of this lane's row
 #pragma unroll
-        for (int a = 0; a < UBATCH; ++a)
+    for (int un0 = 0; un0 < NU; un0 += UBATCH) {
+        u32x4 cur[UBATCH][2];
 #pragma unroll
-            for (int ct2 = 0; ct2 < 2; ++ct2)
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) cur[a][ct2][ks] = vfr[a][ct2][ks];
-        if (un0 + UBATCH < UP && un0 + UBATCH < nunits) load_values(un0 + UBATCH, vfr);
+        for (int a = 0; a < UBATCH; ++a) { cur[a][0] = vfr[a][0]; cur[a][1] = vfr[a][1]; }
+        if (un0 + UBATCH < NU && un0 + UBATCH < nunits) load_values(un0 + UBATCH, vfr);
 #pragma unroll
         for (int a = 0; a < UBATCH; ++a) {
-            const int un = un0 + a;
-            const int ub = ub0 + un;
-            const int b = ub / p.I, i = ub - b * p.I;
-            float *yp = p.Ypart + (static_cast<size_t>(b * p.Hkv + h) * p.nparts + i * p.JS + s) * rec;
-            const bool mine = un < nunits && un_mine == un && r16 < nrows;
-#pragma unroll
-            for (int ct2 = 0; ct2 < 2; ++ct2) {
-                f32x4 o = {0.f, 0.f, 0.f, 0.f};
-                o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur[a][ct2][0]), wb0, o, 0, 0, 0);
-                o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur[a][ct2][1]), wb1, o, 0, 0, 0);
-                if (mine)
-                    *reinterpret_cast<float4 *>(yp + g_mine * D + 16 * (2 * wave + ct2) + 4 * kg) = make_float4(o[0], o[1], o[2], o[3]);
-            }
-            if (wave == 0 && kg == 0 && mine) {
-                yp[G * D + g_mine] = sMx[r16];
-                yp[G * D + G + g_mine] = s == 0 ? sSm[r16] : 0.f;     // the block's mass is counted once
+            const int un = un0 + a;                      // image block within the workgroup
+            const int t = un / UP, ul2 = un - t * UP;    // its MFMA tile and slot in the tile
+            f32x4 o = {0.f, 0.f, 0.f, 0.f};
+            o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur[a][0]), wb[t][0], o, 0, 0, 0);
+            o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur[a][1]), wb[t][1], o, 0, 0, 0);
+            if (un < nunits && un_mine == ul2 && r16 < un_lim) {
+                const int ub = ub0 + un;
+                const int b = ub / p.I, i = ub - b * p.I;
+                float *yp = p.Ypart + (static_cast<size_t>(b * p.Hkv + h) * p.nparts + i * p.JS + s) * p.rec;
+                *reinterpret_cast<f32x4 *>(yp + g_mine * D + 16 * wave + 4 * kg) = f32x4_mk(o[0], o[1], o[2], o[3]);
+                if (wave == 0 && kg == 0) {
+                    yp[G * D + g_mine] = sMx[16 * t + r16];
+                    yp[G * D + G + g_mine] = s == 0 ? sSm[16 * t + r16] : 0.f;     // the block's mass is counted once
+                }
             }
         }
     }
@@ -670,21 +748,17 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
 }
 
 size_t lds_b(int m_pad) { return static_cast<size_t>(kPC) * (m_pad + 8) * sizeof(uint16_t); }
-size_t lds_c(int n)
+size_t lds_c(int n, int nt, int uch)
 {
-    const size_t vis = static_cast<size_t>(16) * (n + 8) * sizeof(uint16_t);
-    const size_t txt = static_cast<size_t>(D) * kLDV * sizeof(uint16_t);
-    return vis > txt ? vis : txt;
+    return (static_cast<size_t>(16) * nt * (n + 8) + static_cast<size_t>(8) * uch * 16 * kULD) * sizeof(uint16_t);
 }
 
 int units_per_group(int G)
 {
-    switch (G) {
+    switch (G) {        // group sizes with a compiled kernel
     case 1: return 16;
-    case 2: return 8;
     case 4: return 4;
     case 7: case 8: return 2;
-    case 16: return 1;
     default: return 0;
     }
 }
@@ -704,11 +778,11 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.NC = p.n / kPC;
     p.tiles_per_unit = p.m16 / 16;
     p.vis_tiles = p.B * p.Hkv * p.I * p.tiles_per_unit;
-    p.txt_tiles_per_bh = (t + 15) / 16;
-    p.total_tiles = p.vis_tiles + p.B * p.Hkv * p.txt_tiles_per_bh;
-    p.ld_t = static_cast<int>(align_up(cap > 0 ? cap : 1, 16));
+    p.nvis_a = (p.vis_tiles + 4 * kTPW - 1) / (4 * kTPW);
     p.UP = units_per_group(p.G);
-    p.NG = p.UP ? (p.B * p.I + p.UP - 1) / p.UP : 0;
+    // two MFMA tiles of query rows per workgroup halve the re-streaming of U when the rows are there
+    p.NT = (p.UP && p.B * p.I > p.UP) ? 2 : 1;
+    p.NG = p.UP ? (p.B * p.I + p.NT * p.UP - 1) / (p.NT * p.UP) : 0;
     p.JS = (p.m + kJC - 1) / kJC;
     p.NXC = (t + kXC - 1) / kXC;
     p.nparts = p.I * p.JS + p.NXC;
@@ -727,21 +801,61 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     };
     p.S = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(p.Hkv) * p.R_pad * p.m_pad * 2));
     p.P = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(p.Hkv) * p.R_pad * p.n * 2));
-    p.stats = reinterpret_cast<float2 *>(take(static_cast<size_t>(p.Hkv) * p.R_pad * p.NC * 8));
-    p.St = reinterpret_cast<float *>(take(static_cast<size_t>(p.B) * p.Hq * p.ld_t * 4));
+    p.stats = reinterpret_cast<f32x2 *>(take(static_cast<size_t>(p.Hkv) * p.R_pad * p.NC * 8));
     p.Ypart = reinterpret_cast<float *>(take(static_cast<size_t>(p.B) * p.Hkv * (p.I * p.JS + nxc_max) * p.rec * 4));
     p.bytes = off;
     p.dbgbuf = nullptr;
     return p;
 }
 
-template <int G, int UP> kvc_status launch_c(const Plan &p, const DecodeCall &c)
+template <int G> void launch_a(const Plan &p, const DecodeCall &c)
 {
-    const int grid = p.nvis_c + p.B * p.Hkv * p.NXC;
-    fc_fused<G, UP><<<grid, 256, lds_c(p.n), c.stream>>>(p, static_cast<const uint16_t *>(c.U),
-                                                         static_cast<const uint16_t *>(c.Vc),
-                                                         static_cast<const uint16_t *>(c.Vt));
-    return KVC_OK;
+    fa_scores<G><<<p.nvis_a + p.B * p.Hkv * p.NXC, 256, 0, c.stream>>>(
+        p, static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc),
+        static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt),
+        static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new));
+}
+
+template <int G, int UP, int NT, int NC> void launch_c3(const Plan &p, const DecodeCall &c)
+{
+    const size_t lds = lds_c(NC * kPC, NT, KSplit<NC>::UCH);
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(fc_fused<G, UP, NT, NC>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        attr_set = true;
+    }
+    fc_fused<G, UP, NT, NC><<<p.nvis_c, 512, lds, c.stream>>>(p, static_cast<const uint16_t *>(c.U),
+                                                             static_cast<const uint16_t *>(c.Vc));
+}
+
+template <int G, int UP, int NT> void launch_c2(const Plan &p, const DecodeCall &c)
+{
+    switch (p.NC) {
+    case 16: launch_c3<G, UP, NT, 16>(p, c); break;
+    case 9: launch_c3<G, UP, NT, 9>(p, c); break;
+    default: launch_c3<G, UP, NT, 4>(p, c); break;
+    }
+}
+
+template <int G, int UP> void launch_ac(const Plan &p, const DecodeCall &c, bool first)
+{
+    if (first) {
+        launch_a<G>(p, c);
+    } else if (p.nvis_c > 0) {
+        if (p.NT == 2) launch_c2<G, UP, 2>(p, c);
+        else launch_c2<G, UP, 1>(p, c);
+    }
+}
+
+void launch_for_group(const Plan &p, const DecodeCall &c, bool first)
+{
+    switch (p.G) {
+    case 1: launch_ac<1, 16>(p, c, first); break;
+    case 4: launch_ac<4, 4>(p, c, first); break;
+    case 7: launch_ac<7, 2>(p, c, first); break;
+    default: launch_ac<8, 2>(p, c, first); break;
+    }
 }
 
 }  // namespace
@@ -750,13 +864,14 @@ bool fast_decode_supported(const kvc_shape &s)
 {
     if (s.dtype != KVC_BF16 || s.head_dim != D) return false;
     if (units_per_group(s.n_q_heads / s.n_kv_heads) == 0) return false;
-    if (s.n_img_tokens % kPC != 0 || s.n_img_tokens > kMaxN) return false;
+    // fc_fused is compiled for 4, 9 and 16 softmax tiles of 64 positions per image block
+    if (s.n_img_tokens != 256 && s.n_img_tokens != 576 && s.n_img_tokens != 1024) return false;
     return lds_b(static_cast<int>(align_up(s.m, 32))) <= kLdsBudget;
 }
 
 size_t fast_decode_ws_bytes(const kvc_shape &s, int32_t max_text)
 {
-    return make_plan(s, max_text, max_text, max_text, 1.f, nullptr).bytes;
+    return make_plan(s, max_text, max_text, max_text, 1.f, nullptr).bytes + (1 << 20);
 }
 
 kvc_status fast_decode(const DecodeCall &c)
@@ -767,11 +882,7 @@ kvc_status fast_decode(const DecodeCall &c)
     p.dbgbuf = (p.dbg & 256) && c.ws_bytes >= p.bytes + (1 << 20)
                    ? reinterpret_cast<unsigned long long *>(static_cast<char *>(c.ws) + ((c.ws_bytes - (1 << 20)) & ~size_t(255)))
                    : nullptr;
-    const int waves = (p.total_tiles + kTPW - 1) / kTPW;
-    fa_scores<<<(waves + 3) / 4, 256, 0, c.stream>>>(
-        p, static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc),
-        static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt),
-        static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new));
+    launch_for_group(p, c, true);
     if (p.nvis_b > 0) {
         static bool attr_set = false;
         if (!attr_set) {
@@ -783,16 +894,7 @@ kvc_status fast_decode(const DecodeCall &c)
         }
         fb_probs<<<p.nvis_b, 256, lds_b(p.m_pad), c.stream>>>(p, static_cast<const uint16_t *>(c.theta));
     }
-    kvc_status st;
-    switch (p.G) {
-    case 1: st = launch_c<1, 16>(p, c); break;
-    case 2: st = launch_c<2, 8>(p, c); break;
-    case 4: st = launch_c<4, 4>(p, c); break;
-    case 7: st = launch_c<7, 2>(p, c); break;
-    case 8: st = launch_c<8, 2>(p, c); break;
-    default: st = launch_c<16, 1>(p, c); break;
-    }
-    if (st != KVC_OK) return st;
+    launch_for_group(p, c, false);
     fd_finalize<<<p.B * p.Hq, 128, 0, c.stream>>>(p, static_cast<const uint16_t *>(c.mu),
                                                   static_cast<uint16_t *>(c.out), c.lse);
     return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
