@@ -119,11 +119,9 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
 
     if (static_cast<int>(blockIdx.x) >= p.nvis_a) {
         // ---------------- text rows: one chunk of kXC rows of one (batch, KV head) ----------------
-        __shared__ __align__(16) float sS[16][kXC + 4];          // logits [head][row]
-        __shared__ __align__(16) uint16_t sWb[16][kSWLD];        // probabilities, bf16
+        __shared__ __align__(16) uint16_t sWb[16][kSWLD];        // probabilities [head][row], bf16
         __shared__ __align__(16) uint16_t sVt[D * kLDV];         // V^T [channel][row]
-        __shared__ float sRed[4][16][2];
-        __shared__ float sMx[16];
+        __shared__ float sRed[2][4][16];                         // per-wave maxima / sums per head
         const int id = blockIdx.x - p.nvis_a;
         const int bh = id / p.NXC, xc = id - bh * p.NXC;
         const int b = bh / p.Hkv, h = bh - b * p.Hkv;
@@ -137,42 +135,43 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
         for (int it = 0; it < kXC / 32; ++it)
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const int xr = lo + 2 * (rowl + 16 * it) + e, x = min(xr, hi - 1);
+                const int x = min(lo + 2 * (rowl + 16 * it) + e, hi - 1);
                 const uint16_t *vrow = (fresh && x == p.t_in) ? v_new + static_cast<size_t>(bh) * D
                                                               : Vt + (static_cast<size_t>(bh) * p.cap + x) * D;
                 vb[it][e] = *(reinterpret_cast<const u32x4 *>(vrow) + cs);
-                if (fresh && x == p.t_in && xr == x)      // keep the cache up to date
-                    *(reinterpret_cast<u32x4 *>(Vt + (static_cast<size_t>(bh) * p.cap + x) * D) + cs) = vb[it][e];
             }
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
-            const int xr = lo + 32 * wave + 16 * tt + r16, x = min(xr, hi - 1);
+            const int x = min(lo + 32 * wave + 16 * tt + r16, hi - 1);
             const uint16_t *krow = (fresh && x == p.t_in) ? k_new + static_cast<size_t>(bh) * D
                                                           : Kt + (static_cast<size_t>(bh) * p.cap + x) * D;
             const u32x4 *kp = reinterpret_cast<const u32x4 *>(krow) + kg;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) kf[tt][ks] = kp[4 * ks];
-            if (fresh && x == p.t_in && xr == x) {
-                u32x4 *kd = reinterpret_cast<u32x4 *>(Kt + (static_cast<size_t>(bh) * p.cap + x) * D) + kg;
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) kd[4 * ks] = kf[tt][ks];
-            }
         }
         {
             const u32x4 *qp = reinterpret_cast<const u32x4 *>(q + (static_cast<size_t>(b) * p.Hq + h * G + min(r16, G - 1)) * D) + kg;
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) qf[ks] = qp[4 * ks];
         }
-        // logits of the two tiles -> LDS
+        TS(0, 1);
+        // logits: lane (head r16, rows 32 wave + 16 tt + 4 kg + e) keeps 8 of them
+        f32x4 sc[2];
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks)
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[tt][ks]), as_bf16x8(qf[ks]), acc, 0, 0, 0);
-            *reinterpret_cast<f32x4 *>(&sS[r16][32 * wave + 16 * tt + 4 * kg]) =
-                f32x4_mk(acc[0] * p.scale, acc[1] * p.scale, acc[2] * p.scale, acc[3] * p.scale);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                sc[tt][e] = (lo + 32 * wave + 16 * tt + 4 * kg + e < hi) ? acc[e] * p.scale : -INFINITY;
         }
+        float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
+                         fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        if (kg == 0) sRed[0][wave][r16] = mx;
         // value rows -> LDS transposed: rows (x, x+1) of channel c share one 32-bit word
 #pragma unroll
         for (int it = 0; it < kXC / 32; ++it) {
@@ -186,41 +185,25 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
             }
         }
         __syncthreads();
-        // probabilities relative to the chunk's own maximum: LPR lanes per row
-        constexpr int LPR = 256 / kXC, NGR = (G + LPR - 1) / LPR;
-        const int xl = threadIdx.x / LPR, x = lo + xl, gsub = threadIdx.x % LPR;
-        float sc[NGR];
+        TS(0, 2);
+        // probabilities relative to the chunk's own maximum, straight from the accumulator layout
+        mx = fmaxf(fmaxf(sRed[0][0][r16], sRed[0][1][r16]), fmaxf(sRed[0][2][r16], sRed[0][3][r16]));
+        float sm = 0.f;
 #pragma unroll
-        for (int k = 0; k < NGR; ++k) {
-            const int g = gsub + LPR * k;
-            sc[k] = (g < G && x < hi) ? sS[g][xl] : -INFINITY;
-        }
+        for (int tt = 0; tt < 2; ++tt) {
+            uint32_t eb[4];
 #pragma unroll
-        for (int k = 0; k < NGR; ++k) {
-            float mx = sc[k];                       // max over rows = lanes with equal (lane % LPR)
-#pragma unroll
-            for (int o = LPR; o < 64; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-            if (lane < LPR && lane + LPR * k < G) sRed[wave][lane + LPR * k][0] = mx;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < NGR; ++k) {
-            const int g = gsub + LPR * k;
-            float e = 0.f, mx = 0.f;
-            if (g < G) {
-                mx = fmaxf(fmaxf(sRed[0][g][0], sRed[1][g][0]), fmaxf(sRed[2][g][0], sRed[3][g][0]));
-                const uint32_t eb = x < hi ? f32_to_bf16_bits(__expf(sc[k] - mx)) : 0u;
-                e = __uint_as_float(eb << 16);
-                sWb[g][xl] = static_cast<uint16_t>(eb);
+            for (int e = 0; e < 4; ++e) {
+                eb[e] = f32_to_bf16_bits(__expf(sc[tt][e] - mx));       // exp(-inf) = 0 beyond the chunk
+                sm += __uint_as_float(eb[e] << 16);
             }
-            float sm = e;
-#pragma unroll
-            for (int o = LPR; o < 64; o <<= 1) sm += __shfl_xor(sm, o, 64);
-            if (lane < LPR && g < G) sRed[wave][g][1] = sm;
-            if (threadIdx.x < LPR && g < G) sMx[g] = mx;
+            *reinterpret_cast<u32x2 *>(&sWb[r16][32 * wave + 16 * tt + 4 * kg]) = u32x2_mk(eb[0] | (eb[1] << 16), eb[2] | (eb[3] << 16));
         }
-        for (int idx = threadIdx.x; idx < (16 - G) * kXC; idx += 256) sWb[G + idx / kXC][idx % kXC] = 0;
+        sm += __shfl_xor(sm, 16, 64);
+        sm += __shfl_xor(sm, 32, 64);
+        if (kg == 0) sRed[1][wave][r16] = sm;
         __syncthreads();
+        TS(0, 3);
         // out_part^T[c][g] = sum_x V^T[c][x] P[g][x]; each wave owns two 16-channel tiles
         float *yp = p.Ypart + (static_cast<size_t>(bh) * p.nparts + p.I * p.JS + xc) * p.rec;
 #pragma unroll
@@ -233,12 +216,19 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
                 const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(&sWb[r16][32 * ks + 8 * kg]);
                 o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, o, 0, 0, 0);
             }
-            if (r16 < G) *reinterpret_cast<f32x4 *>(yp + r16 * D + 16 * ct + 4 * kg) = f32x4_mk(o[0], o[1], o[2], o[3]);
+            if (r16 < G) *reinterpret_cast<f32x4 *>(yp + r16 * D + 16 * ct + 4 * kg) = o;
         }
         if (threadIdx.x < G) {
-            yp[G * D + threadIdx.x] = sMx[threadIdx.x];
-            yp[G * D + G + threadIdx.x] = sRed[0][threadIdx.x][1] + sRed[1][threadIdx.x][1] +
-                                          sRed[2][threadIdx.x][1] + sRed[3][threadIdx.x][1];
+            yp[G * D + threadIdx.x] = mx;            // lanes 0..15 of wave 0 hold the maximum of head r16
+            yp[G * D + G + threadIdx.x] = sRed[1][0][threadIdx.x] + sRed[1][1][threadIdx.x] +
+                                          sRed[1][2][threadIdx.x] + sRed[1][3][threadIdx.x];
+        }
+        // Sec. 3.2: the text cache keeps growing as in the backbone -- store the new token's k, v
+        if (fresh && p.t_in >= lo && p.t_in < hi && threadIdx.x < 32) {
+            const int half = threadIdx.x >> 4, piece = threadIdx.x & 15;
+            const uint16_t *src = (half ? v_new : k_new) + static_cast<size_t>(bh) * D;
+            uint16_t *dst = (half ? Vt : Kt) + (static_cast<size_t>(bh) * p.cap + p.t_in) * D;
+            *(reinterpret_cast<u32x4 *>(dst) + piece) = *(reinterpret_cast<const u32x4 *>(src) + piece);
         }
         TS(0, 4);
         return;
@@ -330,6 +320,7 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
     for (int k = 0; k < SB; ++k)
         sfr[k] = (wave_live && k < KS) ? *reinterpret_cast<const u32x4 *>(srow + 32 * k) : u32x4_mk(0, 0, 0, 0);
 
+    TS(1, 1);
     // ---- stage the theta chunk, transposed, in LDS -------------------------------------------------
     // a thread owns a pair of consecutive rows j, j+1 and 8 positions; the pair is packed so the
     // transposed store is one 32-bit word per position
