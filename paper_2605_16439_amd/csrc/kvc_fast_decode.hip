@@ -36,7 +36,6 @@
 //
 // Query rows of one KV head are ordered r = (b*I + i)*G + g, so the G query heads of a
 // group and consecutive image blocks share MFMA tiles.
-#include <stdlib.h>
 #include "kvc_internal.h"
 
 namespace kvc {
@@ -71,8 +70,9 @@ struct Plan {
     int UP, NT, NG, JS, NXC, nparts, rec;
     int nvis_b, b_stride, nvis_c, c_stride;
     float scale;
-    int dbg;
-    unsigned long long *dbgbuf;
+#if defined(KVC_TIMELINE)
+    unsigned long long *tl;         // timeline slots, see TS()
+#endif
     uint16_t *S;
     uint16_t *P;
     f32x2 *stats;
@@ -80,12 +80,19 @@ struct Plan {
     size_t bytes;
 };
 
-// debug timestamps: kernel id, slot
+// Developer aid, compiled in only with -DKVC_TIMELINE: thread 0 of every workgroup records the
+// wall clock at a few points of each kernel (kernel id, slot) in the last MiB of the workspace.
+#if defined(KVC_TIMELINE)
 #define TS(KID, K)                                                                        \
     do {                                                                                  \
-        if (p.dbgbuf && threadIdx.x == 0)                                                 \
-            p.dbgbuf[((KID) * 1024 + (blockIdx.x < 1024 ? blockIdx.x : 1023)) * 8 + (K)] = wall_clock64(); \
+        if (p.tl && threadIdx.x == 0)                                                     \
+            p.tl[((KID) * 1024 + (blockIdx.x < 1024 ? blockIdx.x : 1023)) * 8 + (K)] = wall_clock64(); \
     } while (0)
+constexpr size_t kTimelineBytes = 1 << 20;
+#else
+#define TS(KID, K) do { } while (0)
+constexpr size_t kTimelineBytes = 0;
+#endif
 
 __host__ __device__ inline u32x4 u32x4_mk(unsigned a, unsigned b, unsigned c, unsigned d) { return u32x4{a, b, c, d}; }
 __host__ __device__ inline u32x2 u32x2_mk(unsigned a, unsigned b) { return u32x2{a, b}; }
@@ -760,7 +767,6 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.B = s.batch; p.Hq = s.n_q_heads; p.Hkv = s.n_kv_heads; p.G = p.Hq / p.Hkv;
     p.n = s.n_img_tokens; p.I = s.n_images; p.m = s.m;
     p.t = t; p.t_in = t_in; p.cap = cap; p.scale = scale;
-    { const char *e = getenv("KVC_DBG"); p.dbg = e ? atoi(e) : 0; }
     p.R = p.B * p.I * p.G;
     p.R_pad = static_cast<int>(align_up(p.R > 0 ? p.R : 1, kRB));
     p.NRB = p.I > 0 ? p.R_pad / kRB : 0;
@@ -795,57 +801,67 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.stats = reinterpret_cast<f32x2 *>(take(static_cast<size_t>(p.Hkv) * p.R_pad * p.NC * 8));
     p.Ypart = reinterpret_cast<float *>(take(static_cast<size_t>(p.B) * p.Hkv * (p.I * p.JS + nxc_max) * p.rec * 4));
     p.bytes = off;
-    p.dbgbuf = nullptr;
+#if defined(KVC_TIMELINE)
+    p.tl = nullptr;
+#endif
     return p;
 }
 
-template <int G> void launch_a(const Plan &p, const DecodeCall &c)
+// Raises a kernel's dynamic-LDS limit once per device (the attribute is per device); a failure is
+// left for the launch that follows to report.
+constexpr int kMaxDevices = 64;
+bool allow_lds(const void *fn, size_t bytes, bool *done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+    if (done[dev]) return true;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes)) != hipSuccess) return false;
+    done[dev] = true;
+    return true;
+}
+
+template <int G> bool launch_a(const Plan &p, const DecodeCall &c)
 {
     fa_scores<G><<<p.nvis_a + p.B * p.Hkv * p.NXC, 256, 0, c.stream>>>(
         p, static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc),
         static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt),
         static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new));
+    return true;
 }
 
-template <int G, int UP, int NT, int NC> void launch_c3(const Plan &p, const DecodeCall &c)
+template <int G, int UP, int NT, int NC> bool launch_c3(const Plan &p, const DecodeCall &c)
 {
     const size_t lds = lds_c(NC * kPC, NT, KSplit<NC>::UCH);
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(fc_fused<G, UP, NT, NC>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        attr_set = true;
-    }
+    static bool attr_set[kMaxDevices] = {};
+    if (!allow_lds(reinterpret_cast<const void *>(fc_fused<G, UP, NT, NC>), lds, attr_set)) return false;
     fc_fused<G, UP, NT, NC><<<p.nvis_c, 512, lds, c.stream>>>(p, static_cast<const uint16_t *>(c.U),
                                                              static_cast<const uint16_t *>(c.Vc));
+    return true;
 }
 
-template <int G, int UP, int NT> void launch_c2(const Plan &p, const DecodeCall &c)
+template <int G, int UP, int NT> bool launch_c2(const Plan &p, const DecodeCall &c)
 {
     switch (p.NC) {
-    case 16: launch_c3<G, UP, NT, 16>(p, c); break;
-    case 9: launch_c3<G, UP, NT, 9>(p, c); break;
-    default: launch_c3<G, UP, NT, 4>(p, c); break;
+    case 16: return launch_c3<G, UP, NT, 16>(p, c);
+    case 9: return launch_c3<G, UP, NT, 9>(p, c);
+    default: return launch_c3<G, UP, NT, 4>(p, c);
     }
 }
 
-template <int G, int UP> void launch_ac(const Plan &p, const DecodeCall &c, bool first)
+template <int G, int UP> bool launch_ac(const Plan &p, const DecodeCall &c, bool first)
 {
-    if (first) {
-        launch_a<G>(p, c);
-    } else if (p.nvis_c > 0) {
-        if (p.NT == 2) launch_c2<G, UP, 2>(p, c);
-        else launch_c2<G, UP, 1>(p, c);
-    }
+    if (first) return launch_a<G>(p, c);
+    if (p.nvis_c == 0) return true;
+    return p.NT == 2 ? launch_c2<G, UP, 2>(p, c) : launch_c2<G, UP, 1>(p, c);
 }
 
-void launch_for_group(const Plan &p, const DecodeCall &c, bool first)
+bool launch_for_group(const Plan &p, const DecodeCall &c, bool first)
 {
     switch (p.G) {
-    case 1: launch_ac<1, 16>(p, c, first); break;
-    case 4: launch_ac<4, 4>(p, c, first); break;
-    case 7: launch_ac<7, 2>(p, c, first); break;
-    default: launch_ac<8, 2>(p, c, first); break;
+    case 1: return launch_ac<1, 16>(p, c, first);
+    case 4: return launch_ac<4, 4>(p, c, first);
+    case 7: return launch_ac<7, 2>(p, c, first);
+    default: return launch_ac<8, 2>(p, c, first);
     }
 }
 
@@ -862,7 +878,7 @@ bool fast_decode_supported(const kvc_shape &s)
 
 size_t fast_decode_ws_bytes(const kvc_shape &s, int32_t max_text)
 {
-    return make_plan(s, max_text, max_text, max_text, 1.f, nullptr).bytes + (1 << 20);
+    return make_plan(s, max_text, max_text, max_text, 1.f, nullptr).bytes + kTimelineBytes;
 }
 
 kvc_status fast_decode(const DecodeCall &c)
@@ -870,22 +886,18 @@ kvc_status fast_decode(const DecodeCall &c)
     Plan p = make_plan(c.s, c.t, c.t_in, c.cap, c.scale, c.ws);
     if (p.nparts > kMaxParts) return generic_decode(c);
     if (p.bytes > c.ws_bytes) return KVC_ERR_WORKSPACE;
-    p.dbgbuf = (p.dbg & 256) && c.ws_bytes >= p.bytes + (1 << 20)
-                   ? reinterpret_cast<unsigned long long *>(static_cast<char *>(c.ws) + ((c.ws_bytes - (1 << 20)) & ~size_t(255)))
-                   : nullptr;
-    launch_for_group(p, c, true);
+#if defined(KVC_TIMELINE)
+    p.tl = c.ws_bytes >= p.bytes + kTimelineBytes
+               ? reinterpret_cast<unsigned long long *>(static_cast<char *>(c.ws) + ((c.ws_bytes - kTimelineBytes) & ~size_t(255)))
+               : nullptr;
+#endif
+    if (!launch_for_group(p, c, true)) return KVC_ERR_HIP;
     if (p.nvis_b > 0) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(fb_probs),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    static_cast<int>(kLdsBudget)) != hipSuccess)
-                return KVC_ERR_HIP;
-            attr_set = true;
-        }
+        static bool attr_set[kMaxDevices] = {};
+        if (!allow_lds(reinterpret_cast<const void *>(fb_probs), kLdsBudget, attr_set)) return KVC_ERR_HIP;
         fb_probs<<<p.nvis_b, 256, lds_b(p.m_pad), c.stream>>>(p, static_cast<const uint16_t *>(c.theta));
     }
-    launch_for_group(p, c, false);
+    if (!launch_for_group(p, c, false)) return KVC_ERR_HIP;
     fd_finalize<<<p.B * p.Hq, 128, 0, c.stream>>>(p, static_cast<const uint16_t *>(c.mu),
                                                   static_cast<uint16_t *>(c.out), c.lse);
     return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
