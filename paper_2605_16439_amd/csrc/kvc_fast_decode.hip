@@ -297,6 +297,7 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
 // MFMA tile: A = theta^T (16 positions x 32 j) from LDS, B = S^T (32 j x 16 rows) from
 // memory, D[pos][row]: a lane ends up with 4 consecutive positions of one row.
 // ------------------------------------------------------------------------------------------
+template <int KS4>
 __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restrict__ theta)
 {
     extern __shared__ __align__(16) uint16_t lds[];
@@ -320,12 +321,16 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
     const bool wave_live = r0 < p.R;
     const int r = r0 + r16;
     const uint16_t *srow = p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + 8 * kg;
+    // KS = m_pad / 32 k-steps of 32 compressed positions, handled as KS4 groups of four without any
+    // test inside the loops: a step beyond KS multiplies a re-read theta fragment by a zero fragment
     const int KS = p.m_pad / 32;
-    constexpr int SB = 20;                       // m <= 640: every fragment in one batch
+    constexpr int SB = 4 * KS4;
     u32x4 sfr[SB];
 #pragma unroll
-    for (int k = 0; k < SB; ++k)
-        sfr[k] = (wave_live && k < KS) ? *reinterpret_cast<const u32x4 *>(srow + 32 * k) : u32x4_mk(0, 0, 0, 0);
+    for (int k = 0; k < SB; ++k) {
+        sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * min(k, KS - 1));
+        if (k >= KS || !wave_live) sfr[k] = u32x4_mk(0, 0, 0, 0);
+    }
 
     TS(1, 1);
     // ---- stage the theta chunk, transposed, in LDS -------------------------------------------------
@@ -335,29 +340,28 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
     const int jp = (lane & 15) + 16 * (wave >> 1);         // row pair within a pass of 64 rows
     {
         const uint16_t *th = theta + static_cast<size_t>(h) * p.m * p.n + pc * PC + 8 * seg;
-        constexpr int FB = 10;                   // passes per batch: m <= 640 is one batch
-        for (int j0 = 2 * jp; j0 < p.m16; j0 += 64 * FB) {
-            u32x4 tv[FB][2];
+        constexpr int FB = 2 * KS4;              // passes of 64 rows: 64 FB >= m_pad, all in one batch
+        const int j0 = 2 * jp;
+        u32x4 tv[FB][2];
 #pragma unroll
-            for (int k = 0; k < FB; ++k)
+        for (int k = 0; k < FB; ++k)
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const int j = j0 + 64 * k + e;
-                    tv[k][e] = u32x4_mk(0, 0, 0, 0);
-                    if (j < p.m) tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(j) * p.n);
-                }
+            for (int e = 0; e < 2; ++e) {
+                const int j = j0 + 64 * k + e;               // rows beyond m are clamped, then zeroed
+                tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(min(j, p.m - 1)) * p.n);
+                if (j >= p.m) tv[k][e] = u32x4_mk(0, 0, 0, 0);
+            }
 #pragma unroll
-            for (int k = 0; k < FB; ++k) {
-                const int j = j0 + 64 * k;
-                if (j < p.m16) {
-                    const uint32_t a[4] = {tv[k][0].x, tv[k][0].y, tv[k][0].z, tv[k][0].w};
-                    const uint32_t c[4] = {tv[k][1].x, tv[k][1].y, tv[k][1].z, tv[k][1].w};
-                    uint32_t *dst = reinterpret_cast<uint32_t *>(ThT + (8 * seg) * LDT + j);
+        for (int k = 0; k < FB; ++k) {
+            const int j = j0 + 64 * k;
+            if (j < p.m16) {
+                const uint32_t a[4] = {tv[k][0].x, tv[k][0].y, tv[k][0].z, tv[k][0].w};
+                const uint32_t c[4] = {tv[k][1].x, tv[k][1].y, tv[k][1].z, tv[k][1].w};
+                uint32_t *dst = reinterpret_cast<uint32_t *>(ThT + (8 * seg) * LDT + j);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        dst[(2 * e) * (LDT / 2)] = (a[e] & 0xffffu) | (c[e] << 16);
-                        dst[(2 * e + 1) * (LDT / 2)] = (a[e] >> 16) | (c[e] & 0xffff0000u);
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    dst[(2 * e) * (LDT / 2)] = (a[e] & 0xffffu) | (c[e] << 16);
+                    dst[(2 * e + 1) * (LDT / 2)] = (a[e] >> 16) | (c[e] & 0xffff0000u);
                 }
             }
         }
@@ -375,25 +379,15 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
     f32x4 acc[PC / 16];
 #pragma unroll
     for (int mt = 0; mt < PC / 16; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int ks0 = 0; ks0 < KS; ks0 += SB) {
-        u32x4 cur[SB];
 #pragma unroll
-        for (int k = 0; k < SB; ++k) cur[k] = sfr[k];
+    for (int k = 0; k < SB; ++k) {
+        const int ks = min(k, KS - 1);
+        // scores beyond the compressed length are zeros written by fa_scores
+        const bf16x8 bfrag = as_bf16x8(sfr[k]);
 #pragma unroll
-        for (int k = 0; k < SB; ++k)
-            if (ks0 + SB + k < KS) sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * (ks0 + SB + k));
-#pragma unroll
-        for (int k = 0; k < SB; ++k) {
-            const int ks = ks0 + k;
-            if (ks < KS) {
-                // scores beyond the compressed length are zeros written by fa_scores
-                const bf16x8 bfrag = as_bf16x8(cur[k]);
-#pragma unroll
-                for (int mt = 0; mt < PC / 16; ++mt) {
-                    const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(ThT + (16 * mt + r16) * LDT + 32 * ks + 8 * kg);
-                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[mt], 0, 0, 0);
-                }
-            }
+        for (int mt = 0; mt < PC / 16; ++mt) {
+            const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(ThT + (16 * mt + r16) * LDT + 32 * ks + 8 * kg);
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[mt], 0, 0, 0);
         }
     }
 
@@ -736,8 +730,8 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
             for (int k = 0; k < PB; ++k) v[k] = yc[static_cast<size_t>(min(pt0 + PB + k, p.nparts - 1)) * rec];
         }
 #pragma unroll
-        for (int k = 0; k < PB; ++k)
-            if (pt0 + k < p.nparts) y += sSc[pt0 + k] * cur[k];
+        for (int k = 0; k < PB; ++k)          // parts beyond the last were loaded clamped: weight zero
+            y += (pt0 + k < p.nparts ? sSc[min(pt0 + k, kMaxParts - 1)] : 0.f) * cur[k];
     }
     y += (zv / z) * bf_lo(mu[static_cast<size_t>(h) * D + c]);
     out[static_cast<size_t>(bg) * D + c] = f32_to_bf16_bits(y);
@@ -820,6 +814,29 @@ bool allow_lds(const void *fn, size_t bytes, bool *done)
     return true;
 }
 
+template <int KS4> bool launch_b1(const Plan &p, const DecodeCall &c)
+{
+    static bool attr_set[kMaxDevices] = {};
+    if (!allow_lds(reinterpret_cast<const void *>(fb_probs<KS4>), kLdsBudget, attr_set)) return false;
+    fb_probs<KS4><<<p.nvis_b, 256, lds_b(p.m_pad), c.stream>>>(p, static_cast<const uint16_t *>(c.theta));
+    return true;
+}
+
+bool launch_b(const Plan &p, const DecodeCall &c)
+{
+    switch ((p.m_pad / 32 + 3) / 4) {      // m <= n <= 1024: at most 8 groups of four k-steps
+    case 1: return launch_b1<1>(p, c);
+    case 2: return launch_b1<2>(p, c);
+    case 3: return launch_b1<3>(p, c);
+    case 4: return launch_b1<4>(p, c);
+    case 5: return launch_b1<5>(p, c);
+    case 6: return launch_b1<6>(p, c);
+    case 7: return launch_b1<7>(p, c);
+    case 8: return launch_b1<8>(p, c);
+    default: return false;
+    }
+}
+
 template <int G> bool launch_a(const Plan &p, const DecodeCall &c)
 {
     fa_scores<G><<<p.nvis_a + p.B * p.Hkv * p.NXC, 256, 0, c.stream>>>(
@@ -893,9 +910,7 @@ kvc_status fast_decode(const DecodeCall &c)
 #endif
     if (!launch_for_group(p, c, true)) return KVC_ERR_HIP;
     if (p.nvis_b > 0) {
-        static bool attr_set[kMaxDevices] = {};
-        if (!allow_lds(reinterpret_cast<const void *>(fb_probs), kLdsBudget, attr_set)) return KVC_ERR_HIP;
-        fb_probs<<<p.nvis_b, 256, lds_b(p.m_pad), c.stream>>>(p, static_cast<const uint16_t *>(c.theta));
+        if (!launch_b(p, c)) return KVC_ERR_HIP;
     }
     if (!launch_for_group(p, c, false)) return KVC_ERR_HIP;
     fd_finalize<<<p.B * p.Hq, 128, 0, c.stream>>>(p, static_cast<const uint16_t *>(c.mu),
