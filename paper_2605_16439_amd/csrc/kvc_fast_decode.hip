@@ -524,8 +524,10 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
                 // blocks beyond the record are clamped: their weights in W are zero
+                // (a record shorter than one block has no complete block: read its first 16 bytes)
                 const int jb = min(jb0 + 4 * ks + kg, max(nfull - 1, 0));
-                dst[a][ks] = *reinterpret_cast<const u32x4 *>(vbase + static_cast<size_t>(jb) * 8 * D + cch * 8);
+                const size_t voff = nfull > 0 ? static_cast<size_t>(jb) * 8 * D + cch * 8 : 0;
+                dst[a][ks] = *reinterpret_cast<const u32x4 *>(vbase + voff);
             }
             if (nfull == 0) { dst[a][0] = u32x4_mk(0, 0, 0, 0); dst[a][1] = u32x4_mk(0, 0, 0, 0); }
             if (has_tail) {                              // [D][wtail] block, element granular

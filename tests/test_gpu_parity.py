@@ -258,3 +258,81 @@ def test_repeat_calls_are_deterministic_and_workspace_is_reusable():
     L.ws.fill_(0xFF)                       # stale workspace contents must not matter
     b, _ = L.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
     assert np.array_equal(a, b)
+
+
+# ---- matrix-core path (bf16, head_dim 128, n in {256, 576, 1024}) at small sizes -----------------
+FAST = synth.Workload("fast_small", 20, 1, 2, 14, 2, 128, "bf16", 256, 3, 0.6, 40, 3)
+
+
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (8, 2), (14, 2), (16, 2)])
+def test_fast_path_group_sizes(hq, hkv):
+    """Every compiled group size G = H_q / H_kv (1, 4, 7, 8), ragged row tiles included."""
+    w = FAST.with_(name=f"fast_g{hq // hkv}", index=20 + hq, n_q_heads=hq, n_kv_heads=hkv, batch=3)
+    m = orc.compressed_len(w.n_img_tokens, w.compression)
+    assert kv.lib().kvc_workspace_bytes is not None
+    check_layer(w, m, pre=5, post=3, steps=(0, 2))
+
+
+@pytest.mark.parametrize("m", [1, 7, 26, 64, 200, 256])
+def test_fast_path_compressed_lengths(m):
+    """One retained row, a single short slice, a slice boundary, a ragged tail, and m = n."""
+    w = FAST.with_(name=f"fast_m{m}", index=40)
+    check_layer(w, m, steps=(0,))
+
+
+def test_fast_path_single_image_no_text_yet():
+    """I = 1 and an empty text cache: the first decode step attends the capsule and its own token."""
+    w = FAST.with_(name="fast_i1_t0", index=41, n_images=1, text_len=0, batch=1, n_img_tokens=576)
+    check_layer(w, orc.compressed_len(576, 0.6), steps=(0, 1, 2))
+
+
+def test_fast_path_many_text_chunks():
+    """Text longer than several 128-row chunks, ending in a ragged one that grows over a boundary."""
+    w = FAST.with_(name="fast_longtext", index=42, text_len=383, steps=3)
+    check_layer(w, 103, steps=(0, 1, 2))
+
+
+def test_fast_path_deterministic_with_stale_workspace():
+    w = FAST.with_(index=43)
+    L = Layer(w, 103)
+    L.compress()
+    q, kn, vn = synth.make_step_inputs(w, 0, 0)
+    a, la = L.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
+    L.ws.fill_(0xFF)
+    b, lb = L.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
+    assert np.array_equal(a, b) and np.array_equal(la, lb)
+
+
+def test_pyramid_schedule_mixed_lengths_share_one_workspace():
+    """Sec. 3.2 (pyramid budgets): layers of one decode step carry different compressed lengths.
+    Three layers with m = 154 / 103 / 52 use one workspace sized for the largest; calls of the
+    layers interleave as in a decode step."""
+    w = FAST.with_(name="fast_pyramid", index=44, layers=3)
+    ms = [orc.compressed_len(w.n_img_tokens, c) for c in (0.4, 0.6, 0.8)]
+    assert ms == [154, 103, 52]
+    Ls = [Layer(w, m, layer=l) for l, m in enumerate(ms)]
+    big = max(Ls, key=lambda L: L.ws.numel())
+    for L in Ls:
+        L.ws = big.ws
+        L.compress()
+    refs = []
+    for L in Ls:
+        Kc_ref, Vc_ref = orc.compress(f64(L.K), f64(L.V), L.p["key_idx"].numpy(), f64(L.p["U"]),
+                                      f64(L.p["mu"]), w.n_img_tokens, w.n_images, 0, store_code(w))
+        assert np.array_equal(f64(L.gKc), Kc_ref)
+        Kh, Vh = orc.reconstruct(Kc_ref, Vc_ref, f64(L.p["theta"]), f64(L.p["U"]), f64(L.p["mu"]),
+                                 w.n_img_tokens)
+        refs.append((Kh, Vh, f64(L.Kt).copy(), f64(L.Vt).copy()))
+    t = w.text_len
+    for step in range(2):
+        for l, L in enumerate(Ls):
+            q, kn, vn = synth.make_step_inputs(w, l, step)
+            out, _ = L.decode(q.to(DEV), t, kn.to(DEV), vn.to(DEV))
+            Kh, Vh, Kt, Vt = refs[l]
+            Kt[:, :, t] = f64(kn)
+            Vt[:, :, t] = f64(vn)
+            ref, _ = orc.attend(f64(q), Kh, Vh, Kt, Vt, t + 1, None)
+            e = row_rel_err(out, ref)
+            _say(f"[parity] pyramid step {step} layer {l} m={ms[l]}: {e:.3e}")
+            assert e <= tol(w)
+        t += 1
