@@ -21,15 +21,18 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
-constexpr int kJT = 64;        // rows j per workgroup
+constexpr int kGJ = 64;        // key rows per gather workgroup
 constexpr int kKT = 64;        // positions per LDS tile
 constexpr int kLD = kKT + 8;   // padded row of the transposed V tile (bf16 elements)
+constexpr int kMaxMT = 4;      // 16-row tiles of U per wavefront, at most
 
 struct CPlan {
     int B, Hkv, n, I, m, vis0;
-    int JT, nproj, ngather;
+    int tiles, TPW, JT;         // 16-row tiles of U, tiles per workgroup, workgroups per image block
+    int GJT, nproj, ngather;
     int64_t sb, sh, ss;
 };
 
@@ -39,6 +42,9 @@ __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, 
 // are XOR-swizzled with the channel group so the transposing stores spread over the banks
 __device__ inline int sv_index(int c, int p) { return c * kLD + ((((p >> 3) ^ (c >> 3)) & 7) << 3) + (p & 7); }
 
+// MT = tiles per wavefront: a workgroup covers up to 64 MT rows of U, so V is read
+// ceil(m / (64 MT)) times per image block and every LDS fragment of V feeds MT MFMAs.
+template <int MT>
 __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__restrict__ K,
                                                    const uint16_t *__restrict__ V,
                                                    const int32_t *__restrict__ idx,
@@ -54,7 +60,7 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
     if (static_cast<int>(blockIdx.x) >= p.nproj) {
         // ---------------- keys: Kc[u][j][:] = K[b,h, vis0 + i n + M[j], :] ----------------
         const int id = blockIdx.x - p.nproj;
-        const int u = id / p.JT, jt = id - u * p.JT;
+        const int u = id / p.GJT, jt = id - u * p.GJT;
         const int bh = u / p.I, i = u - bh * p.I;
         const int b = bh / p.Hkv, h = bh - b * p.Hkv;
         const uint16_t *src = K + b * p.sb + h * p.sh + (static_cast<int64_t>(p.vis0) + static_cast<int64_t>(i) * p.n) * p.ss;
@@ -64,7 +70,7 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
         int jj[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            jj[q] = jt * kJT + 16 * q + rl;
+            jj[q] = jt * kGJ + 16 * q + rl;
             const int j = min(jj[q], p.m - 1);
             v[q] = *(reinterpret_cast<const uint4 *>(src + static_cast<int64_t>(idx[j]) * p.ss) + cs);
         }
@@ -74,39 +80,53 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
         return;
     }
 
-    // ---------------- values: 64 rows j of one image block ----------------
+    // ---------------- values: up to 4 MT tiles of 16 rows j of one image block ----------------
     const int u = blockIdx.x / p.JT, jt = blockIdx.x - u * p.JT;
     const int bh = u / p.I, i = u - bh * p.I;
     const int b = bh / p.Hkv, h = bh - b * p.Hkv;
-    const int j0 = jt * kJT + wave * 16;
-    const bool wave_live = j0 < p.m;
-    const uint16_t *urow = U + (static_cast<size_t>(h) * p.m + min(j0 + r16, p.m - 1)) * p.n + 8 * kg;
+    const int tile0 = jt * p.TPW, ntile = min(p.TPW, p.tiles - tile0);
+    // tile q of this wave is tile0 + wave + 4 q; a tile beyond the workgroup's share repeats the
+    // last row of U and its result is dropped, so the main loop carries no tests
+    int j0[MT];
+    const uint16_t *urow[MT];
+#pragma unroll
+    for (int q = 0; q < MT; ++q) {
+        j0[q] = 16 * (tile0 + wave + 4 * q);
+        urow[q] = U + (static_cast<size_t>(h) * p.m + min(j0[q] + r16, p.m - 1)) * p.n + 8 * kg;
+    }
     const uint16_t *vsrc = V + b * p.sb + h * p.sh + (static_cast<int64_t>(p.vis0) + static_cast<int64_t>(i) * p.n) * p.ss;
     // V tile loads: item = (pair of positions, 8 channels); 512 items, two per thread
     const int pair0 = threadIdx.x >> 4, cs = threadIdx.x & 15;      // second item: pair0 + 16
 
-    f32x4 acc[8], accs = {0.f, 0.f, 0.f, 0.f};
+    f32x4 acc[MT][8], accs[MT];
 #pragma unroll
-    for (int nt = 0; nt < 8; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < MT; ++q) {
+        accs[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) acc[q][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
     const uint32_t one2 = 0x3f803f80u;
     const bf16x8 ones = as_bf16x8(make_uint4(one2, one2, one2, one2));
 
-    uint4 va[2][2], ua[2];
-    auto load_tile = [&](int kt) {
+    // Three register stages rotate by name (the loop is unrolled by three): a tile's loads are
+    // issued two iterations before it is multiplied, and nothing is copied between stages.
+    u32x4 vaA[2][2], uaA[MT][2], vaB[2][2], uaB[MT][2], vaC[2][2], uaC[MT][2];
+    auto load_tile = [&](int kt, u32x4 (&va)[2][2], u32x4 (&ua)[MT][2]) {
 #pragma unroll
         for (int q = 0; q < 2; ++q)
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
                 const int pp = kt * kKT + 2 * (pair0 + 16 * q) + e;
-                va[q][e] = *(reinterpret_cast<const uint4 *>(vsrc + static_cast<int64_t>(pp) * p.ss) + cs);
+                va[q][e] = *(reinterpret_cast<const u32x4 *>(vsrc + static_cast<int64_t>(pp) * p.ss) + cs);
             }
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-            ua[ks] = wave_live ? *reinterpret_cast<const uint4 *>(urow + kt * kKT + 32 * ks) : make_uint4(0, 0, 0, 0);
+        for (int q = 0; q < MT; ++q)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                ua[q][ks] = *reinterpret_cast<const u32x4 *>(urow[q] + kt * kKT + 32 * ks);
     };
-    load_tile(0);
     const int NK = p.n / kKT;
-    for (int kt = 0; kt < NK; ++kt) {
+    auto step = [&](int kt, u32x4 (&va)[2][2], u32x4 (&ua)[MT][2]) {
         uint16_t *buf = sVt[kt & 1];
         // transposed store: positions (2 pair, 2 pair + 1) of channel c share one 32-bit word
 #pragma unroll
@@ -120,45 +140,67 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
                 *reinterpret_cast<uint32_t *>(buf + sv_index(8 * cs + 2 * e + 1, pl)) = (a[e] >> 16) | (c2[e] & 0xffff0000u);
             }
         }
-        const uint4 u0 = ua[0], u1 = ua[1];
         __syncthreads();
-        if (kt + 1 < NK) load_tile(kt + 1);
-        if (wave_live) {
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                const bf16x8 afrag = as_bf16x8(ks == 0 ? u0 : u1);
+        for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
-                for (int nt = 0; nt < 8; ++nt) {
-                    const int c = 16 * nt + r16;
-                    const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(buf + sv_index(c, 32 * ks + 8 * kg));
-                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[nt], 0, 0, 0);
-                }
-                accs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, ones, accs, 0, 0, 0);
+            for (int nt = 0; nt < 8; ++nt) {
+                const int c = 16 * nt + r16;
+                const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(buf + sv_index(c, 32 * ks + 8 * kg));
+#pragma unroll
+                for (int q = 0; q < MT; ++q)
+                    acc[q][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ua[q][ks]), bfrag, acc[q][nt], 0, 0, 0);
             }
+#pragma unroll
+            for (int q = 0; q < MT; ++q)
+                accs[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ua[q][ks]), ones, accs[q], 0, 0, 0);
         }
+        load_tile(min(kt + 3, NK - 1), va, ua);          // past the end: the last tile again, unused
+    };
+    load_tile(0, vaA, uaA);
+    load_tile(min(1, NK - 1), vaB, uaB);
+    load_tile(min(2, NK - 1), vaC, uaC);
+    int kt = 0;
+    for (; kt + 3 <= NK; kt += 3) {                      // no tests inside the loop body
+        step(kt, vaA, uaA);
+        step(kt + 1, vaB, uaB);
+        step(kt + 2, vaC, uaC);
     }
-    if (!wave_live) return;
+    if (kt < NK) step(kt, vaA, uaA);
+    if (kt + 1 < NK) step(kt + 1, vaB, uaB);
 
     // ---- epilogue: centre, round once, store in the blocked layout -----------------------------------
     // lane holds rows j = j0 + 4 kg + e (e = 0..3) of channel c = 16 nt + r16; accs[e] = sum_p U[j][p]
-    const int jb = (j0 + 4 * kg) >> 3, jr = (j0 + 4 * kg) & 7;
-    const int w = min(8, p.m - 8 * jb);                     // width of the block these rows sit in
-    uint16_t *vout = Vc + static_cast<size_t>(u) * p.m * D + static_cast<size_t>(jb) * 8 * D;
 #pragma unroll
-    for (int nt = 0; nt < 8; ++nt) {
-        const int c = 16 * nt + r16;
-        const float muc = __uint_as_float(static_cast<uint32_t>(mu[static_cast<size_t>(h) * D + c]) << 16);
-        uint32_t o[4];
+    for (int q = 0; q < MT; ++q) {
+        if (wave + 4 * q >= ntile) continue;
+        const int jb = (j0[q] + 4 * kg) >> 3, jr = (j0[q] + 4 * kg) & 7;
+        const int w = min(8, p.m - 8 * jb);                     // width of the block these rows sit in
+        uint16_t *vout = Vc + static_cast<size_t>(u) * p.m * D + static_cast<size_t>(jb) * 8 * D;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_bits(acc[nt][e] - accs[e] * muc);
-        if (w == 8) {
-            *reinterpret_cast<uint2 *>(vout + c * 8 + jr) = make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
-        } else if (w > 0) {
+        for (int nt = 0; nt < 8; ++nt) {
+            const int c = 16 * nt + r16;
+            const float muc = __uint_as_float(static_cast<uint32_t>(mu[static_cast<size_t>(h) * D + c]) << 16);
+            uint32_t o[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (jr + e < w) vout[c * w + jr + e] = static_cast<uint16_t>(o[e]);
+            for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_bits(acc[q][nt][e] - accs[q][e] * muc);
+            if (w == 8) {
+                *reinterpret_cast<uint2 *>(vout + c * 8 + jr) = make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
+            } else if (w > 0) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (jr + e < w) vout[c * w + jr + e] = static_cast<uint16_t>(o[e]);
+            }
         }
     }
+}
+
+template <int MT> void launch(const CPlan &p, const CompressCall &c)
+{
+    fk_compress<MT><<<p.nproj + p.ngather, 256, 0, c.stream>>>(
+        p, static_cast<const uint16_t *>(c.K), static_cast<const uint16_t *>(c.V), c.key_idx,
+        static_cast<const uint16_t *>(c.U), static_cast<const uint16_t *>(c.mu),
+        static_cast<uint16_t *>(c.Kc), static_cast<uint16_t *>(c.Vc));
 }
 
 }  // namespace
@@ -177,14 +219,21 @@ kvc_status fast_compress(const CompressCall &c)
     CPlan p;
     p.B = s.batch; p.Hkv = s.n_kv_heads; p.n = s.n_img_tokens; p.I = s.n_images; p.m = s.m;
     p.vis0 = c.vis_start;
-    p.JT = (s.m + kJT - 1) / kJT;
-    p.nproj = p.B * p.Hkv * p.I * p.JT;
-    p.ngather = p.nproj;
+    // the 16-row tiles of U are shared out evenly over as few workgroups as 4 waves x kMaxMT allow
+    p.tiles = (s.m + 15) / 16;
+    p.JT = (p.tiles + 4 * kMaxMT - 1) / (4 * kMaxMT);
+    p.TPW = (p.tiles + p.JT - 1) / p.JT;
+    p.GJT = (s.m + kGJ - 1) / kGJ;
+    const int units = p.B * p.Hkv * p.I;
+    p.nproj = units * p.JT;
+    p.ngather = units * p.GJT;
     p.sb = c.stride_b; p.sh = c.stride_h; p.ss = c.stride_s;
-    fk_compress<<<p.nproj + p.ngather, 256, 0, c.stream>>>(
-        p, static_cast<const uint16_t *>(c.K), static_cast<const uint16_t *>(c.V), c.key_idx,
-        static_cast<const uint16_t *>(c.U), static_cast<const uint16_t *>(c.mu),
-        static_cast<uint16_t *>(c.Kc), static_cast<uint16_t *>(c.Vc));
+    switch ((p.TPW + 3) / 4) {
+    case 1: launch<1>(p, c); break;
+    case 2: launch<2>(p, c); break;
+    case 3: launch<3>(p, c); break;
+    default: launch<4>(p, c); break;
+    }
     return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
 }
 

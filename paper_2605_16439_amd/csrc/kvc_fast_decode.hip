@@ -491,22 +491,23 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
     // row of one tile, 8 rows per instruction; all steps stay in flight
     const int c_begin = kh ? KH0 : 0;
     const int nstep = kh ? (NC - KH0) / UCH : NSTEP;
+    // Only the first step's rows are requested here; the next step and the compressed values follow
+    // once the matrix work has started, so that the loads of one wave overlap the MFMAs of the other
+    // wave on its SIMD instead of holding up the instruction stream in front of them.
     u32x4 ul[NSTEP][2 * UCH];
-    {
-        const int row = min(lo + 16 * jt + (lane >> 3), p.m - 1), row8 = min(lo + 16 * jt + 8 + (lane >> 3), p.m - 1);
-        const uint16_t *u0 = U + (static_cast<size_t>(h) * p.m + row) * n + c_begin * kPC + 8 * (lane & 7);
-        const uint16_t *u8 = U + (static_cast<size_t>(h) * p.m + row8) * n + c_begin * kPC + 8 * (lane & 7);
+    const int urow0 = min(lo + 16 * jt + (lane >> 3), p.m - 1), urow8 = min(lo + 16 * jt + 8 + (lane >> 3), p.m - 1);
+    const uint16_t *u0 = U + (static_cast<size_t>(h) * p.m + urow0) * n + c_begin * kPC + 8 * (lane & 7);
+    const uint16_t *u8 = U + (static_cast<size_t>(h) * p.m + urow8) * n + c_begin * kPC + 8 * (lane & 7);
+    auto load_u = [&](int step) {
+        // a step the shorter k-half does not have re-reads its last tile; the result is not used
+        const int cs0 = min(step, nstep - 1) * UCH;
 #pragma unroll
-        for (int step = 0; step < NSTEP; ++step) {
-            // a step the shorter k-half does not have re-reads its last tile; the result is not used
-            const int cs0 = min(step, nstep - 1) * UCH;
-#pragma unroll
-            for (int ci = 0; ci < UCH; ++ci) {
-                ul[step][2 * ci] = *reinterpret_cast<const u32x4 *>(u0 + (cs0 + ci) * kPC);
-                ul[step][2 * ci + 1] = *reinterpret_cast<const u32x4 *>(u8 + (cs0 + ci) * kPC);
-            }
+        for (int ci = 0; ci < UCH; ++ci) {
+            ul[step][2 * ci] = *reinterpret_cast<const u32x4 *>(u0 + (cs0 + ci) * kPC);
+            ul[step][2 * ci + 1] = *reinterpret_cast<const u32x4 *>(u8 + (cs0 + ci) * kPC);
         }
-    }
+    };
+    load_u(0);
     // compressed values: wave w owns channels 16 w ...; the operand (8 rows j of one channel) is 16
     // contiguous bytes in the blocked layout.  Image blocks are handled in batches of UBATCH.
     constexpr int UBATCH = NU < 4 ? NU : 4;
@@ -546,7 +547,6 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
         }
     };
     u32x4 vfr[UBATCH][2];
-    load_values(0, vfr);
 
     TS(2, 1);
     // ---- block statistics: alpha[row][tile] = exp(tile max - block max) ----------------------------------
@@ -584,6 +584,8 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
         const float *al = &sAl[r16][c_begin];
 #pragma unroll
         for (int step = 0; step < NSTEP; ++step) {
+            if (step + 1 < NSTEP) load_u(step + 1);
+            if (step == NSTEP - 1) load_values(0, vfr);
             if (step < nstep) {
                 __builtin_amdgcn_wave_barrier();        // the wave is done reading the previous step
 #pragma unroll
