@@ -60,7 +60,6 @@ constexpr int kMaxParts = 256;  // fd_finalize keeps one scale per part in LDS
 constexpr int kSWLD = kXC + 8;  // padded row (bf16) of the text probabilities in LDS
 constexpr int kLDV = kXC + 8;   // padded row (bf16) of the transposed text values in LDS
 constexpr int kWLD = kJC + 8;   // padded row (bf16) of the W tile in LDS
-constexpr int kULD = kPC + 8;   // padded row (bf16) of a staged U chunk in LDS
 constexpr size_t kLdsBudget = 150 * 1024;
 
 struct Plan {
@@ -440,8 +439,7 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
     constexpr int NU = NT * UP;                          // image blocks per workgroup
     constexpr int KH0 = KSplit<NC>::KH0, UCH = KSplit<NC>::UCH;
     constexpr int NSTEP = KH0 / UCH;                     // steps of the longer k-half
-    constexpr int USTG = UCH * 16 * kULD;                // staging elements per wave
-    extern __shared__ __align__(16) uint16_t dyn[];      // P [NR][LDP], then U staging [8][UCH][16][kULD]
+    extern __shared__ __align__(16) uint16_t dyn[];      // P [NR][LDP], then the partial sums of k-half 1
     __shared__ __align__(16) uint16_t sWb[NR][kWLD];     // W tile, bf16
     __shared__ float sAl[NR][NC + 1];                    // alpha[row][tile]
     __shared__ float sMx[NR], sSm[NR];
@@ -461,7 +459,6 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
     const int nunits = min(NU, units_total - ub0);
     const int lo = s * kJC, hi = min(p.m, lo + kJC);
     uint16_t *sP = dyn;
-    uint16_t *sU = dyn + NR * LDP + wave * USTG;         // this wave's staging buffer
 
     // ---- everything this workgroup reads is requested up front, without bounds checks: -----------------
     // out-of-range rows are clamped to valid ones and their results are never stored
@@ -495,16 +492,15 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
     // once the matrix work has started, so that the loads of one wave overlap the MFMAs of the other
     // wave on its SIMD instead of holding up the instruction stream in front of them.
     u32x4 ul[NSTEP][2 * UCH];
-    const int urow0 = min(lo + 16 * jt + (lane >> 3), p.m - 1), urow8 = min(lo + 16 * jt + 8 + (lane >> 3), p.m - 1);
-    const uint16_t *u0 = U + (static_cast<size_t>(h) * p.m + urow0) * n + c_begin * kPC + 8 * (lane & 7);
-    const uint16_t *u8 = U + (static_cast<size_t>(h) * p.m + urow8) * n + c_begin * kPC + 8 * (lane & 7);
+    // rows of U as MFMA operands straight from memory: lane (r16, kg) reads 16 bytes of row r16
+    const uint16_t *ud = U + (static_cast<size_t>(h) * p.m + min(lo + 16 * jt + r16, p.m - 1)) * n + c_begin * kPC + 8 * kg;
     auto load_u = [&](int step) {
         // a step the shorter k-half does not have re-reads its last tile; the result is not used
         const int cs0 = min(step, nstep - 1) * UCH;
 #pragma unroll
         for (int ci = 0; ci < UCH; ++ci) {
-            ul[step][2 * ci] = *reinterpret_cast<const u32x4 *>(u0 + (cs0 + ci) * kPC);
-            ul[step][2 * ci + 1] = *reinterpret_cast<const u32x4 *>(u8 + (cs0 + ci) * kPC);
+            ul[step][2 * ci] = *reinterpret_cast<const u32x4 *>(ud + (cs0 + ci) * kPC);
+            ul[step][2 * ci + 1] = *reinterpret_cast<const u32x4 *>(ud + (cs0 + ci) * kPC + 32);
         }
     };
     load_u(0);
@@ -578,25 +574,16 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
     for (int t = 0; t < NT; ++t) w[t] = f32x4{0.f, 0.f, 0.f, 0.f};
     {
         const uint16_t *pb = sP + r16 * LDP + 8 * kg + c_begin * kPC;
-        // staged tile layout: [tile][row 16][kULD]; row (lane >> 3) + 8 (i & 1), 16-byte piece lane & 7
-        uint16_t *uw = sU + (lane >> 3) * kULD + 8 * (lane & 7);
-        const uint16_t *ur = sU + r16 * kULD + 8 * kg;
         const float *al = &sAl[r16][c_begin];
 #pragma unroll
         for (int step = 0; step < NSTEP; ++step) {
             if (step + 1 < NSTEP) load_u(step + 1);
             if (step == NSTEP - 1) load_values(0, vfr);
             if (step < nstep) {
-                __builtin_amdgcn_wave_barrier();        // the wave is done reading the previous step
-#pragma unroll
-                for (int i = 0; i < 2 * UCH; ++i)
-                    *reinterpret_cast<u32x4 *>(uw + (i >> 1) * (16 * kULD) + (i & 1) * (8 * kULD)) = ul[step][i];
-                __builtin_amdgcn_wave_barrier();        // staging buffer is wave-private: no block barrier
 #pragma unroll
                 for (int ci = 0; ci < UCH; ++ci) {      // one softmax tile = 64 positions = two k-steps
                     const int c = step * UCH + ci;
-                    const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(ur + ci * (16 * kULD));
-                    const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(ur + ci * (16 * kULD) + 32);
+                    const bf16x8 a0 = as_bf16x8(ul[step][2 * ci]), a1 = as_bf16x8(ul[step][2 * ci + 1]);
 #pragma unroll
                     for (int t = 0; t < NT; ++t) {
                         f32x4 wt = {0.f, 0.f, 0.f, 0.f};
@@ -611,8 +598,8 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
             }
         }
     }
-    // the two k-halves meet in LDS: half 1 parks its partial sums in its own staging buffer
-    f32x4 *park = reinterpret_cast<f32x4 *>(dyn + NR * LDP + (4 + jt) * USTG) + lane;
+    // the two k-halves meet in LDS: half 1 parks its partial sums behind the rows of P
+    f32x4 *park = reinterpret_cast<f32x4 *>(dyn + NR * LDP) + jt * (64 * NT) + lane;
     if (kh == 1) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) park[64 * t] = f32x4_mk(w[t][0], w[t][1], w[t][2], w[t][3]);
@@ -744,9 +731,10 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
 }
 
 size_t lds_b(int m_pad) { return static_cast<size_t>(kPC) * (m_pad + 8) * sizeof(uint16_t); }
-size_t lds_c(int n, int nt, int uch)
+size_t lds_c(int n, int nt)
 {
-    return (static_cast<size_t>(16) * nt * (n + 8) + static_cast<size_t>(8) * uch * 16 * kULD) * sizeof(uint16_t);
+    // rows of P, then one f32x4 per lane and tile for each of the four waves of k-half 1
+    return static_cast<size_t>(16) * nt * (n + 8) * sizeof(uint16_t) + static_cast<size_t>(4) * nt * 64 * 16;
 }
 
 int units_per_group(int G)
@@ -852,7 +840,7 @@ template <int G> bool launch_a(const Plan &p, const DecodeCall &c)
 
 template <int G, int UP, int NT, int NC> bool launch_c3(const Plan &p, const DecodeCall &c)
 {
-    const size_t lds = lds_c(NC * kPC, NT, KSplit<NC>::UCH);
+    const size_t lds = lds_c(NC * kPC, NT);
     static bool attr_set[kMaxDevices] = {};
     if (!allow_lds(reinterpret_cast<const void *>(fc_fused<G, UP, NT, NC>), lds, attr_set)) return false;
     fc_fused<G, UP, NT, NC><<<p.nvis_c, 512, lds, c.stream>>>(p, static_cast<const uint16_t *>(c.U),
