@@ -2,18 +2,18 @@
 //
 // Values (Sec. 3.1, "Sequence-Level Low-Rank Compression for Values"):
 //     Vc[b,h,i] = U[h] (V[b,h,block i] - 1 mu[h]^T) = U[h] V - (U[h] 1) mu[h]^T
-// is one GEMM per image block, [m x n] . [n x d].  A workgroup owns 64 rows j of one block:
-// each of its 4 wavefronts keeps 16 rows x 128 channels of accumulators, streams its 16 rows
-// of U straight from memory as the A operand (k = position p is contiguous in U), and shares
-// the V tile with the other waves through LDS, where it is transposed on the way in (V is
-// stored position-major, the B operand needs 8 consecutive positions of one channel per
-// lane).  The row sums U 1 come out of the same pass as one extra MFMA against a tile of
+// is one GEMM per image block, [m x n] . [n x d].  A workgroup owns up to 64 MT rows j of one
+// block (MT <= 4): each of its 4 wavefronts keeps MT tiles of 16 rows x 128 channels of
+// accumulators.  Per 64 positions, the workgroup's rows of U are read with whole 128-byte
+// lines and staged in LDS in row order (an MFMA operand is then 16 bytes of one row), and the
+// V tile is transposed on its way into LDS (V is stored position-major, the B operand needs 8
+// consecutive positions of one channel per lane).  Every LDS fragment of V feeds MT MFMAs.  The row sums U 1 come out of the same pass as one extra MFMA against a tile of
 // ones, already in the accumulator layout, so the centring costs no extra read of V.
 // The result is rounded once to bf16 and stored in the blocked channel-major layout that the
 // decode kernel reads as MFMA operands.
 //
-// Keys (Sec. 3.1, "Selective Retention and Reconstruction for Keys"): trailing workgroups of
-// the same launch copy the rows selected by the mask, 16 bytes per lane.
+// Keys (Sec. 3.1, "Selective Retention and Reconstruction for Keys"): a small launch of its own
+// copies the rows selected by the mask, 16 bytes per lane.
 #include "kvc_internal.h"
 
 namespace kvc {
@@ -42,57 +42,58 @@ __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, 
 // are XOR-swizzled with the channel group so the transposing stores spread over the banks
 __device__ inline int sv_index(int c, int p) { return c * kLD + ((((p >> 3) ^ (c >> 3)) & 7) << 3) + (p & 7); }
 
+// Keys (Sec. 3.1): Kc[u][j][:] = K[b,h, vis0 + i n + M[j], :], 64 rows per workgroup, 16 lanes per row.
+__global__ __launch_bounds__(256) void fk_gather(CPlan p, const uint16_t *__restrict__ K,
+                                                 const int32_t *__restrict__ idx,
+                                                 uint16_t *__restrict__ Kc)
+{
+    const int u = blockIdx.x / p.GJT, jt = blockIdx.x - u * p.GJT;
+    const int bh = u / p.I, i = u - bh * p.I;
+    const int b = bh / p.Hkv, h = bh - b * p.Hkv;
+    const uint16_t *src = K + b * p.sb + h * p.sh + (static_cast<int64_t>(p.vis0) + static_cast<int64_t>(i) * p.n) * p.ss;
+    const int rl = threadIdx.x >> 4, cs = threadIdx.x & 15;
+    uint4 v[4];
+    int jj[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        jj[q] = jt * kGJ + 16 * q + rl;
+        const int j = min(jj[q], p.m - 1);
+        v[q] = *(reinterpret_cast<const uint4 *>(src + static_cast<int64_t>(idx[j]) * p.ss) + cs);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if (jj[q] < p.m) *(reinterpret_cast<uint4 *>(Kc + (static_cast<size_t>(u) * p.m + jj[q]) * D) + cs) = v[q];
+}
+
 // MT = tiles per wavefront: a workgroup covers up to 64 MT rows of U, so V is read
 // ceil(m / (64 MT)) times per image block and every LDS fragment of V feeds MT MFMAs.
 template <int MT>
-__global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__restrict__ K,
-                                                   const uint16_t *__restrict__ V,
-                                                   const int32_t *__restrict__ idx,
+__global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__restrict__ V,
                                                    const uint16_t *__restrict__ U,
                                                    const uint16_t *__restrict__ mu,
-                                                   uint16_t *__restrict__ Kc,
                                                    uint16_t *__restrict__ Vc)
 {
     __shared__ __align__(16) uint16_t sVt[2][D * kLD];
+    extern __shared__ __align__(16) uint16_t sU[];          // [2][64 MT][kLD] rows of U, 64 positions each
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
-
-    if (static_cast<int>(blockIdx.x) >= p.nproj) {
-        // ---------------- keys: Kc[u][j][:] = K[b,h, vis0 + i n + M[j], :] ----------------
-        const int id = blockIdx.x - p.nproj;
-        const int u = id / p.GJT, jt = id - u * p.GJT;
-        const int bh = u / p.I, i = u - bh * p.I;
-        const int b = bh / p.Hkv, h = bh - b * p.Hkv;
-        const uint16_t *src = K + b * p.sb + h * p.sh + (static_cast<int64_t>(p.vis0) + static_cast<int64_t>(i) * p.n) * p.ss;
-        // 16 lanes per row, 16 rows per pass, 4 passes
-        const int rl = threadIdx.x >> 4, cs = threadIdx.x & 15;
-        uint4 v[4];
-        int jj[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            jj[q] = jt * kGJ + 16 * q + rl;
-            const int j = min(jj[q], p.m - 1);
-            v[q] = *(reinterpret_cast<const uint4 *>(src + static_cast<int64_t>(idx[j]) * p.ss) + cs);
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            if (jj[q] < p.m) *(reinterpret_cast<uint4 *>(Kc + (static_cast<size_t>(u) * p.m + jj[q]) * D) + cs) = v[q];
-        return;
-    }
 
     // ---------------- values: up to 4 MT tiles of 16 rows j of one image block ----------------
     const int u = blockIdx.x / p.JT, jt = blockIdx.x - u * p.JT;
     const int bh = u / p.I, i = u - bh * p.I;
     const int b = bh / p.Hkv, h = bh - b * p.Hkv;
     const int tile0 = jt * p.TPW, ntile = min(p.TPW, p.tiles - tile0);
-    // tile q of this wave is tile0 + wave + 4 q; a tile beyond the workgroup's share repeats the
-    // last row of U and its result is dropped, so the main loop carries no tests
+    // tile q of this wave is tile0 + wave + 4 q; rows beyond the workgroup's share repeat the last
+    // row of U and their results are dropped, so the main loop carries no tests
     int j0[MT];
-    const uint16_t *urow[MT];
 #pragma unroll
-    for (int q = 0; q < MT; ++q) {
-        j0[q] = 16 * (tile0 + wave + 4 * q);
-        urow[q] = U + (static_cast<size_t>(h) * p.m + min(j0[q] + r16, p.m - 1)) * p.n + 8 * kg;
+    for (int q = 0; q < MT; ++q) j0[q] = 16 * (tile0 + wave + 4 * q);
+    // U loads: item = (row of the workgroup, 16-byte piece of its 64 positions); 2 MT per thread
+    const uint16_t *usrc[2 * MT];
+#pragma unroll
+    for (int k = 0; k < 2 * MT; ++k) {
+        const int row = (static_cast<int>(threadIdx.x) + 256 * k) >> 3;
+        usrc[k] = U + (static_cast<size_t>(h) * p.m + min(16 * tile0 + row, p.m - 1)) * p.n + 8 * (threadIdx.x & 7);
     }
     const uint16_t *vsrc = V + b * p.sb + h * p.sh + (static_cast<int64_t>(p.vis0) + static_cast<int64_t>(i) * p.n) * p.ss;
     // V tile loads: item = (pair of positions, 8 channels); 512 items, two per thread
@@ -110,8 +111,8 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
 
     // Three register stages rotate by name (the loop is unrolled by three): a tile's loads are
     // issued two iterations before it is multiplied, and nothing is copied between stages.
-    u32x4 vaA[2][2], uaA[MT][2], vaB[2][2], uaB[MT][2], vaC[2][2], uaC[MT][2];
-    auto load_tile = [&](int kt, u32x4 (&va)[2][2], u32x4 (&ua)[MT][2]) {
+    u32x4 vaA[2][2], uaA[2 * MT], vaB[2][2], uaB[2 * MT], vaC[2][2], uaC[2 * MT];
+    auto load_tile = [&](int kt, u32x4 (&va)[2][2], u32x4 (&ua)[2 * MT]) {
 #pragma unroll
         for (int q = 0; q < 2; ++q)
 #pragma unroll
@@ -120,14 +121,12 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
                 va[q][e] = *(reinterpret_cast<const u32x4 *>(vsrc + static_cast<int64_t>(pp) * p.ss) + cs);
             }
 #pragma unroll
-        for (int q = 0; q < MT; ++q)
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-                ua[q][ks] = *reinterpret_cast<const u32x4 *>(urow[q] + kt * kKT + 32 * ks);
+        for (int k = 0; k < 2 * MT; ++k) ua[k] = *reinterpret_cast<const u32x4 *>(usrc[k] + kt * kKT);
     };
     const int NK = p.n / kKT;
-    auto step = [&](int kt, u32x4 (&va)[2][2], u32x4 (&ua)[MT][2]) {
+    auto step = [&](int kt, u32x4 (&va)[2][2], u32x4 (&ua)[2 * MT]) {
         uint16_t *buf = sVt[kt & 1];
+        uint16_t *ubuf = sU + (kt & 1) * (64 * MT * kLD);
         // transposed store: positions (2 pair, 2 pair + 1) of channel c share one 32-bit word
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
@@ -140,20 +139,29 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
                 *reinterpret_cast<uint32_t *>(buf + sv_index(8 * cs + 2 * e + 1, pl)) = (a[e] >> 16) | (c2[e] & 0xffff0000u);
             }
         }
+#pragma unroll
+        for (int k = 0; k < 2 * MT; ++k) {
+            const int row = (static_cast<int>(threadIdx.x) + 256 * k) >> 3;
+            *reinterpret_cast<u32x4 *>(ubuf + row * kLD + 8 * (threadIdx.x & 7)) = ua[k];
+        }
         __syncthreads();
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 af[MT];
+#pragma unroll
+            for (int q = 0; q < MT; ++q)
+                af[q] = *reinterpret_cast<const bf16x8 *>(ubuf + (16 * (wave + 4 * q) + r16) * kLD + 32 * ks + 8 * kg);
 #pragma unroll
             for (int nt = 0; nt < 8; ++nt) {
                 const int c = 16 * nt + r16;
                 const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(buf + sv_index(c, 32 * ks + 8 * kg));
 #pragma unroll
                 for (int q = 0; q < MT; ++q)
-                    acc[q][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ua[q][ks]), bfrag, acc[q][nt], 0, 0, 0);
+                    acc[q][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[q], bfrag, acc[q][nt], 0, 0, 0);
             }
 #pragma unroll
             for (int q = 0; q < MT; ++q)
-                accs[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ua[q][ks]), ones, accs[q], 0, 0, 0);
+                accs[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[q], ones, accs[q], 0, 0, 0);
         }
         load_tile(min(kt + 3, NK - 1), va, ua);          // past the end: the last tile again, unused
     };
@@ -195,12 +203,15 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
     }
 }
 
-template <int MT> void launch(const CPlan &p, const CompressCall &c)
+template <int MT> bool launch(const CPlan &p, const CompressCall &c)
 {
-    fk_compress<MT><<<p.nproj + p.ngather, 256, 0, c.stream>>>(
-        p, static_cast<const uint16_t *>(c.K), static_cast<const uint16_t *>(c.V), c.key_idx,
-        static_cast<const uint16_t *>(c.U), static_cast<const uint16_t *>(c.mu),
-        static_cast<uint16_t *>(c.Kc), static_cast<uint16_t *>(c.Vc));
+    const size_t lds = static_cast<size_t>(2) * 64 * MT * kLD * sizeof(uint16_t);
+    static bool attr_set[kMaxDevices] = {};
+    if (!allow_lds(reinterpret_cast<const void *>(fk_compress<MT>), lds, attr_set)) return false;
+    fk_compress<MT><<<p.nproj, 256, lds, c.stream>>>(
+        p, static_cast<const uint16_t *>(c.V), static_cast<const uint16_t *>(c.U),
+        static_cast<const uint16_t *>(c.mu), static_cast<uint16_t *>(c.Vc));
+    return true;
 }
 
 }  // namespace
@@ -228,13 +239,16 @@ kvc_status fast_compress(const CompressCall &c)
     p.nproj = units * p.JT;
     p.ngather = units * p.GJT;
     p.sb = c.stride_b; p.sh = c.stride_h; p.ss = c.stride_s;
+    fk_gather<<<p.ngather, 256, 0, c.stream>>>(p, static_cast<const uint16_t *>(c.K), c.key_idx,
+                                               static_cast<uint16_t *>(c.Kc));
+    bool ok;
     switch ((p.TPW + 3) / 4) {
-    case 1: launch<1>(p, c); break;
-    case 2: launch<2>(p, c); break;
-    case 3: launch<3>(p, c); break;
-    default: launch<4>(p, c); break;
+    case 1: ok = launch<1>(p, c); break;
+    case 2: ok = launch<2>(p, c); break;
+    case 3: ok = launch<3>(p, c); break;
+    default: ok = launch<4>(p, c); break;
     }
-    return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
+    return ok && hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
 }
 
 }  // namespace kvc

@@ -793,19 +793,6 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     return p;
 }
 
-// Raises a kernel's dynamic-LDS limit once per device (the attribute is per device); a failure is
-// left for the launch that follows to report.
-constexpr int kMaxDevices = 64;
-bool allow_lds(const void *fn, size_t bytes, bool *done)
-{
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
-    if (done[dev]) return true;
-    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes)) != hipSuccess) return false;
-    done[dev] = true;
-    return true;
-}
-
 template <int KS4> bool launch_b1(const Plan &p, const DecodeCall &c)
 {
     static bool attr_set[kMaxDevices] = {};

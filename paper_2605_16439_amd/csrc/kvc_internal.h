@@ -89,6 +89,19 @@ struct CompressCall {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Raises a kernel's dynamic-LDS limit once per device (the attribute is per device); `done` is the
+// caller's static flag array for that kernel.  False: the launch must not go ahead.
+constexpr int kMaxDevices = 64;
+inline bool allow_lds(const void *fn, size_t bytes, bool *done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+    if (done[dev]) return true;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes)) != hipSuccess) return false;
+    done[dev] = true;
+    return true;
+}
+
 // scalar (shape-agnostic) path
 size_t generic_decode_ws_bytes(const kvc_shape &s, int32_t max_text);
 kvc_status generic_decode(const DecodeCall &c);
