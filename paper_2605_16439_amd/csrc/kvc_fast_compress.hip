@@ -12,8 +12,8 @@
 // The result is rounded once to bf16 and stored in the blocked channel-major layout that the
 // decode kernel reads as MFMA operands.
 //
-// Keys (Sec. 3.1, "Selective Retention and Reconstruction for Keys"): a small launch of its own
-// copies the rows selected by the mask, 16 bytes per lane.
+// Keys (Sec. 3.1, "Selective Retention and Reconstruction for Keys"): every workgroup first copies
+// the key rows that the mask selects for its own rows j, 16 bytes per lane.
 #include "kvc_internal.h"
 
 namespace kvc {
@@ -24,7 +24,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
-constexpr int kGJ = 64;        // key rows per gather workgroup
 constexpr int kKT = 64;        // positions per LDS tile
 constexpr int kLD = kKT + 8;   // padded row of the transposed V tile (bf16 elements)
 constexpr int kMaxMT = 4;      // 16-row tiles of U per wavefront, at most
@@ -32,7 +31,7 @@ constexpr int kMaxMT = 4;      // 16-row tiles of U per wavefront, at most
 struct CPlan {
     int B, Hkv, n, I, m, vis0;
     int tiles, TPW, JT;         // 16-row tiles of U, tiles per workgroup, workgroups per image block
-    int GJT, nproj, ngather;
+    int nproj;
     int64_t sb, sh, ss;
 };
 
@@ -40,37 +39,17 @@ __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, 
 
 // element (channel c, position p of the tile) of the transposed tile; 16-byte chunks of a row
 // are XOR-swizzled with the channel group so the transposing stores spread over the banks
-__device__ inline int sv_index(int c, int p) { return c * kLD + ((((p >> 3) ^ (c >> 3)) & 7) << 3) + (p & 7); }
-
-// Keys (Sec. 3.1): Kc[u][j][:] = K[b,h, vis0 + i n + M[j], :], 64 rows per workgroup, 16 lanes per row.
-__global__ __launch_bounds__(256) void fk_gather(CPlan p, const uint16_t *__restrict__ K,
-                                                 const int32_t *__restrict__ idx,
-                                                 uint16_t *__restrict__ Kc)
-{
-    const int u = blockIdx.x / p.GJT, jt = blockIdx.x - u * p.GJT;
-    const int bh = u / p.I, i = u - bh * p.I;
-    const int b = bh / p.Hkv, h = bh - b * p.Hkv;
-    const uint16_t *src = K + b * p.sb + h * p.sh + (static_cast<int64_t>(p.vis0) + static_cast<int64_t>(i) * p.n) * p.ss;
-    const int rl = threadIdx.x >> 4, cs = threadIdx.x & 15;
-    uint4 v[4];
-    int jj[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        jj[q] = jt * kGJ + 16 * q + rl;
-        const int j = min(jj[q], p.m - 1);
-        v[q] = *(reinterpret_cast<const uint4 *>(src + static_cast<int64_t>(idx[j]) * p.ss) + cs);
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-        if (jj[q] < p.m) *(reinterpret_cast<uint4 *>(Kc + (static_cast<size_t>(u) * p.m + jj[q]) * D) + cs) = v[q];
-}
+__device__ inline int sv_index(int c, int p) { return c * kLD + ((((p >> 3) ^ (c >> 4)) & 7) << 3) + (p & 7); }
 
 // MT = tiles per wavefront: a workgroup covers up to 64 MT rows of U, so V is read
 // ceil(m / (64 MT)) times per image block and every LDS fragment of V feeds MT MFMAs.
 template <int MT>
-__global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__restrict__ V,
+__global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__restrict__ K,
+                                                   const uint16_t *__restrict__ V,
+                                                   const int32_t *__restrict__ idx,
                                                    const uint16_t *__restrict__ U,
                                                    const uint16_t *__restrict__ mu,
+                                                   uint16_t *__restrict__ Kc,
                                                    uint16_t *__restrict__ Vc)
 {
     __shared__ __align__(16) uint16_t sVt[2][D * kLD];
@@ -95,6 +74,25 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
         const int row = (static_cast<int>(threadIdx.x) + 256 * k) >> 3;
         usrc[k] = U + (static_cast<size_t>(h) * p.m + min(16 * tile0 + row, p.m - 1)) * p.n + 8 * (threadIdx.x & 7);
     }
+    // ---- keys (Sec. 3.1): Kc[u][j][:] = K[b,h, vis0 + i n + M[j], :] for this workgroup's rows j -------
+    // 16 lanes per row, 16 rows per pass; all rows are requested before the first is stored, and the
+    // stores drain while the projection below starts
+    {
+        const uint16_t *ksrc = K + b * p.sb + h * p.sh + (static_cast<int64_t>(p.vis0) + static_cast<int64_t>(i) * p.n) * p.ss;
+        const int rl = threadIdx.x >> 4, c16 = threadIdx.x & 15;
+        const int jend = min(16 * (tile0 + ntile), p.m);
+        u32x4 kv[4 * MT];
+#pragma unroll
+        for (int k = 0; k < 4 * MT; ++k) {
+            const int j = min(16 * (tile0 + k) + rl, p.m - 1);
+            kv[k] = *(reinterpret_cast<const u32x4 *>(ksrc + static_cast<int64_t>(idx[j]) * p.ss) + c16);
+        }
+#pragma unroll
+        for (int k = 0; k < 4 * MT; ++k) {
+            const int j = 16 * (tile0 + k) + rl;
+            if (j < jend) *(reinterpret_cast<u32x4 *>(Kc + (static_cast<size_t>(u) * p.m + j) * D) + c16) = kv[k];
+        }
+    }
     const uint16_t *vsrc = V + b * p.sb + h * p.sh + (static_cast<int64_t>(p.vis0) + static_cast<int64_t>(i) * p.n) * p.ss;
     // V tile loads: item = (pair of positions, 8 channels); 512 items, two per thread
     const int pair0 = threadIdx.x >> 4, cs = threadIdx.x & 15;      // second item: pair0 + 16
@@ -109,9 +107,10 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
     const uint32_t one2 = 0x3f803f80u;
     const bf16x8 ones = as_bf16x8(make_uint4(one2, one2, one2, one2));
 
-    // Three register stages rotate by name (the loop is unrolled by three): a tile's loads are
-    // issued two iterations before it is multiplied, and nothing is copied between stages.
-    u32x4 vaA[2][2], uaA[2 * MT], vaB[2][2], uaB[2 * MT], vaC[2][2], uaC[2 * MT];
+    // Two register stages rotate by name (the loop is unrolled by two): a tile's loads are issued
+    // right after the barrier of the previous tile and have that tile's MFMA work to arrive; nothing
+    // is copied between stages.
+    u32x4 vaA[2][2], uaA[2 * MT], vaB[2][2], uaB[2 * MT];
     auto load_tile = [&](int kt, u32x4 (&va)[2][2], u32x4 (&ua)[2 * MT]) {
 #pragma unroll
         for (int q = 0; q < 2; ++q)
@@ -145,40 +144,47 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
             *reinterpret_cast<u32x4 *>(ubuf + row * kLD + 8 * (threadIdx.x & 7)) = ua[k];
         }
         __syncthreads();
+        load_tile(min(kt + 2, NK - 1), va, ua);          // past the end: the last tile again, unused
+        // every fragment of the tile is requested from LDS before the first MFMA: the reads of one
+        // wave then overlap the matrix work instead of being waited for one by one
+        bf16x8 af[2][MT], bq[2][8];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-            bf16x8 af[MT];
 #pragma unroll
             for (int q = 0; q < MT; ++q)
-                af[q] = *reinterpret_cast<const bf16x8 *>(ubuf + (16 * (wave + 4 * q) + r16) * kLD + 32 * ks + 8 * kg);
+                af[ks][q] = *reinterpret_cast<const bf16x8 *>(ubuf + (16 * (wave + 4 * q) + r16) * kLD + 32 * ks + 8 * kg);
 #pragma unroll
-            for (int nt = 0; nt < 8; ++nt) {
-                const int c = 16 * nt + r16;
-                const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(buf + sv_index(c, 32 * ks + 8 * kg));
+            for (int nt = 0; nt < 8; ++nt)
+                bq[ks][nt] = *reinterpret_cast<const bf16x8 *>(buf + sv_index(16 * nt + r16, 32 * ks + 8 * kg));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt)
 #pragma unroll
                 for (int q = 0; q < MT; ++q)
-                    acc[q][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[q], bfrag, acc[q][nt], 0, 0, 0);
-            }
+                    acc[q][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks][q], bq[ks][nt], acc[q][nt], 0, 0, 0);
 #pragma unroll
             for (int q = 0; q < MT; ++q)
-                accs[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[q], ones, accs[q], 0, 0, 0);
+                accs[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks][q], ones, accs[q], 0, 0, 0);
         }
-        load_tile(min(kt + 3, NK - 1), va, ua);          // past the end: the last tile again, unused
     };
     load_tile(0, vaA, uaA);
     load_tile(min(1, NK - 1), vaB, uaB);
-    load_tile(min(2, NK - 1), vaC, uaC);
     int kt = 0;
-    for (; kt + 3 <= NK; kt += 3) {                      // no tests inside the loop body
+    for (; kt + 2 <= NK; kt += 2) {                      // no tests inside the loop body
         step(kt, vaA, uaA);
         step(kt + 1, vaB, uaB);
-        step(kt + 2, vaC, uaC);
     }
     if (kt < NK) step(kt, vaA, uaA);
-    if (kt + 1 < NK) step(kt + 1, vaB, uaB);
 
     // ---- epilogue: centre, round once, store in the blocked layout -----------------------------------
     // lane holds rows j = j0 + 4 kg + e (e = 0..3) of channel c = 16 nt + r16; accs[e] = sum_p U[j][p]
+    float muc[8];
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt)
+        muc[nt] = __uint_as_float(static_cast<uint32_t>(mu[static_cast<size_t>(h) * D + 16 * nt + r16]) << 16);
 #pragma unroll
     for (int q = 0; q < MT; ++q) {
         if (wave + 4 * q >= ntile) continue;
@@ -188,10 +194,9 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) {
             const int c = 16 * nt + r16;
-            const float muc = __uint_as_float(static_cast<uint32_t>(mu[static_cast<size_t>(h) * D + c]) << 16);
             uint32_t o[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_bits(acc[q][nt][e] - accs[q][e] * muc);
+            for (int e = 0; e < 4; ++e) o[e] = f32_to_bf16_bits(acc[q][nt][e] - accs[q][e] * muc[nt]);
             if (w == 8) {
                 *reinterpret_cast<uint2 *>(vout + c * 8 + jr) = make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
             } else if (w > 0) {
@@ -209,8 +214,9 @@ template <int MT> bool launch(const CPlan &p, const CompressCall &c)
     static bool attr_set[kMaxDevices] = {};
     if (!allow_lds(reinterpret_cast<const void *>(fk_compress<MT>), lds, attr_set)) return false;
     fk_compress<MT><<<p.nproj, 256, lds, c.stream>>>(
-        p, static_cast<const uint16_t *>(c.V), static_cast<const uint16_t *>(c.U),
-        static_cast<const uint16_t *>(c.mu), static_cast<uint16_t *>(c.Vc));
+        p, static_cast<const uint16_t *>(c.K), static_cast<const uint16_t *>(c.V), c.key_idx,
+        static_cast<const uint16_t *>(c.U), static_cast<const uint16_t *>(c.mu),
+        static_cast<uint16_t *>(c.Kc), static_cast<uint16_t *>(c.Vc));
     return true;
 }
 
@@ -230,17 +236,27 @@ kvc_status fast_compress(const CompressCall &c)
     CPlan p;
     p.B = s.batch; p.Hkv = s.n_kv_heads; p.n = s.n_img_tokens; p.I = s.n_images; p.m = s.m;
     p.vis0 = c.vis_start;
-    // the 16-row tiles of U are shared out evenly over as few workgroups as 4 waves x kMaxMT allow
+    // The 16-row tiles of U are shared out evenly over JT workgroups per image block, each wave taking
+    // MT = ceil(tiles per workgroup / 4) of them.  JT is chosen by a small cost model fitted to
+    // measurements on MI355X: time per round of resident workgroups grows with MT (fewer, fatter
+    // workgroups read V less often but leave one workgroup per CU), MT = 1 fits two per CU.
     p.tiles = (s.m + 15) / 16;
-    p.JT = (p.tiles + 4 * kMaxMT - 1) / (4 * kMaxMT);
-    p.TPW = (p.tiles + p.JT - 1) / p.JT;
-    p.GJT = (s.m + kGJ - 1) / kGJ;
     const int units = p.B * p.Hkv * p.I;
+    {
+        static const int round_cost[kMaxMT + 1] = {0, 27, 30, 36, 42};
+        const int cus = 256;
+        long best = -1;
+        for (int jt = (p.tiles + 4 * kMaxMT - 1) / (4 * kMaxMT); jt <= (p.tiles + 3) / 4; ++jt) {
+            const int tpw = (p.tiles + jt - 1) / jt, mt = (tpw + 3) / 4;
+            const long slots = mt == 1 ? 2L * cus : cus;
+            const long rounds = (static_cast<long>(units) * jt + slots - 1) / slots;
+            const long cost = rounds * round_cost[mt];
+            if (best < 0 || cost < best) { best = cost; p.JT = jt; }
+        }
+    }
+    p.TPW = (p.tiles + p.JT - 1) / p.JT;
     p.nproj = units * p.JT;
-    p.ngather = units * p.GJT;
     p.sb = c.stride_b; p.sh = c.stride_h; p.ss = c.stride_s;
-    fk_gather<<<p.ngather, 256, 0, c.stream>>>(p, static_cast<const uint16_t *>(c.K), c.key_idx,
-                                               static_cast<uint16_t *>(c.Kc));
     bool ok;
     switch ((p.TPW + 3) / 4) {
     case 1: ok = launch<1>(p, c); break;

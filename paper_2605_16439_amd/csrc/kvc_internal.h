@@ -17,13 +17,11 @@ struct bf16_t {
 __host__ __device__ inline float to_f(float x) { return x; }
 __device__ inline float to_f(bf16_t x) { return __uint_as_float(static_cast<uint32_t>(x.v) << 16); }
 
-// round-to-nearest-even fp32 -> bf16 bits
+// round-to-nearest-even fp32 -> bf16 bits: gfx950 converts in hardware (one packed instruction
+// per pair of values)
 __device__ inline uint16_t f32_to_bf16_bits(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);  // NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return static_cast<uint16_t>(u >> 16);
+    return __builtin_bit_cast(uint16_t, static_cast<__bf16>(f));
 }
 
 template <class T> __device__ inline T from_f(float f);
