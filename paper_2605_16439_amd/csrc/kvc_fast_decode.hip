@@ -28,11 +28,16 @@
 //  * kernel boundaries are the only grid-wide synchronisation: a device-scope fence inside a
 //    kernel writes back and invalidates an XCD's whole L2 and costs far more than a launch;
 //  * a load whose lanes use only half of each 128-byte line (what an MFMA operand fetched
-//    straight from a row-major matrix does: 16 rows x 64 bytes) runs at half the L2->CU rate,
-//    so operands that are re-read from L2 (U in fc_fused) are fetched with fully coalesced
-//    loads and handed to the MFMA through a wave-private LDS buffer;
-//  * every kernel requests its independent data up front, stores MFMA results directly
-//    (no cross-lane reductions) and stays small in code (cold instruction cache per launch).
+//    straight from a row-major matrix does: 16 rows x 64 bytes) runs at half the L1 rate; for U
+//    in fc_fused, which is bound by L2 bandwidth, that measured equal to staging coalesced loads
+//    through LDS, so the simpler direct operand loads are used;
+//  * loads are requested in the order the matrix work needs them, the bulk (second half of U,
+//    compressed values) only after the first MFMAs are under way: requesting everything up front
+//    stalls the instruction stream on a full memory queue before any matrix work starts;
+//  * loops that feed MFMAs carry no tests (trip counts are template parameters): a guarded loop
+//    makes the compiler move accumulators between register files at every step;
+//  * MFMA results are stored directly (no cross-lane reductions beyond two steps) and code stays
+//    small (cold instruction cache per launch).
 //
 // Query rows of one KV head are ordered r = (b*I + i)*G + g, so the G query heads of a
 // group and consecutive image blocks share MFMA tiles.
