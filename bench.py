@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--generic", action="store_true", help="force the scalar kernels")
+    ap.add_argument("--read-probe", type=int, default=0, metavar="GiB",
+                    help="also time a plain streaming read-sum over this many GiB and report it as "
+                         "roofline.measured_read_ceiling (GB/s)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="also run 3 plain device copies of this many MiB (counter calibration "
                          "for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
@@ -178,6 +181,23 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
+    read_ceiling = None
+    if args.read_probe:
+        # the library's plain read kernel over a buffer far larger than every cache
+        buf = torch.ones((args.read_probe << 30) // 4, dtype=torch.int32, device=dev)
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        kv.kvc_probe_read(buf, sink)
+        best = 0.0
+        for _ in range(5):
+            e0, e1 = ev(), ev()
+            e0.record()
+            kv.kvc_probe_read(buf, sink)
+            e1.record()
+            e1.synchronize()
+            best = max(best, buf.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+        read_ceiling = best
+        del buf
+
     t_avg = w.text_len + (K + 1) / 2.0      # rows attended, new token included
     abytes = sum(algorithmic_bytes(w, ml, t_avg) for ml in ms) / L        # mean over the layers
     achieved = abytes / (call_us * 1e-6) / 1e9
@@ -200,7 +220,8 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic["bytes_per_call"] if traffic else None,
                      "kernel": "kvc_reconstruct_attend_decode (fa_scores + fb_probs + fc_fused + fd_finalize)",
-                     "algorithmic_bytes_per_launch": abytes, "us_per_launch": call_us},
+                     "algorithmic_bytes_per_launch": abytes, "us_per_launch": call_us,
+                     "measured_read_ceiling": read_ceiling},
         "compress": {"ms_per_layer": comp_ms / L,
                      "tflops": 2.0 * w.batch * w.n_kv_heads * w.n_images * (sum(ms) / L)
                      * w.n_img_tokens * w.head_dim / (comp_ms / L * 1e-3) / 1e12},

@@ -165,6 +165,14 @@ kvc_status kvc_compress_generic(const kvc_shape *shape, const kvc_params *params
                                 void *Kc, void *Vc,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* Measurement aid (no part of the method): a plain streaming read of `bytes` bytes of device
+   memory at `buf` (16-byte aligned, bytes a multiple of 16), 16 bytes per lane, grid-stride, every
+   value folded into a checksum that is written to `sink` (device, at least 4 bytes) only if it
+   equals a fixed pattern.  Timing it over a buffer much larger than the caches gives the
+   streaming-read rate this chip reaches, to set beside the published HBM peak.  Asynchronous on
+   `stream`.  Errors: KVC_ERR_NULL, KVC_ERR_ALIGN, KVC_ERR_HIP. */
+kvc_status kvc_probe_read(const void *buf, size_t bytes, void *sink, void *stream);
+
 /* Static string for a status code. */
 const char *kvc_status_string(int32_t status);
 

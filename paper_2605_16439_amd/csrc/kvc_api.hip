@@ -226,6 +226,32 @@ kvc_status kvc_reconstruct_attend_decode_generic(const kvc_shape *shape, const k
     return generic_decode(c);
 }
 
+namespace {
+__global__ __launch_bounds__(256) void probe_read(const uint4 *__restrict__ p, size_t n16, unsigned *sink)
+{
+    size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+    unsigned acc = 0;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = p[i], b = p[i + stride], c = p[i + 2 * stride], d = p[i + 3 * stride];
+        acc += a.x ^ b.y ^ c.z ^ d.w;
+    }
+    for (; i < n16; i += stride) acc += p[i].x;
+    if (acc == 0x12345678u) *sink = acc;
+}
+}  // namespace
+
+kvc_status kvc_probe_read(const void *buf, size_t bytes, void *sink, void *stream)
+{
+    if (!buf || !sink) return KVC_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(buf) & 15) || (bytes & 15) || (reinterpret_cast<uintptr_t>(sink) & 3))
+        return KVC_ERR_ALIGN;
+    if (bytes == 0) return KVC_OK;
+    probe_read<<<256 * 16, 256, 0, static_cast<hipStream_t>(stream)>>>(
+        static_cast<const uint4 *>(buf), bytes / 16, static_cast<unsigned *>(sink));
+    return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
+}
+
 const char *kvc_status_string(int32_t status)
 {
     switch (status) {

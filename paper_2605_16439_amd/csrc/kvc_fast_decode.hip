@@ -249,6 +249,7 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
     const int tile0 = (blockIdx.x * 4 + wave) * kTPW;
     u32x4 kf[kTPW][4], qf[kTPW][4];
     bool live[kTPW];
+    int bh_prev = -1;
 #pragma unroll
     for (int tt = 0; tt < kTPW; ++tt) {
         const int tile = tile0 + tt;
@@ -261,9 +262,17 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
         const u32x4 *kp = reinterpret_cast<const u32x4 *>(Kc + (static_cast<size_t>(u) * p.m + row) * D) + kg;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) kf[tt][ks] = kp[4 * ks];
-        const u32x4 *qp = reinterpret_cast<const u32x4 *>(q + (static_cast<size_t>(b) * p.Hq + h * G + min(r16, G - 1)) * D) + kg;
+        // tiles of one (batch, KV head) share the query rows: the second tile of a wave reloads them
+        // only when it belongs to another one
+        if (tt == 0 || bh != bh_prev) {
+            const u32x4 *qp = reinterpret_cast<const u32x4 *>(q + (static_cast<size_t>(b) * p.Hq + h * G + min(r16, G - 1)) * D) + kg;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) qf[tt][ks] = qp[4 * ks];
+            for (int ks = 0; ks < 4; ++ks) qf[tt][ks] = qp[4 * ks];
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) qf[tt][ks] = qf[tt - 1][ks];
+        }
+        bh_prev = bh;
     }
     TS(0, 1);
 #pragma unroll

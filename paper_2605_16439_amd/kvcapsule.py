@@ -29,7 +29,7 @@ KVC_BF16 = 1
 EXPORTS = [
     "kvc_compressed_len", "kvc_workspace_bytes", "kvc_memory_footprint", "kvc_compress",
     "kvc_reconstruct_attend_decode", "kvc_reconstruct_attend_decode_generic",
-    "kvc_compress_generic", "kvc_status_string", "kvc_version",
+    "kvc_compress_generic", "kvc_probe_read", "kvc_status_string", "kvc_version",
 ]
 
 
@@ -81,11 +81,20 @@ def lib() -> ctypes.CDLL:
         for name in ("kvc_reconstruct_attend_decode", "kvc_reconstruct_attend_decode_generic"):
             getattr(L, name).restype = i32
             getattr(L, name).argtypes = dec
+        L.kvc_probe_read.restype = i32
+        L.kvc_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         L.kvc_status_string.restype = ctypes.c_char_p
         L.kvc_status_string.argtypes = [i32]
         L.kvc_version.restype = ctypes.c_char_p
         _lib = L
     return _lib
+
+
+def kvc_probe_read(buf: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """Streaming read of all of `buf` (measurement aid); `sink` is any device tensor of >= 4 bytes."""
+    st = lib().kvc_probe_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream(stream))
+    if st != KVC_OK:
+        raise KvcError(st, "kvc_probe_read")
 
 
 def status_string(status: int) -> str:

@@ -123,3 +123,13 @@ def test_workspace_size_and_status_strings():
     seen = {kv.status_string(c) for c in range(-7, 1)}
     assert len(seen) == 8 and kv.status_string(kv.KVC_OK) == "ok"
     assert kv.status_string(-99) == "unknown status"
+
+
+def test_probe_read_rejects_bad_arguments_before_touching_the_device():
+    L = kv.lib()
+    fake = ctypes.c_void_p(0x10000)
+    assert L.kvc_probe_read(None, 1024, fake, None) == kv.KVC_ERR_NULL
+    assert L.kvc_probe_read(fake, 1024, None, None) == kv.KVC_ERR_NULL
+    assert L.kvc_probe_read(ctypes.c_void_p(0x10008), 1024, fake, None) == kv.KVC_ERR_ALIGN
+    assert L.kvc_probe_read(fake, 1000, fake, None) == kv.KVC_ERR_ALIGN
+    assert L.kvc_probe_read(fake, 0, fake, None) == kv.KVC_OK
