@@ -336,3 +336,48 @@ def test_pyramid_schedule_mixed_lengths_share_one_workspace():
             _say(f"[parity] pyramid step {step} layer {l} m={ms[l]}: {e:.3e}")
             assert e <= tol(w)
         t += 1
+
+
+def test_fitted_parameters_on_structured_kv():
+    """Parameters fitted (harness-side, tests/calibration.py) to keys and values with the redundancy
+    Sec. 3.1 describes: the HIP path must agree with the oracle to the usual bar, and both stay
+    close to full-cache attention (the cosine is reported; it belongs to this synthetic data)."""
+    import calibration as cal
+    w = FAST.with_(name="fast_fitted", index=45, batch=2, n_images=2, text_len=24, steps=1)
+    n, I, d, m = w.n_img_tokens, w.n_images, w.head_dim, 103
+    bf = lambda a: torch.from_numpy(a).to(torch.bfloat16)
+    Kc_, Vc_, Ak, Av, mu0 = cal.make_structured_kv(11, 3, w.n_kv_heads, n, I, d, 40, 0.05)
+    idx, theta, U, mu = cal.fit_params(Kc_, Vc_, n, m)
+    K, V, *_ = cal.make_structured_kv(12, w.batch, w.n_kv_heads, n, I, d, 40, 0.05, Ak, Av, mu0)
+    L = Layer(w, m)
+    # replace the random tensors by the structured ones (rounded once to bf16, shared by both sides)
+    L.K, L.V = bf(K), bf(V)
+    L.gK, L.gV = L.K.to(DEV), L.V.to(DEV)
+    L.p = dict(key_idx=torch.from_numpy(idx), theta=bf(theta), U=bf(U), mu=bf(mu))
+    L.g = {k: v.to(DEV) for k, v in L.p.items()}
+    L.params = kv.make_params(L.g["key_idx"], L.g["theta"], L.g["U"], L.g["mu"])
+    L.compress()
+    th, Uh, muh = f64(L.p["theta"]), f64(L.p["U"]), f64(L.p["mu"])
+    Kc_ref, Vc_ref = orc.compress(f64(L.K), f64(L.V), idx, Uh, muh, n, I, 0, store_code(w))
+    assert np.array_equal(f64(L.gKc), Kc_ref)
+    assert block_rel_err(unpack_vc(L.gVc, m, d), Vc_ref) <= tol(w)
+    Kh, Vh = orc.reconstruct(Kc_ref, Vc_ref, th, Uh, muh, n)
+    q, kn, vn = synth.make_step_inputs(w, 0, 0)
+    out, _ = L.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
+    Kt, Vt = f64(L.Kt).copy(), f64(L.Vt).copy()
+    Kt[:, :, w.text_len], Vt[:, :, w.text_len] = f64(kn), f64(vn)
+    ref, _ = orc.attend(f64(q), Kh, Vh, Kt, Vt, w.text_len + 1, None)
+    e = row_rel_err(out, ref)
+    # full-cache attention on the uncompressed keys and values
+    G = w.n_q_heads // w.n_kv_heads
+    Kf = np.concatenate([f64(L.K), Kt[:, :, :w.text_len + 1]], axis=2).repeat(G, axis=1)
+    Vf = np.concatenate([f64(L.V), Vt[:, :, :w.text_len + 1]], axis=2).repeat(G, axis=1)
+    full = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(f64(q))[:, :, None, :], torch.from_numpy(Kf), torch.from_numpy(Vf))[:, :, 0].numpy()
+    c_out = cal.mean_cosine(out, full)
+    c_k = cal.mean_cosine(Kh.reshape(f64(L.K).shape), f64(L.K))
+    c_v = cal.mean_cosine(Vh.reshape(f64(L.V).shape), f64(L.V))
+    _say(f"[parity] fitted params: HIP vs oracle {e:.3e}; cos(K_hat,K) {c_k:.4f} cos(V_hat,V) {c_v:.4f} "
+         f"cos(HIP out, full-cache out) {c_out:.4f}")
+    assert e <= tol(w)
+    assert c_k >= 0.98 and c_v >= 0.98 and c_out >= 0.98
