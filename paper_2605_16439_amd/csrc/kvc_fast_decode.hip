@@ -72,6 +72,7 @@ struct Plan {
     int R, R_pad, NRB, m_pad, m16, NC;
     int tiles_per_unit, vis_tiles, nvis_a;
     int UP, NT, NG, JS, NXC, nparts, rec;
+    int merge, nvp;                 // one part per workgroup (its image blocks merged); vision parts per (b, head)
     int nvis_b, b_stride, nvis_c, c_stride;
     float scale;
 #if defined(KVC_TIMELINE)
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
         __syncthreads();
         TS(0, 3);
         // out_part^T[c][g] = sum_x V^T[c][x] P[g][x]; each wave owns two 16-channel tiles
-        float *yp = p.Ypart + (static_cast<size_t>(bh) * p.nparts + p.I * p.JS + xc) * p.rec;
+        float *yp = p.Ypart + (static_cast<size_t>(bh) * p.nparts + p.nvp + xc) * p.rec;
 #pragma unroll
         for (int ct2 = 0; ct2 < 2; ++ct2) {
             const int ct = 2 * wave + ct2;
@@ -642,6 +643,17 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
     }
     constexpr int un_lim = UP * G;
     const int un_mine = r16 / G, g_mine = r16 - un_mine * G;     // image block (within a tile) of this lane's row
+    // merged mode: the blocks' outputs are brought to a common maximum per query head and summed
+    float gm = -INFINITY, sc[NT];
+    if (p.merge) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int ul = 0; ul < UP; ++ul) gm = fmaxf(gm, sMx[16 * t + ul * G + g_mine]);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) sc[t] = __expf(sMx[16 * t + r16] - gm);
+    }
+    f32x4 ysum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int un0 = 0; un0 < NU; un0 += UBATCH) {
         u32x4 cur[UBATCH][2];
@@ -655,7 +667,10 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
             f32x4 o = {0.f, 0.f, 0.f, 0.f};
             o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur[a][0]), wb[t][0], o, 0, 0, 0);
             o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur[a][1]), wb[t][1], o, 0, 0, 0);
-            if (un < nunits && un_mine == ul2 && r16 < un_lim) {
+            if (p.merge) {
+                const float w8 = (un_mine == ul2 && r16 < un_lim) ? sc[t] : 0.f;   // rows of other blocks: cross terms
+                ysum[0] += w8 * o[0]; ysum[1] += w8 * o[1]; ysum[2] += w8 * o[2]; ysum[3] += w8 * o[3];
+            } else if (un < nunits && un_mine == ul2 && r16 < un_lim) {
                 const int ub = ub0 + un;
                 const int b = ub / p.I, i = ub - b * p.I;
                 float *yp = p.Ypart + (static_cast<size_t>(b * p.Hkv + h) * p.nparts + i * p.JS + s) * p.rec;
@@ -664,6 +679,33 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
                     yp[G * D + g_mine] = sMx[16 * t + r16];
                     yp[G * D + G + g_mine] = s == 0 ? sSm[16 * t + r16] : 0.f;     // the block's mass is counted once
                 }
+            }
+        }
+    }
+    if (p.merge) {
+        // sum over the blocks of a tile: rows ul G + g for ul = 0 .. UP-1 sit in lanes of one 16-lane row
+        if constexpr ((G & (G - 1)) == 0) {
+#pragma unroll
+            for (int o2 = G; o2 < 16; o2 <<= 1)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ysum[e] += __shfl_xor(ysum[e], o2, 64);
+        } else {
+            static_assert(UP == 2, "blocks of a tile are summed with one exchange");
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ysum[e] += __shfl(ysum[e], (lane & 48) | ((r16 + G) & 15), 64);
+        }
+        if (r16 < G) {
+            const int b = ub0 / p.I, gi = (ub0 - b * p.I) / NU;
+            float *yp = p.Ypart + (static_cast<size_t>(b * p.Hkv + h) * p.nparts + gi * p.JS + s) * p.rec;
+            *reinterpret_cast<f32x4 *>(yp + r16 * D + 16 * wave + 4 * kg) = ysum;
+            if (wave == 0 && kg == 0) {
+                float sm = 0.f;
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int ul = 0; ul < UP; ++ul) sm += sSm[16 * t + ul * G + r16] * __expf(sMx[16 * t + ul * G + r16] - gm);
+                yp[G * D + r16] = gm;
+                yp[G * D + G + r16] = s == 0 ? sm : 0.f;                       // the blocks' mass is counted once
             }
         }
     }
@@ -686,7 +728,7 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rec = p.rec, GD = p.G * D;
     const float *yb = p.Ypart + static_cast<size_t>(b * p.Hkv + h) * p.nparts * rec;
-    const int nvp = p.I * p.JS;
+    const int nvp = p.nvp;
     const int c = threadIdx.x;
     const float *yc = yb + g * D + c;
     // first batch of partial outputs in flight together with the statistics
@@ -782,7 +824,11 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.NG = p.UP ? (p.B * p.I + p.NT * p.UP - 1) / (p.NT * p.UP) : 0;
     p.JS = (p.m + kJC - 1) / kJC;
     p.NXC = (t + kXC - 1) / kXC;
-    p.nparts = p.I * p.JS + p.NXC;
+    // When every workgroup of fc_fused holds image blocks of one batch element only, it merges them
+    // into a single part record (fewer, larger-grained parts for fd_finalize to read)
+    p.merge = (p.UP && p.I > 0 && p.I % (p.NT * p.UP) == 0) ? 1 : 0;
+    p.nvp = (p.merge ? p.I / (p.NT * p.UP) : p.I) * p.JS;
+    p.nparts = p.nvp + p.NXC;
     p.rec = static_cast<int>(align_up(p.G * D + 2 * p.G, 4));   // 16-byte aligned records
     p.b_stride = static_cast<int>(align_up(p.Hkv * p.NC, 8));
     p.nvis_b = p.NRB * p.b_stride;
