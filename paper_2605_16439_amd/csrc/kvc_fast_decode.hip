@@ -716,11 +716,13 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
 // fd_finalize: joint softmax over all parts of one (batch, query head): rescale the partial
 // outputs to the global maximum, normalise, add (sum P_vis) mu, store out and lse.
 // ------------------------------------------------------------------------------------------
+// PB = parts fetched per batch (a multiple of 8 covering all parts when there are at most 64).
+template <int PB>
 __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__restrict__ mu,
                                                    uint16_t *__restrict__ out,
                                                    float *__restrict__ lse)
 {
-    __shared__ float sSc[kMaxParts];
+    __shared__ float sSc[kMaxParts + 64];
     __shared__ float sRed[2][3];
     TS(3, 0);
     const int bg = blockIdx.x, b = bg / p.Hq, gq = bg - b * p.Hq;
@@ -731,27 +733,32 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
     const int nvp = p.nvp;
     const int c = threadIdx.x;
     const float *yc = yb + g * D + c;
-    // first batch of partial outputs in flight together with the statistics
-    constexpr int PB = 64;
-    float v[PB];
-#pragma unroll
-    for (int k = 0; k < PB; ++k) v[k] = yc[static_cast<size_t>(min(k, p.nparts - 1)) * rec];
+    // statistics first, then the first batch of partial outputs: one round trip for both
     float ml[2], sl[2];
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
-        const int pt = threadIdx.x + 128 * k;
-        ml[k] = pt < p.nparts ? yb[static_cast<size_t>(pt) * rec + GD + g] : -INFINITY;
-        sl[k] = pt < p.nparts ? yb[static_cast<size_t>(pt) * rec + GD + p.G + g] : 0.f;
+        const int pt = min(static_cast<int>(threadIdx.x) + 128 * k, p.nparts - 1);
+        ml[k] = yb[static_cast<size_t>(pt) * rec + GD + g];
+        sl[k] = yb[static_cast<size_t>(pt) * rec + GD + p.G + g];
     }
+    float v[PB];
+#pragma unroll
+    for (int k = 0; k < PB; ++k) v[k] = yc[static_cast<size_t>(min(k, p.nparts - 1)) * rec];
+    TS(3, 1);
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+        if (static_cast<int>(threadIdx.x) + 128 * k >= p.nparts) { ml[k] = -INFINITY; sl[k] = 0.f; }
     float mx = wave_max(fmaxf(ml[0], ml[1]));
     if (lane == 0) sRed[wave][0] = mx;
+    if (threadIdx.x < 64) sSc[kMaxParts + threadIdx.x] = 0.f;
     __syncthreads();
+    TS(3, 2);
     mx = fmaxf(sRed[0][0], sRed[1][0]);
     float a[2], z = 0.f, zv = 0.f;
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         const int pt = threadIdx.x + 128 * k;
-        a[k] = pt < p.nparts ? __expf(ml[k] - mx) : 0.f;
+        a[k] = __expf(ml[k] - mx);              // exp(-inf) = 0 beyond the last part
         z += sl[k] * a[k];
         if (pt < nvp) zv += sl[k] * a[k];
     }
@@ -761,12 +768,11 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
     __syncthreads();
     z = sRed[0][1] + sRed[1][1];
     zv = sRed[0][2] + sRed[1][2];
+    const float rz = 1.f / z;
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        const int pt = threadIdx.x + 128 * k;
-        if (pt < p.nparts) sSc[pt] = a[k] / z;
-    }
+    for (int k = 0; k < 2; ++k) sSc[threadIdx.x + 128 * k] = a[k] * rz;     // zero weight beyond the last part
     __syncthreads();
+    TS(3, 3);
     float y = 0.f;
     for (int pt0 = 0; pt0 < p.nparts; pt0 += PB) {
         float cur[PB];
@@ -777,10 +783,9 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
             for (int k = 0; k < PB; ++k) v[k] = yc[static_cast<size_t>(min(pt0 + PB + k, p.nparts - 1)) * rec];
         }
 #pragma unroll
-        for (int k = 0; k < PB; ++k)          // parts beyond the last were loaded clamped: weight zero
-            y += (pt0 + k < p.nparts ? sSc[min(pt0 + k, kMaxParts - 1)] : 0.f) * cur[k];
+        for (int k = 0; k < PB; ++k) y += sSc[pt0 + k] * cur[k];    // clamped duplicates carry weight zero
     }
-    y += (zv / z) * bf_lo(mu[static_cast<size_t>(h) * D + c]);
+    y += (zv * rz) * bf_lo(mu[static_cast<size_t>(h) * D + c]);
     out[static_cast<size_t>(bg) * D + c] = f32_to_bf16_bits(y);
     if (c == 0 && lse) lse[bg] = mx + __logf(z);
     TS(3, 4);
@@ -851,6 +856,26 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.tl = nullptr;
 #endif
     return p;
+}
+
+template <int PB> void launch_d1(const Plan &p, const DecodeCall &c)
+{
+    fd_finalize<PB><<<p.B * p.Hq, 128, 0, c.stream>>>(p, static_cast<const uint16_t *>(c.mu),
+                                                      static_cast<uint16_t *>(c.out), c.lse);
+}
+
+void launch_d(const Plan &p, const DecodeCall &c)
+{
+    switch (((p.nparts < 64 ? p.nparts : 64) + 7) >> 3) {      // parts per batch, in eights
+    case 1: launch_d1<8>(p, c); break;
+    case 2: launch_d1<16>(p, c); break;
+    case 3: launch_d1<24>(p, c); break;
+    case 4: launch_d1<32>(p, c); break;
+    case 5: launch_d1<40>(p, c); break;
+    case 6: launch_d1<48>(p, c); break;
+    case 7: launch_d1<56>(p, c); break;
+    default: launch_d1<64>(p, c); break;
+    }
 }
 
 template <int KS4> bool launch_b1(const Plan &p, const DecodeCall &c)
@@ -952,8 +977,7 @@ kvc_status fast_decode(const DecodeCall &c)
         if (!launch_b(p, c)) return KVC_ERR_HIP;
     }
     if (!launch_for_group(p, c, false)) return KVC_ERR_HIP;
-    fd_finalize<<<p.B * p.Hq, 128, 0, c.stream>>>(p, static_cast<const uint16_t *>(c.mu),
-                                                  static_cast<uint16_t *>(c.out), c.lse);
+    launch_d(p, c);
     return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
 }
 
