@@ -381,3 +381,26 @@ def test_fitted_parameters_on_structured_kv():
          f"cos(HIP out, full-cache out) {c_out:.4f}")
     assert e <= tol(w)
     assert c_k >= 0.98 and c_v >= 0.98 and c_out >= 0.98
+
+
+def test_fast_path_without_append_and_vision_only():
+    """Matrix-core path with no new token (the cache is attended as it is), and with no text at all
+    (Alg. 1 proper: softmax over the image logits only)."""
+    w = FAST.with_(name="fast_noappend", index=46)
+    m = 103
+    L = Layer(w, m)
+    L.compress()
+    q, _, _ = synth.make_step_inputs(w, 0, 0)
+    gKc, gVc = f64(L.gKc), unpack_vc(L.gVc, m, w.head_dim)
+    th, U, mu = f64(L.p["theta"]), f64(L.p["U"]), f64(L.p["mu"])
+    Kt0, Vt0 = f64(L.gKt).copy(), f64(L.gVt).copy()
+    out, lse = L.decode(q.to(DEV), w.text_len)                     # k_new = v_new = None
+    ref, lref = orc.reconstruct_attend_decode(f64(q), gKc, gVc, th, U, mu, w.n_img_tokens,
+                                              f64(L.Kt), f64(L.Vt), w.text_len)
+    assert row_rel_err(out, ref) <= tol(w)
+    assert np.array_equal(f64(L.gKt), Kt0) and np.array_equal(f64(L.gVt), Vt0)   # caches untouched
+    kv.kvc_reconstruct_attend_decode(L.shape, L.params, q.to(DEV), L.gKc, L.gVc, None, None, 0, 0,
+                                     None, None, 0.0, L.out, L.lse, L.ws)
+    torch.cuda.synchronize()
+    ref, _ = orc.reconstruct_attend_decode(f64(q), gKc, gVc, th, U, mu, w.n_img_tokens, None, None, 0)
+    assert row_rel_err(f64(L.out), ref) <= tol(w)
