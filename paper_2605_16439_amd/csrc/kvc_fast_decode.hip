@@ -462,13 +462,15 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
     const int r16 = lane & 15, kg = lane >> 4;
     const int jt = wave & 3, kh = wave >> 2;
 
-    // ug is the slow index with a stride that is a multiple of 8: workgroups that stream the same
-    // rows of U[h] sit on one XCD and share its L2
+    // Workgroup ids are dealt round-robin over the 8 XCDs (private L2s).  The pair (row group ug,
+    // head h) picks the XCD: key = h + H_kv ug, class key mod 8; the JS slices of one pair share a
+    // class, so its rows of P are fetched into one L2 only, and the rows of U[h] into at most
+    // 8 / H_kv of them (one when H_kv >= 8).
     TS(2, 0);
-    const int ug = blockIdx.x / p.c_stride;
-    const int hs = blockIdx.x - ug * p.c_stride;
-    if (hs >= p.Hkv * p.JS) return;
-    const int h = hs / p.JS, s = hs - h * p.JS;
+    const int w8 = blockIdx.x >> 3;
+    const int s = w8 % p.JS, key = (w8 / p.JS) * 8 + (blockIdx.x & 7);
+    if (key >= p.NG * p.Hkv) return;
+    const int h = key % p.Hkv, ug = key / p.Hkv;
     const int ub0 = ug * NU;
     const int units_total = p.B * p.I;
     const int nunits = min(NU, units_total - ub0);
@@ -837,8 +839,8 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.rec = static_cast<int>(align_up(p.G * D + 2 * p.G, 4));   // 16-byte aligned records
     p.b_stride = static_cast<int>(align_up(p.Hkv * p.NC, 8));
     p.nvis_b = p.NRB * p.b_stride;
-    p.c_stride = static_cast<int>(align_up(p.Hkv * p.JS, 8));
-    p.nvis_c = p.I > 0 ? p.NG * p.c_stride : 0;
+    p.c_stride = 0;
+    p.nvis_c = p.I > 0 ? static_cast<int>(align_up(p.NG * p.Hkv, 8)) * p.JS : 0;
 
     const int nxc_max = (cap + kXC - 1) / kXC;
     size_t off = 0;
