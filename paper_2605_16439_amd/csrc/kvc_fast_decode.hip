@@ -73,7 +73,7 @@ struct Plan {
     int tiles_per_unit, vis_tiles, nvis_a;
     int UP, NT, NG, JS, NXC, nparts, rec;
     int merge, nvp;                 // one part per workgroup (its image blocks merged); vision parts per (b, head)
-    int nvis_b, b_stride, nvis_c, c_stride;
+    int nvis_b, nvis_c;
     float scale;
 #if defined(KVC_TIMELINE)
     unsigned long long *tl;         // timeline slots, see TS()
@@ -319,12 +319,13 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
 
-    // rb is the slow index and its stride is a multiple of 8, so the workgroups that share a
-    // (head, chunk) slice of theta land on the same XCD and share its L2
-    const int rb = blockIdx.x / p.b_stride;
-    const int hc = blockIdx.x - rb * p.b_stride;
-    if (hc >= p.Hkv * p.NC) return;
-    const int h = hc / p.NC, pc = hc - h * p.NC;
+    // Workgroup ids are dealt round-robin over the 8 XCDs (private L2s).  The pair (row block rb,
+    // head h) picks the XCD (key = h + H_kv rb, class key mod 8): its rows of S reach one L2 only,
+    // and a chunk of theta[h] at most 8 / H_kv of them.
+    const int w8 = blockIdx.x >> 3;
+    const int pc = w8 % p.NC, key = (w8 / p.NC) * 8 + (blockIdx.x & 7);
+    if (key >= p.NRB * p.Hkv) return;
+    const int h = key % p.Hkv, rb = key / p.Hkv;
 
     TS(1, 0);
     const int LDT = p.m_pad + 8;
@@ -837,9 +838,7 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.nvp = (p.merge ? p.I / (p.NT * p.UP) : p.I) * p.JS;
     p.nparts = p.nvp + p.NXC;
     p.rec = static_cast<int>(align_up(p.G * D + 2 * p.G, 4));   // 16-byte aligned records
-    p.b_stride = static_cast<int>(align_up(p.Hkv * p.NC, 8));
-    p.nvis_b = p.NRB * p.b_stride;
-    p.c_stride = 0;
+    p.nvis_b = static_cast<int>(align_up(p.NRB * p.Hkv, 8)) * p.NC;
     p.nvis_c = p.I > 0 ? static_cast<int>(align_up(p.NG * p.Hkv, 8)) * p.JS : 0;
 
     const int nxc_max = (cap + kXC - 1) / kXC;
