@@ -728,8 +728,11 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
     __shared__ float sSc[kMaxParts + 64];
     __shared__ float sRed[2][3];
     TS(3, 0);
-    const int bg = blockIdx.x, b = bg / p.Hq, gq = bg - b * p.Hq;
-    const int h = gq / p.G, g = gq - h * p.G;
+    // the head is the fast index of the workgroup id: ids are dealt round-robin over the XCDs, so a
+    // head's rows are finished on the XCDs whose L2 saw its parts being written
+    const int h = blockIdx.x % p.Hkv, bgi = blockIdx.x / p.Hkv;
+    const int b = bgi / p.G, g = bgi - b * p.G;
+    const int bg = b * p.Hq + h * p.G + g;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rec = p.rec, GD = p.G * D;
     const float *yb = p.Ypart + static_cast<size_t>(b * p.Hkv + h) * p.nparts * rec;
