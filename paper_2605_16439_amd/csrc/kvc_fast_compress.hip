@@ -38,7 +38,8 @@ struct CPlan {
 __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // element (channel c, position p of the tile) of the transposed tile; 16-byte chunks of a row
-// are XOR-swizzled with the channel group so the transposing stores spread over the banks
+// are XOR-swizzled with the index of the channel's 16-row MFMA tile: the transposing stores
+// spread over the banks and the operand reads of one tile stay conflict-free
 __device__ inline int sv_index(int c, int p) { return c * kLD + ((((p >> 3) ^ (c >> 4)) & 7) << 3) + (p & 7); }
 
 // MT = tiles per wavefront: a workgroup covers up to 64 MT rows of U, so V is read

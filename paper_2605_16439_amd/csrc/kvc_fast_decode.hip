@@ -49,7 +49,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-// 16-byte and 8-byte register images as native vectors (HIP's u32x4 / f32x2 structs turn plain
+// 16-byte and 8-byte register images as native vectors (HIP's uint4 / float2 structs turn plain
 // copies into memcpy through private memory, which ends up in scratch)
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -107,8 +107,9 @@ __device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, 
 __device__ inline float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ inline float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 // element (channel c, row x) of the transposed text-value tile; the 16-byte chunks of a channel
-// row are XOR-swizzled with the channel group so the transposing stores spread over the banks
-__device__ inline int vt_index(int c, int x) { return c * kLDV + ((((x >> 3) ^ (c >> 3)) & (kXC / 8 - 1)) << 3) + (x & 7); }
+// row are XOR-swizzled with the index of the channel's 16-row MFMA tile: the transposing stores
+// spread over the banks and the operand reads of one tile stay conflict-free
+__device__ inline int vt_index(int c, int x) { return c * kLDV + ((((x >> 3) ^ (c >> 4)) & (kXC / 8 - 1)) << 3) + (x & 7); }
 
 // ------------------------------------------------------------------------------------------
 // fa_scores: Alg. 1 step 1 on the compressed keys (vision workgroups), and the complete
