@@ -404,3 +404,19 @@ def test_fast_path_without_append_and_vision_only():
     torch.cuda.synchronize()
     ref, _ = orc.reconstruct_attend_decode(f64(q), gKc, gVc, th, U, mu, w.n_img_tokens, None, None, 0)
     assert row_rel_err(f64(L.out), ref) <= tol(w)
+
+
+@pytest.mark.parametrize("hq,hkv,batch,images", [
+    (4, 4, 2, 32),      # G = 1, two tiles of 16 blocks per workgroup
+    (4, 4, 1, 16),      # G = 1, one tile
+    (8, 2, 2, 8),       # G = 4
+    (16, 2, 2, 4),      # G = 8
+    (14, 2, 2, 8),      # G = 7, two tiles
+    (14, 2, 1, 2),      # G = 7, one tile
+])
+def test_fast_path_merged_part_records(hq, hkv, batch, images):
+    """Shapes in which the image blocks of a fused-kernel workgroup belong to one batch element, so
+    their partial outputs are rescaled to a common maximum and merged into one part record."""
+    w = FAST.with_(name=f"fast_merge_{hq}_{hkv}_{batch}_{images}", index=50 + hq + images,
+                   n_q_heads=hq, n_kv_heads=hkv, batch=batch, n_images=images, text_len=20, steps=2)
+    check_layer(w, 103, steps=(0, 1))
