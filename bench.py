@@ -57,9 +57,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--generic", action="store_true", help="force the scalar kernels")
-    ap.add_argument("--read-probe", type=int, default=0, metavar="GiB",
-                    help="also time a plain streaming read-sum over this many GiB and report it as "
-                         "roofline.measured_read_ceiling (GB/s)")
+    ap.add_argument("--read-probe", type=int, default=4, metavar="GiB",
+                    help="time a plain streaming read over this many GiB and report it as "
+                         "roofline.measured_read_ceiling (GB/s); 0 skips it")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="also run 3 plain device copies of this many MiB (counter calibration "
                          "for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)")
