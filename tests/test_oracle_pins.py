@@ -341,3 +341,53 @@ def test_capsule_size_matches_ratio():
         Kc, Vc = orc.compress(K, K, idx, np.zeros((1, m, n)), np.zeros((1, 2)), n, 1, 0)
         assert (Kc.size + Vc.size) / (2.0 * K.size) == m / n
         assert abs(m / n - (1 - c)) < 1.0 / n
+
+
+# ---------------------------------------------------------------- brute force on a tiny case
+def test_brute_force_python_loops_on_tiny_case():
+    """Sec. 3.1 / 3.2 written out a second time as scalar Python loops (no matrix routines):
+    compress, reconstruct, joint softmax over vision and text, GQA, new-token append."""
+    import math
+    B, Hq, Hkv, d, n, I, m, t = 2, 4, 2, 3, 5, 2, 3, 2
+    G = Hq // Hkv
+    r = rng(77)
+    K = r.standard_normal((B, Hkv, 1 + I * n + 1, d))        # one row before and after the span
+    V = r.standard_normal((B, Hkv, 1 + I * n + 1, d))
+    idx = np.array([0, 2, 4], dtype=np.int32)
+    theta = r.standard_normal((Hkv, m, n))
+    U = r.standard_normal((Hkv, m, n))
+    mu = r.standard_normal((Hkv, d))
+    q = r.standard_normal((B, Hq, d))
+    Kt = r.standard_normal((B, Hkv, t + 1, d))
+    Vt = r.standard_normal((B, Hkv, t + 1, d))
+    kn, vn = r.standard_normal((B, Hkv, d)), r.standard_normal((B, Hkv, d))
+    scale = 0.7
+
+    Kc, Vc = orc.compress(K, V, idx, U, mu, n, I, 1)
+    out, lse = orc.reconstruct_attend_decode(q, Kc, Vc, theta, U, mu, n, Kt.copy(), Vt.copy(), t, kn, vn,
+                                             scale)
+    for b in range(B):
+        for gq in range(Hq):
+            h = gq // G
+            keys, vals = [], []
+            for i in range(I):
+                # capsule of block i
+                kc = [[K[b, h, 1 + i * n + idx[j], c] for c in range(d)] for j in range(m)]
+                vc = [[sum(U[h, j, p] * (V[b, h, 1 + i * n + p, c] - mu[h, c]) for p in range(n))
+                       for c in range(d)] for j in range(m)]
+                for p in range(n):
+                    keys.append([sum(theta[h, j, p] * kc[j][c] for j in range(m)) for c in range(d)])
+                    vals.append([sum(U[h, j, p] * vc[j][c] for j in range(m)) + mu[h, c] for c in range(d)])
+            for x in range(t):
+                keys.append(list(Kt[b, h, x]))
+                vals.append(list(Vt[b, h, x]))
+            keys.append(list(kn[b, h]))
+            vals.append(list(vn[b, h]))
+            logits = [scale * sum(q[b, gq, c] * k[c] for c in range(d)) for k in keys]
+            mx = max(logits)
+            w = [math.exp(s - mx) for s in logits]
+            z = sum(w)
+            for c in range(d):
+                y = sum(w[x] * vals[x][c] for x in range(len(vals))) / z
+                assert abs(out[b, gq, c] - y) < 1e-12
+            assert abs(lse[b, gq] - (mx + math.log(z))) < 1e-12
