@@ -420,3 +420,30 @@ def test_fast_path_merged_part_records(hq, hkv, batch, images):
     w = FAST.with_(name=f"fast_merge_{hq}_{hkv}_{batch}_{images}", index=50 + hq + images,
                    n_q_heads=hq, n_kv_heads=hkv, batch=batch, n_images=images, text_len=20, steps=2)
     check_layer(w, 103, steps=(0, 1))
+
+
+def test_decode_replayed_from_a_hip_graph():
+    """The decode call only enqueues kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so after one warm-up call it can be captured into a HIP graph.  Replays,
+    with eager calls and synchronisations between them, must reproduce the eager result."""
+    w = FAST.with_(name="fast_graph", index=47, n_images=4)
+    L = Layer(w, 103)
+    L.compress()
+    q, kn, vn = synth.make_step_inputs(w, 0, 0)
+    gq, gkn, gvn = q.to(DEV), kn.to(DEV), vn.to(DEV)
+    eager, _ = L.decode(gq, w.text_len, gkn, gvn)              # warm-up outside the capture
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            kv.kvc_reconstruct_attend_decode(L.shape, L.params, gq, L.gKc, L.gVc, L.gKt, L.gVt,
+                                             w.text_len, w.text_cap, gkn, gvn, 0.0, L.out, L.lse, L.ws,
+                                             stream=s)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        L.out.zero_()
+        L.ws.fill_(0x5A)                                       # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(f64(L.out), eager), f"replay {rep} differs from the eager call"
