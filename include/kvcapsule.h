@@ -15,6 +15,10 @@
  *  - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL is
  *    the default stream) and return without synchronising.  Calls that share a
  *    workspace must be ordered on one stream.
+ *  - The first call for a kernel variant on a device also sets a function
+ *    attribute (dynamic LDS limit); every later call consists of kernel launches
+ *    only -- no allocation, memset, copy or synchronisation -- and may be captured
+ *    into a HIP graph.
  *  - Tensors are dense row-major with head_dim fastest unless strides are
  *    passed.  Every pointer must be 16-byte aligned.
  *  - The return value is a kvc_status; a negative value means nothing was
