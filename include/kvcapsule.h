@@ -31,7 +31,7 @@
  *    t text tokens in the cache.
  *  - Every valid shape is served.  The matrix-core (MFMA) kernels cover bf16 with
  *    d = 128: compression for n a multiple of 64; decode for n in {256, 576, 1024},
- *    G in {1, 4, 7, 8} and at most 256 partial results per (batch element, KV head).
+ *    G in {1, 2, 4, 6, 7, 8} and at most 256 partial results per (batch element, KV head).
  *    Other shapes, and fp32, run shape-agnostic scalar kernels: same results within
  *    rounding, far lower speed.
  */

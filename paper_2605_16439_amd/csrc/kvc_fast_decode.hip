@@ -809,8 +809,9 @@ int units_per_group(int G)
 {
     switch (G) {        // group sizes with a compiled kernel
     case 1: return 16;
+    case 2: return 8;
     case 4: return 4;
-    case 7: case 8: return 2;
+    case 6: case 7: case 8: return 2;
     default: return 0;
     }
 }
@@ -945,7 +946,9 @@ bool launch_for_group(const Plan &p, const DecodeCall &c, bool first)
 {
     switch (p.G) {
     case 1: return launch_ac<1, 16>(p, c, first);
+    case 2: return launch_ac<2, 8>(p, c, first);
     case 4: return launch_ac<4, 4>(p, c, first);
+    case 6: return launch_ac<6, 2>(p, c, first);
     case 7: return launch_ac<7, 2>(p, c, first);
     default: return launch_ac<8, 2>(p, c, first);
     }

@@ -264,9 +264,9 @@ def test_repeat_calls_are_deterministic_and_workspace_is_reusable():
 FAST = synth.Workload("fast_small", 20, 1, 2, 14, 2, 128, "bf16", 256, 3, 0.6, 40, 3)
 
 
-@pytest.mark.parametrize("hq,hkv", [(4, 4), (8, 2), (14, 2), (16, 2)])
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (4, 2), (8, 2), (12, 2), (14, 2), (16, 2)])
 def test_fast_path_group_sizes(hq, hkv):
-    """Every compiled group size G = H_q / H_kv (1, 4, 7, 8), ragged row tiles included."""
+    """Every compiled group size G = H_q / H_kv (1, 2, 4, 6, 7, 8), ragged row tiles included."""
     w = FAST.with_(name=f"fast_g{hq // hkv}", index=20 + hq, n_q_heads=hq, n_kv_heads=hkv, batch=3)
     m = orc.compressed_len(w.n_img_tokens, w.compression)
     assert kv.lib().kvc_workspace_bytes is not None
@@ -409,7 +409,9 @@ def test_fast_path_without_append_and_vision_only():
 @pytest.mark.parametrize("hq,hkv,batch,images", [
     (4, 4, 2, 32),      # G = 1, two tiles of 16 blocks per workgroup
     (4, 4, 1, 16),      # G = 1, one tile
+    (4, 2, 2, 16),      # G = 2
     (8, 2, 2, 8),       # G = 4
+    (12, 2, 2, 4),      # G = 6
     (16, 2, 2, 4),      # G = 8
     (14, 2, 2, 8),      # G = 7, two tiles
     (14, 2, 1, 2),      # G = 7, one tile
