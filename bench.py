@@ -156,18 +156,24 @@ def main():
     for step in warm:                       # warm-up: same slot, text length not advanced
         for a in step:
             layer_step(a)
+    # the timed region is also bracketed by one pair of HIP events on the launch stream: the device
+    # time of the K x L calls, launch gaps between them included, with nothing recorded in between
+    ev_beg, ev_end = ev(), ev()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    ev_beg.record()
     for step in timed:                      # timed: text cache grows by one token per step
         for a in step:
             layer_step(a)
+    ev_end.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     wall = t1 - t0
     assert bool(torch.isfinite(out.float()).all()), "non-finite attention output"
+    call_us = ev_beg.elapsed_time(ev_end) * 1e3 / (K * L)
 
-    # ---- device time of the decode call, HIP events on the launch stream -------------------------
-    # (second identical pass, so the event records do not perturb the wall-clock figure above)
+    # second identical pass with an event pair around every single call (each pair adds about 2 us
+    # of stream work, so this figure is an upper bound of the per-call device time)
     pairs = []
     for step in timed:
         for a in step:
@@ -177,7 +183,7 @@ def main():
             e1.record()
             pairs.append((e0, e1))
     torch.cuda.synchronize()
-    call_us = sum(a.elapsed_time(b) for a, b in pairs) * 1e3 / len(pairs)
+    call_us_pairs = sum(a.elapsed_time(b) for a, b in pairs) * 1e3 / len(pairs)
 
     if args.copy_probe:
         src = torch.empty(args.copy_probe << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -226,6 +232,7 @@ def main():
                      "traffic": traffic["bytes_per_call"] if traffic else None,
                      "kernel": "kvc_reconstruct_attend_decode (fa_scores + fb_probs + fc_fused + fd_finalize)",
                      "algorithmic_bytes_per_launch": abytes, "us_per_launch": call_us,
+                     "us_per_launch_event_pair_each": call_us_pairs,
                      "measured_read_ceiling": read_ceiling},
         "compress": {"ms_per_layer": comp_ms / (L * copies),
                      "tflops": 2.0 * w.batch * w.n_kv_heads * w.n_images * (sum(ms) / L)
