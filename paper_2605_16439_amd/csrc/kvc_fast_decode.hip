@@ -342,10 +342,11 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
     const int KS = p.m_pad / 32;
     constexpr int SB = 4 * KS4;
     u32x4 sfr[SB];
+    // (steps of the last group that lie beyond KS are not loaded at all: uniform tests, loads only)
 #pragma unroll
     for (int k = 0; k < SB; ++k) {
-        sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * min(k, KS - 1));
-        if (k >= KS || !wave_live) sfr[k] = u32x4_mk(0, 0, 0, 0);
+        sfr[k] = u32x4_mk(0, 0, 0, 0);
+        if (wave_live && (k < SB - 4 || k < KS)) sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * k);
     }
 
     TS(1, 1);
@@ -360,13 +361,18 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
         const int j0 = 2 * jp;
         u32x4 tv[FB][2];
 #pragma unroll
-        for (int k = 0; k < FB; ++k)
+        for (int k = 0; k < FB; ++k) {
+            tv[k][0] = u32x4_mk(0, 0, 0, 0);
+            tv[k][1] = u32x4_mk(0, 0, 0, 0);
+            if (k < FB - 2 || 64 * k < p.m) {                // a whole pass beyond m is not loaded (uniform test)
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int j = j0 + 64 * k + e;               // rows beyond m are clamped, then zeroed
-                tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(min(j, p.m - 1)) * p.n);
-                if (j >= p.m) tv[k][e] = u32x4_mk(0, 0, 0, 0);
+                for (int e = 0; e < 2; ++e) {
+                    const int j = j0 + 64 * k + e;           // single rows beyond m are clamped, then zeroed
+                    tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(min(j, p.m - 1)) * p.n);
+                    if (j >= p.m) tv[k][e] = u32x4_mk(0, 0, 0, 0);
+                }
             }
+        }
 #pragma unroll
         for (int k = 0; k < FB; ++k) {
             const int j = j0 + 64 * k;
