@@ -55,7 +55,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int D = 128;          // head_dim of this path
-constexpr int kRB = 64;         // query rows per fb_probs workgroup (4 waves x 16)
+constexpr int kRB = 128;        // query rows are padded to this: fb_probs workgroups take 64 or 128 (4 or 8 waves)
 constexpr int kPC = 64;         // positions per fb_probs workgroup (one softmax tile)
 constexpr int kTPW = 2;         // 16-row key tiles per wavefront in fa_scores
 constexpr int kJC = 64;         // capsule rows per fc_fused workgroup (one 16-row tile per wave)
@@ -69,7 +69,7 @@ constexpr size_t kLdsBudget = 150 * 1024;
 
 struct Plan {
     int B, Hq, Hkv, G, n, I, m, t, t_in, cap;
-    int R, R_pad, NRB, m_pad, m16, NC;
+    int R, R_pad, NRB, RBW, m_pad, m16, NC;   // RBW: waves (16-row tiles) per fb_probs workgroup
     int tiles_per_unit, vis_tiles, nvis_a;
     int UP, NT, NG, JS, NXC, nparts, rec;
     int merge, nvp;                 // one part per workgroup (its image blocks merged); vision parts per (b, head)
@@ -312,8 +312,8 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
 // MFMA tile: A = theta^T (16 positions x 32 j) from LDS, B = S^T (32 j x 16 rows) from
 // memory, D[pos][row]: a lane ends up with 4 consecutive positions of one row.
 // ------------------------------------------------------------------------------------------
-template <int KS4>
-__global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restrict__ theta)
+template <int KS4, int NW>
+__global__ __launch_bounds__(64 * NW) void fb_probs(Plan p, const uint16_t *__restrict__ theta)
 {
     extern __shared__ __align__(16) uint16_t lds[];
     constexpr int PC = kPC;
@@ -333,7 +333,7 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
     uint16_t *ThT = lds;                 // [PC][LDT]   theta chunk, transposed: ThT[pos][j]
 
     // scores of this wave's 16 rows: first batch of fragments in flight during the LDS fill
-    const int r0 = rb * kRB + wave * 16;
+    const int r0 = rb * (16 * NW) + wave * 16;
     const bool wave_live = r0 < p.R;
     const int r = r0 + r16;
     const uint16_t *srow = p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + 8 * kg;
@@ -353,21 +353,22 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
     // ---- stage the theta chunk, transposed, in LDS -------------------------------------------------
     // a thread owns a pair of consecutive rows j, j+1 and 8 positions; the pair is packed so the
     // transposed store is one 32-bit word per position
+    constexpr int RPP = 16 * NW;                           // rows of theta per pass of the workgroup
     const int seg = (lane >> 4) + 4 * (wave & 1);          // 16-byte segment of the chunk row
-    const int jp = (lane & 15) + 16 * (wave >> 1);         // row pair within a pass of 64 rows
+    const int jp = (lane & 15) + 16 * (wave >> 1);         // row pair within a pass of RPP rows
     {
         const uint16_t *th = theta + static_cast<size_t>(h) * p.m * p.n + pc * PC + 8 * seg;
-        constexpr int FB = 2 * KS4;              // passes of 64 rows: 64 FB >= m_pad, all in one batch
+        constexpr int FB = 128 * KS4 / RPP;      // passes of RPP rows: RPP FB >= m_pad, all in one batch
         const int j0 = 2 * jp;
         u32x4 tv[FB][2];
 #pragma unroll
         for (int k = 0; k < FB; ++k) {
             tv[k][0] = u32x4_mk(0, 0, 0, 0);
             tv[k][1] = u32x4_mk(0, 0, 0, 0);
-            if (k < FB - 2 || 64 * k < p.m) {                // a whole pass beyond m is not loaded (uniform test)
+            if (k < FB - 2 || RPP * k < p.m) {               // a whole pass beyond m is not loaded (uniform test)
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
-                    const int j = j0 + 64 * k + e;           // single rows beyond m are clamped, then zeroed
+                    const int j = j0 + RPP * k + e;          // single rows beyond m are clamped, then zeroed
                     tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(min(j, p.m - 1)) * p.n);
                     if (j >= p.m) tv[k][e] = u32x4_mk(0, 0, 0, 0);
                 }
@@ -375,7 +376,7 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
         }
 #pragma unroll
         for (int k = 0; k < FB; ++k) {
-            const int j = j0 + 64 * k;
+            const int j = j0 + RPP * k;
             if (j < p.m16) {
                 const uint32_t a[4] = {tv[k][0].x, tv[k][0].y, tv[k][0].z, tv[k][0].w};
                 const uint32_t c[4] = {tv[k][1].x, tv[k][1].y, tv[k][1].z, tv[k][1].w};
@@ -389,7 +390,7 @@ __global__ __launch_bounds__(256) void fb_probs(Plan p, const uint16_t *__restri
         }
         // zero the k padding of the transposed chunk: columns [m16, m_pad)
         const int padc = p.m_pad - p.m16;
-        for (int idx = threadIdx.x; idx < PC * padc; idx += 256) {
+        for (int idx = threadIdx.x; idx < PC * padc; idx += 64 * NW) {
             const int pp = idx / padc, j = p.m16 + idx - pp * padc;
             ThT[pp * LDT + j] = 0;
         }
@@ -830,7 +831,10 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.t = t; p.t_in = t_in; p.cap = cap; p.scale = scale;
     p.R = p.B * p.I * p.G;
     p.R_pad = static_cast<int>(align_up(p.R > 0 ? p.R : 1, kRB));
-    p.NRB = p.I > 0 ? p.R_pad / kRB : 0;
+    // 64-row workgroups unless they would need more than two rounds over the CUs: then 128 rows per
+    // workgroup re-read the theta chunk half as often
+    p.RBW = (p.I > 0 && static_cast<long>(p.R_pad / 64) * p.Hkv * (p.n / kPC) > 512) ? 8 : 4;
+    p.NRB = p.I > 0 ? (p.R_pad + 16 * p.RBW - 1) / (16 * p.RBW) : 0;
     p.m_pad = static_cast<int>(align_up(p.m, 32));
     p.m16 = static_cast<int>(align_up(p.m, 16));
     p.NC = p.n / kPC;
@@ -890,12 +894,17 @@ void launch_d(const Plan &p, const DecodeCall &c)
     }
 }
 
-template <int KS4> bool launch_b1(const Plan &p, const DecodeCall &c)
+template <int KS4, int NW> bool launch_b2(const Plan &p, const DecodeCall &c)
 {
     static bool attr_set[kMaxDevices] = {};
-    if (!allow_lds(reinterpret_cast<const void *>(fb_probs<KS4>), kLdsBudget, attr_set)) return false;
-    fb_probs<KS4><<<p.nvis_b, 256, lds_b(p.m_pad), c.stream>>>(p, static_cast<const uint16_t *>(c.theta));
+    if (!allow_lds(reinterpret_cast<const void *>(fb_probs<KS4, NW>), kLdsBudget, attr_set)) return false;
+    fb_probs<KS4, NW><<<p.nvis_b, 64 * NW, lds_b(p.m_pad), c.stream>>>(p, static_cast<const uint16_t *>(c.theta));
     return true;
+}
+
+template <int KS4> bool launch_b1(const Plan &p, const DecodeCall &c)
+{
+    return p.RBW == 8 ? launch_b2<KS4, 8>(p, c) : launch_b2<KS4, 4>(p, c);
 }
 
 bool launch_b(const Plan &p, const DecodeCall &c)
