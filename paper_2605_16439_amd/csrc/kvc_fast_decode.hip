@@ -10,7 +10,7 @@
 //               exp relative to the chunk's own maximum, P V_text (V_text transposed through
 //               LDS), and write a finished part record; the one that owns row text_len also
 //               stores the new token's k, v (Sec. 3.2: text KV is kept as it is).
-//   fb_probs    L = S theta (step 2) as a skinny GEMM per KV head, 64 query rows x 64
+//   fb_probs    L = S theta (step 2) as a skinny GEMM per KV head, 64 (or 128) query rows x 64
 //               positions per workgroup with the theta chunk transposed into LDS on the way
 //               in; emits P = exp(L - tile max) in bf16 and the tile's (max, sum) per row.
 //   fc_fused    per (KV head, group of up to 32 query rows = whole image blocks, 64 rows j
@@ -307,8 +307,8 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
 }
 
 // ------------------------------------------------------------------------------------------
-// fb_probs: Alg. 1 step 2 and the numerator of the softmax for one tile of 64 rows x 64
-// positions: L[r][pos] = sum_j S[r][j] theta[j][pos], P = exp(L - tile max).
+// fb_probs: Alg. 1 step 2 and the numerator of the softmax for one tile of 16 NW rows x 64
+// positions (NW waves, one 16-row MFMA tile each): L[r][pos] = sum_j S[r][j] theta[j][pos], P = exp(L - tile max).
 // MFMA tile: A = theta^T (16 positions x 32 j) from LDS, B = S^T (32 j x 16 rows) from
 // memory, D[pos][row]: a lane ends up with 4 consecutive positions of one row.
 // ------------------------------------------------------------------------------------------
