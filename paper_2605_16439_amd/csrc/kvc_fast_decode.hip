@@ -39,10 +39,8 @@
 //  * MFMA results are stored directly (no cross-lane reductions beyond two steps) and code stays
 //    small (cold instruction cache per launch).
 //
-// Query rows of one KV head: image block ub = b*I + i owns G consecutive rows (one per query head of
-// the group), and UPB whole image blocks fill a 64-row block (UPB a multiple of the image blocks
-// one fc_fused workgroup handles, the rest of the 64 rows unused), so that consecutive image blocks
-// share MFMA tiles and a workgroup of fc_fused depends on one 64-row block of fb_probs only.
+// Query rows of one KV head are ordered r = (b*I + i)*G + g, so the G query heads of a
+// group and consecutive image blocks share MFMA tiles.
 #include "kvc_internal.h"
 
 namespace kvc {
@@ -72,7 +70,6 @@ constexpr size_t kLdsBudget = 150 * 1024;
 struct Plan {
     int B, Hq, Hkv, G, n, I, m, t, t_in, cap;
     int R, R_pad, NRB, RBW, m_pad, m16, NC;   // RBW: waves (16-row tiles) per fb_probs workgroup
-    int UPB, RV;                    // image blocks and valid rows per 64-row block of query rows
     int tiles_per_unit, vis_tiles, nvis_a;
     int UP, NT, NG, JS, NXC, nparts, rec;
     int merge, nvp;                 // one part per workgroup (its image blocks merged); vision parts per (b, head)
@@ -113,11 +110,6 @@ __device__ inline float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff000
 // row are XOR-swizzled with the index of the channel's 16-row MFMA tile: the transposing stores
 // spread over the banks and the operand reads of one tile stay conflict-free
 __device__ inline int vt_index(int c, int x) { return c * kLDV + ((((x >> 3) ^ (c >> 4)) & (kXC / 8 - 1)) << 3) + (x & 7); }
-
-// first query row of image block ub (b*I + i) of a KV head
-__device__ inline int unit_row(const Plan &p, int ub) { const int blk = ub / p.UPB; return blk * 64 + (ub - blk * p.UPB) * p.G; }
-// rows of a 64-row block beyond its image blocks, and blocks beyond the last image block, hold nothing
-__device__ inline bool row_valid(const Plan &p, int r) { return (r & 63) < p.RV && r < p.R; }
 
 // ------------------------------------------------------------------------------------------
 // fa_scores: Alg. 1 step 1 on the compressed keys (vision workgroups), and the complete
@@ -297,7 +289,7 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
         const int u = tile / p.tiles_per_unit, jt = tile - u * p.tiles_per_unit;
         const int bh = u / p.I, i = u - bh * p.I;
         const int b = bh / p.Hkv, h = bh - b * p.Hkv;
-        const int r = unit_row(p, b * p.I + i) + r16;
+        const int r = (b * p.I + i) * G + r16;
         const int j = jt * 16 + 4 * kg;
         uint32_t w[2];
 #pragma unroll
@@ -432,18 +424,17 @@ __global__ __launch_bounds__(64 * NW) void fb_probs(Plan p, const uint16_t *__re
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     float sum = 0.f;
-    const bool valid = row_valid(p, r);
     uint16_t *prow = p.P + (static_cast<size_t>(h) * p.R_pad + r) * p.n + pc * PC + 4 * kg;
 #pragma unroll
     for (int mt = 0; mt < PC / 16; ++mt) {
         const uint32_t a0 = f32_to_bf16_bits(__expf(acc[mt][0] - mx)), a1 = f32_to_bf16_bits(__expf(acc[mt][1] - mx));
         const uint32_t a2 = f32_to_bf16_bits(__expf(acc[mt][2] - mx)), a3 = f32_to_bf16_bits(__expf(acc[mt][3] - mx));
         sum += __uint_as_float(a0 << 16) + __uint_as_float(a1 << 16) + __uint_as_float(a2 << 16) + __uint_as_float(a3 << 16);
-        if (valid) *reinterpret_cast<u32x2 *>(prow + 16 * mt) = u32x2_mk(a0 | (a1 << 16), a2 | (a3 << 16));
+        if (r < p.R) *reinterpret_cast<u32x2 *>(prow + 16 * mt) = u32x2_mk(a0 | (a1 << 16), a2 | (a3 << 16));
     }
     sum += __shfl_xor(sum, 16, 64);
     sum += __shfl_xor(sum, 32, 64);
-    if (kg == 0 && valid) p.stats[(static_cast<size_t>(h) * p.R_pad + r) * p.NC + pc] = f32x2_mk(mx, sum);
+    if (kg == 0 && r < p.R) p.stats[(static_cast<size_t>(h) * p.R_pad + r) * p.NC + pc] = f32x2_mk(mx, sum);
     TS(1, 4);
 }
 
@@ -492,7 +483,6 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
     const int ub0 = ug * NU;
     const int units_total = p.B * p.I;
     const int nunits = min(NU, units_total - ub0);
-    const int row0 = unit_row(p, ub0);                   // the workgroup's image blocks are consecutive rows of one 64-row block
     const int lo = s * kJC, hi = min(p.m, lo + kJC);
     uint16_t *sP = dyn;
 
@@ -505,7 +495,7 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
     const int prow_i = threadIdx.x >> 4, psub = threadIdx.x & 15;
     {
         const int pr = min(prow_i, NR - 1);
-        const int r = row0 + min((pr >> 4) * (UP * G) + min(pr & 15, UP * G - 1), nunits * G - 1);
+        const int r = min(ub0 * G + (pr >> 4) * (UP * G) + (pr & 15), p.R - 1);
         const u32x4 *prow = reinterpret_cast<const u32x4 *>(p.P + (static_cast<size_t>(h) * p.R_pad + r) * n);
 #pragma unroll
         for (int k = 0; k < KP; ++k) pfr[k] = prow[min(16 * k + psub, PCH - 1)];
@@ -515,7 +505,7 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
 #pragma unroll
     for (int k = 0; k < NC; ++k) st[k] = f32x2_mk(0.f, 0.f);
     if (wave == 0) {
-        const int r = row0 + min(min(kg, NT - 1) * (UP * G) + min(r16, UP * G - 1), nunits * G - 1);
+        const int r = min(ub0 * G + min(kg, NT - 1) * (UP * G) + r16, p.R - 1);
         const f32x2 *sp = p.stats + (static_cast<size_t>(h) * p.R_pad + r) * NC;
 #pragma unroll
         for (int k = 0; k < NC; ++k) st[k] = sp[k];
@@ -839,15 +829,7 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.B = s.batch; p.Hq = s.n_q_heads; p.Hkv = s.n_kv_heads; p.G = p.Hq / p.Hkv;
     p.n = s.n_img_tokens; p.I = s.n_images; p.m = s.m;
     p.t = t; p.t_in = t_in; p.cap = cap; p.scale = scale;
-    p.UP = units_per_group(p.G);
-    // two MFMA tiles of query rows per workgroup halve the re-streaming of U when the rows are there
-    p.NT = (p.UP && p.B * p.I > p.UP) ? 2 : 1;
-    {
-        const int nu = p.UP ? p.NT * p.UP : 1, units = p.B * p.I;
-        p.UPB = p.UP ? (64 / p.G) / nu * nu : 1;
-        p.RV = p.UPB * p.G;
-        p.R = units > 0 ? ((units - 1) / p.UPB) * 64 + ((units - 1) % p.UPB + 1) * p.G : 0;
-    }
+    p.R = p.B * p.I * p.G;
     p.R_pad = static_cast<int>(align_up(p.R > 0 ? p.R : 1, kRB));
     // 64-row workgroups unless they would need more than two rounds over the CUs: then 128 rows per
     // workgroup re-read the theta chunk half as often
@@ -859,6 +841,9 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.tiles_per_unit = p.m16 / 16;
     p.vis_tiles = p.B * p.Hkv * p.I * p.tiles_per_unit;
     p.nvis_a = (p.vis_tiles + 4 * kTPW - 1) / (4 * kTPW);
+    p.UP = units_per_group(p.G);
+    // two MFMA tiles of query rows per workgroup halve the re-streaming of U when the rows are there
+    p.NT = (p.UP && p.B * p.I > p.UP) ? 2 : 1;
     p.NG = p.UP ? (p.B * p.I + p.NT * p.UP - 1) / (p.NT * p.UP) : 0;
     p.JS = (p.m + kJC - 1) / kJC;
     p.NXC = (t + kXC - 1) / kXC;
