@@ -75,9 +75,10 @@ typedef struct {
 /* Per-layer learned parameters, fixed at inference (Sec. 3.2). */
 typedef struct {
     const int32_t *key_idx; /* M : [m] strictly ascending indices in [0, n); shared  */
-                            /* by heads, blocks and batch (Sec. 3.1, Keys).  Not     */
-                            /* validated on the device: out-of-range entries are the */
-                            /* caller's error.  Unused by the decode call.           */
+                            /* by heads, blocks and batch (Sec. 3.1, Keys).  Lives   */
+                            /* in device memory, so it is not validated: an entry    */
+                            /* outside [0, n) is the caller's error and is read as   */
+                            /* the nearest row of the block.  Unused by decode.      */
     const void *theta;      /* theta : [H_kv][m][n] key / score reconstructor        */
                             /* (App. C; applied to scores in Alg. 1 step 2)          */
     const void *U;          /* U : [H_kv][m][n] value PCA basis (Sec. 3.1, Values)   */

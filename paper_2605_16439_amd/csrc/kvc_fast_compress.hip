@@ -86,7 +86,8 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
 #pragma unroll
         for (int k = 0; k < 4 * MT; ++k) {
             const int j = min(16 * (tile0 + k) + rl, p.m - 1);
-            kv[k] = *(reinterpret_cast<const u32x4 *>(ksrc + static_cast<int64_t>(idx[j]) * p.ss) + c16);
+            const int row = min(max(idx[j], 0), p.n - 1);      // an index outside the block must not leave it
+            kv[k] = *(reinterpret_cast<const u32x4 *>(ksrc + static_cast<int64_t>(row) * p.ss) + c16);
         }
 #pragma unroll
         for (int k = 0; k < 4 * MT; ++k) {

@@ -178,7 +178,8 @@ __global__ void g_gather(const T *__restrict__ K, const int32_t *__restrict__ id
     const size_t bh = blockIdx.z;
     const int b = static_cast<int>(bh / Hkv), h = static_cast<int>(bh % Hkv);
     const int i = blockIdx.y, j = blockIdx.x;
-    const T *src = K + b * sb + h * sh + (static_cast<int64_t>(vis0) + static_cast<int64_t>(i) * n + idx[j]) * ss;
+    const int row = min(max(idx[j], 0), n - 1);              // an index outside the block must not leave it
+    const T *src = K + b * sb + h * sh + (static_cast<int64_t>(vis0) + static_cast<int64_t>(i) * n + row) * ss;
     T *dst = Kc + ((bh * I + i) * m + j) * d;
     for (int c = threadIdx.x; c < d; c += blockDim.x) dst[c] = src[c];
 }

@@ -194,6 +194,24 @@ def test_strided_prefill_kv():
     assert block_rel_err(unpack_vc(L.gVc, m, w.head_dim), Vc_ref) <= tol(w)
 
 
+@pytest.mark.parametrize("generic", [True, False])
+def test_key_indices_outside_the_block_are_read_as_its_nearest_row(generic):
+    """M lives in device memory and cannot be validated by the host: the kernels clamp its entries
+    to the image block, so a bad index can neither leave the block nor the buffer."""
+    w = SMALL_BF16.with_(index=16, n_img_tokens=128)     # a block length the matrix-core kernel takes
+    m = 30
+    L = Layer(w, m, pre=4, post=4, generic=generic)
+    idx = L.p["key_idx"].clone()
+    idx[0], idx[1], idx[-1] = -7, -(1 << 30), w.n_img_tokens + (1 << 29)
+    g_idx = idx.to(DEV)
+    L.params = kv.make_params(g_idx, L.g["theta"], L.g["U"], L.g["mu"])
+    L.compress()
+    clamped = idx.clamp(0, w.n_img_tokens - 1).numpy()
+    Kc_ref, _ = orc.compress(f64(L.K), f64(L.V), clamped, f64(L.p["U"]), f64(L.p["mu"]),
+                             w.n_img_tokens, w.n_images, 4, store_code(w))
+    assert np.array_equal(f64(L.gKc), Kc_ref)
+
+
 def test_config1_tiny_fp32_full():
     w = synth.WORKLOADS["tiny"]
     m = orc.compressed_len(w.n_img_tokens, w.compression)
