@@ -99,6 +99,12 @@ constexpr size_t kTimelineBytes = 1 << 20;
 constexpr size_t kTimelineBytes = 0;
 #endif
 
+// The arguments of a kernel (the plan and the pointers after it) span two 128-byte lines of device
+// memory that no cache holds when a workgroup starts.  Naming one value of each line at the top of
+// the kernel makes the compiler fetch both at once, before the first test that could end the
+// workgroup, instead of paying one memory round trip after the other.
+#define KVC_FETCH_ARGS(first, last) asm volatile("" ::"s"(first), "s"(last))
+
 __host__ __device__ inline u32x4 u32x4_mk(unsigned a, unsigned b, unsigned c, unsigned d) { return u32x4{a, b, c, d}; }
 __host__ __device__ inline u32x2 u32x2_mk(unsigned a, unsigned b) { return u32x2{a, b}; }
 __host__ __device__ inline f32x4 f32x4_mk(float a, float b, float c, float d) { return f32x4{a, b, c, d}; }
@@ -126,6 +132,7 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
                                                  const uint16_t *__restrict__ k_new,
                                                  const uint16_t *__restrict__ v_new)
 {
+    KVC_FETCH_ARGS(p.B, v_new);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
     TS(0, 0);
@@ -315,6 +322,7 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
 template <int KS4, int NW>
 __global__ __launch_bounds__(64 * NW) void fb_probs(Plan p, const uint16_t *__restrict__ theta)
 {
+    KVC_FETCH_ARGS(p.B, theta);
     extern __shared__ __align__(16) uint16_t lds[];
     constexpr int PC = kPC;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -458,6 +466,7 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
                                                 const uint16_t *__restrict__ Vc)
 {
     static_assert(G * UP <= 16, "the rows of a tile must fit one MFMA tile");
+    KVC_FETCH_ARGS(p.B, Vc);
     constexpr int n = NC * kPC, LDP = n + 8;
     constexpr int NR = 16 * NT;
     constexpr int NU = NT * UP;                          // image blocks per workgroup
@@ -733,6 +742,7 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
                                                    uint16_t *__restrict__ out,
                                                    float *__restrict__ lse)
 {
+    KVC_FETCH_ARGS(p.B, lse);
     __shared__ float sSc[kMaxParts + 64];
     __shared__ float sRed[2][3];
     TS(3, 0);
