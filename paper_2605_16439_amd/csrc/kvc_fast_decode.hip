@@ -74,6 +74,8 @@ struct Plan {
     int UP, NT, NG, JS, NXC, nparts, rec;
     int merge, nvp;                 // one part per workgroup (its image blocks merged); vision parts per (b, head)
     int nvis_b, nvis_c;
+    // multipliers for the divisions by NXC, Hkv, tiles_per_unit, I, NC, JS and G (see quot())
+    unsigned qNXC, qHkv, qTPU, qI, qNC, qJS, qG;
     float scale;
 #if defined(KVC_TIMELINE)
     unsigned long long *tl;         // timeline slots, see TS()
@@ -98,6 +100,12 @@ constexpr size_t kTimelineBytes = 1 << 20;
 #define TS(KID, K) do { } while (0)
 constexpr size_t kTimelineBytes = 0;
 #endif
+
+// x / d for 0 <= x with x d < 2^32, as one multiplication by q = floor(2^32 / d) + 1 (q = 0 stands
+// for d = 1).  The index arithmetic at the top of every kernel sits in front of its first load; a
+// division by a run-time value costs some thirty dependent instructions there.
+__device__ inline int quot(int x, unsigned q) { return q ? static_cast<int>(__umulhi(static_cast<unsigned>(x), q)) : x; }
+inline unsigned quot_multiplier(int d) { return d > 1 ? static_cast<unsigned>((1ull << 32) / static_cast<unsigned>(d)) + 1u : 0u; }
 
 // The arguments of a kernel (the plan and the pointers after it) span two 128-byte lines of device
 // memory that no cache holds when a workgroup starts.  Naming one value of each line at the top of
@@ -143,8 +151,8 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
         __shared__ __align__(16) uint16_t sVt[D * kLDV];         // V^T [channel][row]
         __shared__ float sRed[2][4][16];                         // per-wave maxima / sums per head
         const int id = blockIdx.x - p.nvis_a;
-        const int bh = id / p.NXC, xc = id - bh * p.NXC;
-        const int b = bh / p.Hkv, h = bh - b * p.Hkv;
+        const int bh = quot(id, p.qNXC), xc = id - bh * p.NXC;
+        const int b = quot(bh, p.qHkv), h = bh - b * p.Hkv;
         const int lo = xc * kXC, hi = min(p.t, lo + kXC);
         const bool fresh = k_new != nullptr;                       // row t_in comes from k_new / v_new
         // value rows of the chunk (16 lanes per row, a lane takes pairs of consecutive rows) and key
@@ -264,9 +272,9 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
         const int tile = tile0 + tt;
         live[tt] = tile < p.vis_tiles;
         if (!live[tt]) continue;
-        const int u = tile / p.tiles_per_unit, jt = tile - u * p.tiles_per_unit;
-        const int bh = u / p.I;
-        const int b = bh / p.Hkv, h = bh - b * p.Hkv;
+        const int u = quot(tile, p.qTPU), jt = tile - u * p.tiles_per_unit;
+        const int bh = quot(u, p.qI);
+        const int b = quot(bh, p.qHkv), h = bh - b * p.Hkv;
         const int row = min(jt * 16 + r16, p.m - 1);
         const u32x4 *kp = reinterpret_cast<const u32x4 *>(Kc + (static_cast<size_t>(u) * p.m + row) * D) + kg;
 #pragma unroll
@@ -293,9 +301,9 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
         for (int ks = 0; ks < 4; ++ks)
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[tt][ks]), as_bf16x8(qf[tt][ks]), acc, 0, 0, 0);
         if (r16 >= G) continue;      // columns beyond the group are copies of head G-1
-        const int u = tile / p.tiles_per_unit, jt = tile - u * p.tiles_per_unit;
-        const int bh = u / p.I, i = u - bh * p.I;
-        const int b = bh / p.Hkv, h = bh - b * p.Hkv;
+        const int u = quot(tile, p.qTPU), jt = tile - u * p.tiles_per_unit;
+        const int bh = quot(u, p.qI), i = u - bh * p.I;
+        const int b = quot(bh, p.qHkv), h = bh - b * p.Hkv;
         const int r = (b * p.I + i) * G + r16;
         const int j = jt * 16 + 4 * kg;
         uint32_t w[2];
@@ -332,9 +340,10 @@ __global__ __launch_bounds__(64 * NW) void fb_probs(Plan p, const uint16_t *__re
     // head h) picks the XCD (key = h + H_kv rb, class key mod 8): its rows of S reach one L2 only,
     // and a chunk of theta[h] at most 8 / H_kv of them.
     const int w8 = blockIdx.x >> 3;
-    const int pc = w8 % p.NC, key = (w8 / p.NC) * 8 + (blockIdx.x & 7);
+    const int w8q = quot(w8, p.qNC);
+    const int pc = w8 - w8q * p.NC, key = w8q * 8 + (blockIdx.x & 7);
     if (key >= p.NRB * p.Hkv) return;
-    const int h = key % p.Hkv, rb = key / p.Hkv;
+    const int rb = quot(key, p.qHkv), h = key - rb * p.Hkv;
 
     TS(1, 0);
     const int LDT = p.m_pad + 8;
@@ -486,9 +495,10 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
     // 8 / H_kv of them (one when H_kv >= 8).
     TS(2, 0);
     const int w8 = blockIdx.x >> 3;
-    const int s = w8 % p.JS, key = (w8 / p.JS) * 8 + (blockIdx.x & 7);
+    const int w8q = quot(w8, p.qJS);
+    const int s = w8 - w8q * p.JS, key = w8q * 8 + (blockIdx.x & 7);
     if (key >= p.NG * p.Hkv) return;
-    const int h = key % p.Hkv, ug = key / p.Hkv;
+    const int ug = quot(key, p.qHkv), h = key - ug * p.Hkv;
     const int ub0 = ug * NU;
     const int units_total = p.B * p.I;
     const int nunits = min(NU, units_total - ub0);
@@ -551,7 +561,7 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
 #pragma unroll
         for (int a = 0; a < UBATCH; ++a) {
             const int ub = ub0 + min(un0 + a, nunits - 1);
-            const int b = ub / p.I, i = ub - b * p.I;
+            const int b = quot(ub, p.qI), i = ub - b * p.I;
             const uint16_t *vbase = Vc + (static_cast<size_t>(b * p.Hkv + h) * p.I + i) * p.m * D;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
@@ -692,7 +702,7 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
                 ysum[0] += w8 * o[0]; ysum[1] += w8 * o[1]; ysum[2] += w8 * o[2]; ysum[3] += w8 * o[3];
             } else if (un < nunits && un_mine == ul2 && r16 < un_lim) {
                 const int ub = ub0 + un;
-                const int b = ub / p.I, i = ub - b * p.I;
+                const int b = quot(ub, p.qI), i = ub - b * p.I;
                 float *yp = p.Ypart + (static_cast<size_t>(b * p.Hkv + h) * p.nparts + i * p.JS + s) * p.rec;
                 *reinterpret_cast<f32x4 *>(yp + g_mine * D + 16 * wave + 4 * kg) = f32x4_mk(o[0], o[1], o[2], o[3]);
                 if (wave == 0 && kg == 0) {
@@ -715,7 +725,7 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
             for (int e = 0; e < 4; ++e) ysum[e] += __shfl(ysum[e], (lane & 48) | ((r16 + G) & 15), 64);
         }
         if (r16 < G) {
-            const int b = ub0 / p.I, gi = (ub0 - b * p.I) / NU;
+            const int b = quot(ub0, p.qI), gi = (ub0 - b * p.I) / NU;
             float *yp = p.Ypart + (static_cast<size_t>(b * p.Hkv + h) * p.nparts + gi * p.JS + s) * p.rec;
             *reinterpret_cast<f32x4 *>(yp + r16 * D + 16 * wave + 4 * kg) = ysum;
             if (wave == 0 && kg == 0) {
@@ -748,8 +758,8 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
     TS(3, 0);
     // the head is the fast index of the workgroup id: ids are dealt round-robin over the XCDs, so a
     // head's rows are finished on the XCDs whose L2 saw its parts being written
-    const int h = blockIdx.x % p.Hkv, bgi = blockIdx.x / p.Hkv;
-    const int b = bgi / p.G, g = bgi - b * p.G;
+    const int bgi = quot(blockIdx.x, p.qHkv), h = blockIdx.x - bgi * p.Hkv;
+    const int b = quot(bgi, p.qG), g = bgi - b * p.G;
     const int bg = b * p.Hq + h * p.G + g;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int rec = p.rec, GD = p.G * D;
@@ -865,6 +875,8 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.rec = static_cast<int>(align_up(p.G * D + 2 * p.G, 4));   // 16-byte aligned records
     p.nvis_b = static_cast<int>(align_up(p.NRB * p.Hkv, 8)) * p.NC;
     p.nvis_c = p.I > 0 ? static_cast<int>(align_up(p.NG * p.Hkv, 8)) * p.JS : 0;
+    p.qNXC = quot_multiplier(p.NXC); p.qHkv = quot_multiplier(p.Hkv); p.qTPU = quot_multiplier(p.tiles_per_unit);
+    p.qI = quot_multiplier(p.I); p.qNC = quot_multiplier(p.NC); p.qJS = quot_multiplier(p.JS); p.qG = quot_multiplier(p.G);
 
     const int nxc_max = (cap + kXC - 1) / kXC;
     size_t off = 0;
@@ -999,6 +1011,16 @@ kvc_status fast_decode(const DecodeCall &c)
 {
     Plan p = make_plan(c.s, c.t, c.t_in, c.cap, c.scale, c.ws);
     if (p.nparts > kMaxParts) return generic_decode(c);
+    // quot(): every dividend is a workgroup, tile or image-block index, every divisor one of these
+    {
+        const long args[] = {static_cast<long>(p.nvis_a) * 4 * kTPW, static_cast<long>(p.B) * p.Hkv * p.NXC, p.nvis_b, p.nvis_c,
+                             static_cast<long>(p.B) * p.Hq, static_cast<long>(p.B) * p.Hkv * p.I + 64};
+        const int divs[] = {p.NXC, p.Hkv, p.tiles_per_unit, p.I, p.NC, p.JS, p.G};
+        long amax = 0, dmax = 1;
+        for (long a : args) amax = a > amax ? a : amax;
+        for (int d : divs) dmax = d > dmax ? d : dmax;
+        if (amax * dmax >= (1ll << 32)) return generic_decode(c);
+    }
     if (p.bytes > c.ws_bytes) return KVC_ERR_WORKSPACE;
 #if defined(KVC_TIMELINE)
     p.tl = c.ws_bytes >= p.bytes + kTimelineBytes
