@@ -110,8 +110,10 @@ inline unsigned quot_multiplier(int d) { return d > 1 ? static_cast<unsigned>((1
 // The arguments of a kernel (the plan and the pointers after it) span two 128-byte lines of device
 // memory that no cache holds when a workgroup starts.  Naming one value of each line at the top of
 // the kernel makes the compiler fetch both at once, before the first test that could end the
-// workgroup, instead of paying one memory round trip after the other.
-#define KVC_FETCH_ARGS(first, last) asm volatile("" ::"s"(first), "s"(last))
+// workgroup, instead of paying one memory round trip after the other; naming what the address
+// arithmetic in front of the first loads needs keeps those fetches in the same batch.
+#define KVC_FETCH_ARGS(first, last, a, b, c, d, e, f) \
+    asm volatile("" ::"s"(first), "s"(last), "s"(a), "s"(b), "s"(c), "s"(d), "s"(e), "s"(f))
 
 __host__ __device__ inline u32x4 u32x4_mk(unsigned a, unsigned b, unsigned c, unsigned d) { return u32x4{a, b, c, d}; }
 __host__ __device__ inline u32x2 u32x2_mk(unsigned a, unsigned b) { return u32x2{a, b}; }
@@ -140,7 +142,7 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
                                                  const uint16_t *__restrict__ k_new,
                                                  const uint16_t *__restrict__ v_new)
 {
-    KVC_FETCH_ARGS(p.B, v_new);
+    KVC_FETCH_ARGS(p.B, v_new, q, Kc, p.qTPU, p.qI, p.qHkv, p.m);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
     TS(0, 0);
@@ -330,7 +332,7 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
 template <int KS4, int NW>
 __global__ __launch_bounds__(64 * NW) void fb_probs(Plan p, const uint16_t *__restrict__ theta)
 {
-    KVC_FETCH_ARGS(p.B, theta);
+    KVC_FETCH_ARGS(p.B, theta, p.S, p.qNC, p.qHkv, p.m_pad, p.R, p.R_pad);
     extern __shared__ __align__(16) uint16_t lds[];
     constexpr int PC = kPC;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -475,7 +477,7 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
                                                 const uint16_t *__restrict__ Vc)
 {
     static_assert(G * UP <= 16, "the rows of a tile must fit one MFMA tile");
-    KVC_FETCH_ARGS(p.B, Vc);
+    KVC_FETCH_ARGS(p.B, Vc, p.P, p.stats, U, p.qJS, p.qHkv, p.I);
     constexpr int n = NC * kPC, LDP = n + 8;
     constexpr int NR = 16 * NT;
     constexpr int NU = NT * UP;                          // image blocks per workgroup
@@ -752,7 +754,7 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
                                                    uint16_t *__restrict__ out,
                                                    float *__restrict__ lse)
 {
-    KVC_FETCH_ARGS(p.B, lse);
+    KVC_FETCH_ARGS(p.B, lse, p.Ypart, p.qHkv, p.qG, p.nparts, p.rec, mu);
     __shared__ float sSc[kMaxParts + 64];
     __shared__ float sRed[2][3];
     TS(3, 0);
