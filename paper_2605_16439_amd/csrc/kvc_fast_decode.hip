@@ -827,6 +827,47 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
     TS(3, 4);
 }
 
+// The same for at most 64 parts (PB = their number rounded up to eight): a lane per part holds its
+// statistics, so each of the two waves finds the joint maximum and sum with shuffles alone -- no
+// LDS, no barrier -- and all partial outputs are fetched in the same round trip as the statistics.
+template <int PB>
+__global__ __launch_bounds__(128) void fd_finalize_few(Plan p, const uint16_t *__restrict__ mu,
+                                                       uint16_t *__restrict__ out,
+                                                       float *__restrict__ lse)
+{
+    KVC_FETCH_ARGS(p.B, lse, p.Ypart, p.qHkv, p.qG, p.nparts, p.rec, mu);
+    TS(3, 0);
+    const int bgi = quot(blockIdx.x, p.qHkv), h = blockIdx.x - bgi * p.Hkv;
+    const int b = quot(bgi, p.qG), g = bgi - b * p.G;
+    const int bg = b * p.Hq + h * p.G + g;
+    const int lane = threadIdx.x & 63, c = threadIdx.x;
+    const int rec = p.rec, GD = p.G * D, np = p.nparts;
+    const float *yb = p.Ypart + static_cast<size_t>(b * p.Hkv + h) * np * rec;
+    const int pl = min(lane, np - 1);
+    float ml = yb[static_cast<size_t>(pl) * rec + GD + g];
+    float sl = yb[static_cast<size_t>(pl) * rec + GD + p.G + g];
+    const float *yc = yb + g * D + c;
+    float v[PB];
+#pragma unroll
+    for (int k = 0; k < PB; ++k) v[k] = yc[static_cast<size_t>(min(k, np - 1)) * rec];
+    const float muc = bf_lo(mu[static_cast<size_t>(h) * D + c]);
+    TS(3, 1);
+    if (lane >= np) { ml = -INFINITY; sl = 0.f; }
+    const float mx = wave_max(ml);
+    const float a = __expf(ml - mx);                      // zero beyond the last part
+    const float z = wave_sum(sl * a);
+    const float zv = wave_sum(lane < p.nvp ? sl * a : 0.f);
+    const float rz = 1.f / z;
+    const float wgt = a * rz;
+    TS(3, 3);
+    float y = (zv * rz) * muc;
+#pragma unroll
+    for (int k = 0; k < PB; ++k) y += __shfl(wgt, k, 64) * v[k];     // clamped duplicates: weight zero
+    out[static_cast<size_t>(bg) * D + c] = f32_to_bf16_bits(y);
+    if (c == 0 && lse) lse[bg] = mx + __logf(z);
+    TS(3, 4);
+}
+
 size_t lds_b(int m_pad) { return static_cast<size_t>(kPC) * (m_pad + 8) * sizeof(uint16_t); }
 size_t lds_c(int n, int nt)
 {
@@ -900,13 +941,18 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
 
 template <int PB> void launch_d1(const Plan &p, const DecodeCall &c)
 {
-    fd_finalize<PB><<<p.B * p.Hq, 128, 0, c.stream>>>(p, static_cast<const uint16_t *>(c.mu),
-                                                      static_cast<uint16_t *>(c.out), c.lse);
+    fd_finalize_few<PB><<<p.B * p.Hq, 128, 0, c.stream>>>(p, static_cast<const uint16_t *>(c.mu),
+                                                          static_cast<uint16_t *>(c.out), c.lse);
 }
 
 void launch_d(const Plan &p, const DecodeCall &c)
 {
-    switch (((p.nparts < 64 ? p.nparts : 64) + 7) >> 3) {      // parts per batch, in eights
+    if (p.nparts > 64) {
+        fd_finalize<64><<<p.B * p.Hq, 128, 0, c.stream>>>(p, static_cast<const uint16_t *>(c.mu),
+                                                         static_cast<uint16_t *>(c.out), c.lse);
+        return;
+    }
+    switch ((p.nparts + 7) >> 3) {      // parts, in eights
     case 1: launch_d1<8>(p, c); break;
     case 2: launch_d1<16>(p, c); break;
     case 3: launch_d1<24>(p, c); break;
