@@ -43,6 +43,8 @@
 // group and consecutive image blocks share MFMA tiles.
 #include "kvc_internal.h"
 
+#include <algorithm>
+
 namespace kvc {
 namespace {
 
@@ -70,7 +72,8 @@ constexpr size_t kLdsBudget = 150 * 1024;
 struct Plan {
     int B, Hq, Hkv, G, n, I, m, t, t_in, cap;
     int R, R_pad, NRB, RBW, m_pad, m16, NC;   // RBW: waves (16-row tiles) per fb_probs workgroup
-    int tiles_per_unit, vis_tiles, nvis_a;
+    int tiles_per_unit, vis_tiles, nvis_a, ntext_a;   // fa_scores: vision workgroups, text workgroups (these come first)
+    int ntext_c, ntext_c8;          // fc_fused: text workgroups (lowest ids), padded to a multiple of 8
     int UP, NT, NG, JS, NXC, nparts, rec;
     int merge, nvp;                 // one part per workgroup (its image blocks merged); vision parts per (b, head)
     int nvis_b, nvis_c;
@@ -128,6 +131,136 @@ __device__ inline float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff000
 __device__ inline int vt_index(int c, int x) { return c * kLDV + ((((x >> 3) ^ (c >> 4)) & (kXC / 8 - 1)) << 3) + (x & 7); }
 
 // ------------------------------------------------------------------------------------------
+// text_part: the complete attention part of kXC rows of the text cache of one (batch, KV head),
+// by four waves; `id` numbers the chunks, `lds` holds kTextLds bytes.  Runs as extra workgroups of
+// fc_fused (its longest launch, bound by the L2s, with CUs and HBM bandwidth to spare), or of
+// fa_scores when there are no vision tokens.
+// Part record in Ypart: [G][D] floats of un-normalised output, [G] maxima, [G] sums.
+// ------------------------------------------------------------------------------------------
+constexpr size_t kTextLds = (16 * kSWLD + D * kLDV) * sizeof(uint16_t) + 2 * 4 * 16 * sizeof(float);
+
+template <int G>
+__device__ __forceinline__ void text_part(const Plan &p, const uint16_t *__restrict__ q, uint16_t *__restrict__ Kt,
+                                          uint16_t *__restrict__ Vt, const uint16_t *__restrict__ k_new,
+                                          const uint16_t *__restrict__ v_new, uint16_t *lds, const int id)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r16 = lane & 15, kg = lane >> 4;
+    // ---------------- text rows: one chunk of kXC rows of one (batch, KV head) ----------------
+    uint16_t (*sWb)[kSWLD] = reinterpret_cast<uint16_t (*)[kSWLD]>(lds);               // probabilities [head][row], bf16
+    uint16_t *sVt = lds + 16 * kSWLD;                                                  // V^T [channel][row]
+    float (*sRed)[4][16] = reinterpret_cast<float (*)[4][16]>(lds + 16 * kSWLD + D * kLDV);   // per-wave maxima / sums per head
+    const int bh = quot(id, p.qNXC), xc = id - bh * p.NXC;
+    const int b = quot(bh, p.qHkv), h = bh - b * p.Hkv;
+    const int lo = xc * kXC, hi = min(p.t, lo + kXC);
+    const bool fresh = k_new != nullptr;                       // row t_in comes from k_new / v_new
+    // value rows of the chunk (16 lanes per row, a lane takes pairs of consecutive rows) and key
+    // rows of this wave's two 16-row tiles
+    const int rowl = wave * 4 + kg, cs = r16;
+    u32x4 vb[kXC / 32][2], kf[2][4], qf[4];
+#pragma unroll
+    for (int it = 0; it < kXC / 32; ++it)
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int x = min(lo + 2 * (rowl + 16 * it) + e, hi - 1);
+            const uint16_t *vrow = (fresh && x == p.t_in) ? v_new + static_cast<size_t>(bh) * D
+                                                          : Vt + (static_cast<size_t>(bh) * p.cap + x) * D;
+            vb[it][e] = *(reinterpret_cast<const u32x4 *>(vrow) + cs);
+        }
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+        const int x = min(lo + 32 * wave + 16 * tt + r16, hi - 1);
+        const uint16_t *krow = (fresh && x == p.t_in) ? k_new + static_cast<size_t>(bh) * D
+                                                      : Kt + (static_cast<size_t>(bh) * p.cap + x) * D;
+        const u32x4 *kp = reinterpret_cast<const u32x4 *>(krow) + kg;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) kf[tt][ks] = kp[4 * ks];
+    }
+    {
+        const u32x4 *qp = reinterpret_cast<const u32x4 *>(q + (static_cast<size_t>(b) * p.Hq + h * G + min(r16, G - 1)) * D) + kg;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) qf[ks] = qp[4 * ks];
+    }
+    TS(0, 1);
+    // logits: lane (head r16, rows 32 wave + 16 tt + 4 kg + e) keeps 8 of them
+    f32x4 sc[2];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[tt][ks]), as_bf16x8(qf[ks]), acc, 0, 0, 0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            sc[tt][e] = (lo + 32 * wave + 16 * tt + 4 * kg + e < hi) ? acc[e] * p.scale : -INFINITY;
+    }
+    float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
+                     fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    if (kg == 0) sRed[0][wave][r16] = mx;
+    // value rows -> LDS transposed: rows (x, x+1) of channel c share one 32-bit word
+#pragma unroll
+    for (int it = 0; it < kXC / 32; ++it) {
+        const int xl2 = 2 * (rowl + 16 * it);
+        const uint32_t a[4] = {vb[it][0].x, vb[it][0].y, vb[it][0].z, vb[it][0].w};
+        const uint32_t c2[4] = {vb[it][1].x, vb[it][1].y, vb[it][1].z, vb[it][1].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            *reinterpret_cast<uint32_t *>(sVt + vt_index(8 * cs + 2 * e, xl2)) = (a[e] & 0xffffu) | (c2[e] << 16);
+            *reinterpret_cast<uint32_t *>(sVt + vt_index(8 * cs + 2 * e + 1, xl2)) = (a[e] >> 16) | (c2[e] & 0xffff0000u);
+        }
+    }
+    __syncthreads();
+    TS(0, 2);
+    // probabilities relative to the chunk's own maximum, straight from the accumulator layout
+    mx = fmaxf(fmaxf(sRed[0][0][r16], sRed[0][1][r16]), fmaxf(sRed[0][2][r16], sRed[0][3][r16]));
+    float sm = 0.f;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+        uint32_t eb[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            eb[e] = f32_to_bf16_bits(__expf(sc[tt][e] - mx));       // exp(-inf) = 0 beyond the chunk
+            sm += __uint_as_float(eb[e] << 16);
+        }
+        *reinterpret_cast<u32x2 *>(&sWb[r16][32 * wave + 16 * tt + 4 * kg]) = u32x2_mk(eb[0] | (eb[1] << 16), eb[2] | (eb[3] << 16));
+    }
+    sm += __shfl_xor(sm, 16, 64);
+    sm += __shfl_xor(sm, 32, 64);
+    if (kg == 0) sRed[1][wave][r16] = sm;
+    __syncthreads();
+    TS(0, 3);
+    // out_part^T[c][g] = sum_x V^T[c][x] P[g][x]; each wave owns two 16-channel tiles
+    float *yp = p.Ypart + (static_cast<size_t>(bh) * p.nparts + p.nvp + xc) * p.rec;
+#pragma unroll
+    for (int ct2 = 0; ct2 < 2; ++ct2) {
+        const int ct = 2 * wave + ct2;
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < kXC / 32; ++ks) {
+            const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(sVt + vt_index(16 * ct + r16, 32 * ks + 8 * kg));
+            const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(&sWb[r16][32 * ks + 8 * kg]);
+            o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, o, 0, 0, 0);
+        }
+        if (r16 < G) *reinterpret_cast<f32x4 *>(yp + r16 * D + 16 * ct + 4 * kg) = o;
+    }
+    if (threadIdx.x < G) {
+        yp[G * D + threadIdx.x] = mx;            // lanes 0..15 of wave 0 hold the maximum of head r16
+        yp[G * D + G + threadIdx.x] = sRed[1][0][threadIdx.x] + sRed[1][1][threadIdx.x] +
+                                      sRed[1][2][threadIdx.x] + sRed[1][3][threadIdx.x];
+    }
+    // Sec. 3.2: the text cache keeps growing as in the backbone -- store the new token's k, v
+    if (fresh && p.t_in >= lo && p.t_in < hi && threadIdx.x < 32) {
+        const int half = threadIdx.x >> 4, piece = threadIdx.x & 15;
+        const uint16_t *src = (half ? v_new : k_new) + static_cast<size_t>(bh) * D;
+        uint16_t *dst = (half ? Vt : Kt) + (static_cast<size_t>(bh) * p.cap + p.t_in) * D;
+        *(reinterpret_cast<u32x4 *>(dst) + piece) = *(reinterpret_cast<const u32x4 *>(src) + piece);
+    }
+    TS(0, 4);
+}
+
+// ------------------------------------------------------------------------------------------
 // fa_scores: Alg. 1 step 1 on the compressed keys (vision workgroups), and the complete
 // attention part of 128 text rows (text workgroups).
 // MFMA tile: A = 16 key rows x 32 channels, B = 32 channels x 16 query heads of the group,
@@ -147,125 +280,15 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
     const int r16 = lane & 15, kg = lane >> 4;
     TS(0, 0);
 
-    if (static_cast<int>(blockIdx.x) >= p.nvis_a) {
-        // ---------------- text rows: one chunk of kXC rows of one (batch, KV head) ----------------
-        __shared__ __align__(16) uint16_t sWb[16][kSWLD];        // probabilities [head][row], bf16
-        __shared__ __align__(16) uint16_t sVt[D * kLDV];         // V^T [channel][row]
-        __shared__ float sRed[2][4][16];                         // per-wave maxima / sums per head
-        const int id = blockIdx.x - p.nvis_a;
-        const int bh = quot(id, p.qNXC), xc = id - bh * p.NXC;
-        const int b = quot(bh, p.qHkv), h = bh - b * p.Hkv;
-        const int lo = xc * kXC, hi = min(p.t, lo + kXC);
-        const bool fresh = k_new != nullptr;                       // row t_in comes from k_new / v_new
-        // value rows of the chunk (16 lanes per row, a lane takes pairs of consecutive rows) and key
-        // rows of this wave's two 16-row tiles
-        const int rowl = wave * 4 + kg, cs = r16;
-        u32x4 vb[kXC / 32][2], kf[2][4], qf[4];
-#pragma unroll
-        for (int it = 0; it < kXC / 32; ++it)
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const int x = min(lo + 2 * (rowl + 16 * it) + e, hi - 1);
-                const uint16_t *vrow = (fresh && x == p.t_in) ? v_new + static_cast<size_t>(bh) * D
-                                                              : Vt + (static_cast<size_t>(bh) * p.cap + x) * D;
-                vb[it][e] = *(reinterpret_cast<const u32x4 *>(vrow) + cs);
-            }
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            const int x = min(lo + 32 * wave + 16 * tt + r16, hi - 1);
-            const uint16_t *krow = (fresh && x == p.t_in) ? k_new + static_cast<size_t>(bh) * D
-                                                          : Kt + (static_cast<size_t>(bh) * p.cap + x) * D;
-            const u32x4 *kp = reinterpret_cast<const u32x4 *>(krow) + kg;
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) kf[tt][ks] = kp[4 * ks];
-        }
-        {
-            const u32x4 *qp = reinterpret_cast<const u32x4 *>(q + (static_cast<size_t>(b) * p.Hq + h * G + min(r16, G - 1)) * D) + kg;
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) qf[ks] = qp[4 * ks];
-        }
-        TS(0, 1);
-        // logits: lane (head r16, rows 32 wave + 16 tt + 4 kg + e) keeps 8 of them
-        f32x4 sc[2];
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[tt][ks]), as_bf16x8(qf[ks]), acc, 0, 0, 0);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                sc[tt][e] = (lo + 32 * wave + 16 * tt + 4 * kg + e < hi) ? acc[e] * p.scale : -INFINITY;
-        }
-        float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
-                         fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        if (kg == 0) sRed[0][wave][r16] = mx;
-        // value rows -> LDS transposed: rows (x, x+1) of channel c share one 32-bit word
-#pragma unroll
-        for (int it = 0; it < kXC / 32; ++it) {
-            const int xl2 = 2 * (rowl + 16 * it);
-            const uint32_t a[4] = {vb[it][0].x, vb[it][0].y, vb[it][0].z, vb[it][0].w};
-            const uint32_t c2[4] = {vb[it][1].x, vb[it][1].y, vb[it][1].z, vb[it][1].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                *reinterpret_cast<uint32_t *>(sVt + vt_index(8 * cs + 2 * e, xl2)) = (a[e] & 0xffffu) | (c2[e] << 16);
-                *reinterpret_cast<uint32_t *>(sVt + vt_index(8 * cs + 2 * e + 1, xl2)) = (a[e] >> 16) | (c2[e] & 0xffff0000u);
-            }
-        }
-        __syncthreads();
-        TS(0, 2);
-        // probabilities relative to the chunk's own maximum, straight from the accumulator layout
-        mx = fmaxf(fmaxf(sRed[0][0][r16], sRed[0][1][r16]), fmaxf(sRed[0][2][r16], sRed[0][3][r16]));
-        float sm = 0.f;
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            uint32_t eb[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                eb[e] = f32_to_bf16_bits(__expf(sc[tt][e] - mx));       // exp(-inf) = 0 beyond the chunk
-                sm += __uint_as_float(eb[e] << 16);
-            }
-            *reinterpret_cast<u32x2 *>(&sWb[r16][32 * wave + 16 * tt + 4 * kg]) = u32x2_mk(eb[0] | (eb[1] << 16), eb[2] | (eb[3] << 16));
-        }
-        sm += __shfl_xor(sm, 16, 64);
-        sm += __shfl_xor(sm, 32, 64);
-        if (kg == 0) sRed[1][wave][r16] = sm;
-        __syncthreads();
-        TS(0, 3);
-        // out_part^T[c][g] = sum_x V^T[c][x] P[g][x]; each wave owns two 16-channel tiles
-        float *yp = p.Ypart + (static_cast<size_t>(bh) * p.nparts + p.nvp + xc) * p.rec;
-#pragma unroll
-        for (int ct2 = 0; ct2 < 2; ++ct2) {
-            const int ct = 2 * wave + ct2;
-            f32x4 o = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < kXC / 32; ++ks) {
-                const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(sVt + vt_index(16 * ct + r16, 32 * ks + 8 * kg));
-                const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(&sWb[r16][32 * ks + 8 * kg]);
-                o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, o, 0, 0, 0);
-            }
-            if (r16 < G) *reinterpret_cast<f32x4 *>(yp + r16 * D + 16 * ct + 4 * kg) = o;
-        }
-        if (threadIdx.x < G) {
-            yp[G * D + threadIdx.x] = mx;            // lanes 0..15 of wave 0 hold the maximum of head r16
-            yp[G * D + G + threadIdx.x] = sRed[1][0][threadIdx.x] + sRed[1][1][threadIdx.x] +
-                                          sRed[1][2][threadIdx.x] + sRed[1][3][threadIdx.x];
-        }
-        // Sec. 3.2: the text cache keeps growing as in the backbone -- store the new token's k, v
-        if (fresh && p.t_in >= lo && p.t_in < hi && threadIdx.x < 32) {
-            const int half = threadIdx.x >> 4, piece = threadIdx.x & 15;
-            const uint16_t *src = (half ? v_new : k_new) + static_cast<size_t>(bh) * D;
-            uint16_t *dst = (half ? Vt : Kt) + (static_cast<size_t>(bh) * p.cap + p.t_in) * D;
-            *(reinterpret_cast<u32x4 *>(dst) + piece) = *(reinterpret_cast<const u32x4 *>(src) + piece);
-        }
-        TS(0, 4);
+    // without vision tokens there is no fc_fused launch: the text chunks are handled here
+    if (static_cast<int>(blockIdx.x) < p.ntext_a) {
+        __shared__ __align__(16) uint16_t sText[kTextLds / 2];
+        text_part<G>(p, q, Kt, Vt, k_new, v_new, sText, blockIdx.x);
         return;
     }
 
     // ---------------- vision: kTPW tiles of 16 compressed key rows per wave ----------------
-    const int tile0 = (blockIdx.x * 4 + wave) * kTPW;
+    const int tile0 = ((blockIdx.x - p.ntext_a) * 4 + wave) * kTPW;
     u32x4 kf[kTPW][4], qf[kTPW][4];
     bool live[kTPW];
     int bh_prev = -1;
@@ -474,10 +497,14 @@ template <> struct KSplit<4> { static constexpr int KH0 = 2, UCH = 2; };
 
 template <int G, int UP, int NT, int NC>
 __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restrict__ U,
-                                                const uint16_t *__restrict__ Vc)
+                                                const uint16_t *__restrict__ Vc,
+                                                const uint16_t *__restrict__ q,
+                                                uint16_t *__restrict__ Kt, uint16_t *__restrict__ Vt,
+                                                const uint16_t *__restrict__ k_new,
+                                                const uint16_t *__restrict__ v_new)
 {
     static_assert(G * UP <= 16, "the rows of a tile must fit one MFMA tile");
-    KVC_FETCH_ARGS(p.B, Vc, p.P, p.stats, U, p.qJS, p.qHkv, p.I);
+    KVC_FETCH_ARGS(p.B, v_new, p.P, p.stats, U, p.qJS, p.qHkv, p.I);
     constexpr int n = NC * kPC, LDP = n + 8;
     constexpr int NR = 16 * NT;
     constexpr int NU = NT * UP;                          // image blocks per workgroup
@@ -495,6 +522,13 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
     // head h) picks the XCD: key = h + H_kv ug, class key mod 8; the JS slices of one pair share a
     // class, so its rows of P are fetched into one L2 only, and the rows of U[h] into at most
     // 8 / H_kv of them (one when H_kv >= 8).
+    // The text chunks ride along as the first workgroups (four waves each; they take about as long
+    // as the others and start first).  Their number is padded to a multiple of 8 so that the ids
+    // after them keep their residue class.
+    if (static_cast<int>(blockIdx.x) >= p.nvis_c) {
+        if (threadIdx.x < 256) text_part<G>(p, q, Kt, Vt, k_new, v_new, dyn, blockIdx.x - p.nvis_c);
+        return;
+    }
     TS(2, 0);
     const int w8 = blockIdx.x >> 3;
     const int w8q = quot(w8, p.qJS);
@@ -910,6 +944,10 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.NG = p.UP ? (p.B * p.I + p.NT * p.UP - 1) / (p.NT * p.UP) : 0;
     p.JS = (p.m + kJC - 1) / kJC;
     p.NXC = (t + kXC - 1) / kXC;
+    // the text chunks are extra workgroups of fc_fused; without vision tokens, of fa_scores
+    p.ntext_a = (p.I > 0 && p.UP) ? 0 : p.B * p.Hkv * p.NXC;
+    p.ntext_c = (p.I > 0 && p.UP) ? p.B * p.Hkv * p.NXC : 0;
+    p.ntext_c8 = static_cast<int>(align_up(p.ntext_c, 8));
     // When every workgroup of fc_fused holds image blocks of one batch element only, it merges them
     // into a single part record (fewer, larger-grained parts for fd_finalize to read)
     p.merge = (p.UP && p.I > 0 && p.I % (p.NT * p.UP) == 0) ? 1 : 0;
@@ -994,7 +1032,7 @@ bool launch_b(const Plan &p, const DecodeCall &c)
 
 template <int G> bool launch_a(const Plan &p, const DecodeCall &c)
 {
-    fa_scores<G><<<p.nvis_a + p.B * p.Hkv * p.NXC, 256, 0, c.stream>>>(
+    fa_scores<G><<<p.ntext_a + p.nvis_a, 256, 0, c.stream>>>(
         p, static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc),
         static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt),
         static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new));
@@ -1003,11 +1041,13 @@ template <int G> bool launch_a(const Plan &p, const DecodeCall &c)
 
 template <int G, int UP, int NT, int NC> bool launch_c3(const Plan &p, const DecodeCall &c)
 {
-    const size_t lds = lds_c(NC * kPC, NT);
+    const size_t lds = std::max(lds_c(NC * kPC, NT), kTextLds);
     static bool attr_set[kMaxDevices] = {};
     if (!allow_lds(reinterpret_cast<const void *>(fc_fused<G, UP, NT, NC>), lds, attr_set)) return false;
-    fc_fused<G, UP, NT, NC><<<p.nvis_c, 512, lds, c.stream>>>(p, static_cast<const uint16_t *>(c.U),
-                                                             static_cast<const uint16_t *>(c.Vc));
+    fc_fused<G, UP, NT, NC><<<p.nvis_c + p.ntext_c, 512, lds, c.stream>>>(
+        p, static_cast<const uint16_t *>(c.U), static_cast<const uint16_t *>(c.Vc), static_cast<const uint16_t *>(c.q),
+        static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt), static_cast<const uint16_t *>(c.k_new),
+        static_cast<const uint16_t *>(c.v_new));
     return true;
 }
 
