@@ -267,7 +267,7 @@ __device__ __forceinline__ void text_part(const Plan &p, const uint16_t *__restr
 // D[key row][head]; a lane ends up with 4 consecutive key rows of one head.
 // Part record in Ypart: [G][D] floats of un-normalised output, [G] maxima, [G] sums.
 // ------------------------------------------------------------------------------------------
-template <int G>
+template <int G, bool TEXT>
 __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restrict__ q,
                                                  const uint16_t *__restrict__ Kc,
                                                  uint16_t *__restrict__ Kt,
@@ -280,11 +280,14 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
     const int r16 = lane & 15, kg = lane >> 4;
     TS(0, 0);
 
-    // without vision tokens there is no fc_fused launch: the text chunks are handled here
-    if (static_cast<int>(blockIdx.x) < p.ntext_a) {
-        __shared__ __align__(16) uint16_t sText[kTextLds / 2];
-        text_part<G>(p, q, Kt, Vt, k_new, v_new, sText, blockIdx.x);
-        return;
+    // without vision tokens there is no fc_fused launch: the text chunks are handled here (TEXT; the
+    // instance for the usual case reserves no LDS)
+    if constexpr (TEXT) {
+        if (static_cast<int>(blockIdx.x) < p.ntext_a) {
+            __shared__ __align__(16) uint16_t sText[kTextLds / 2];
+            text_part<G>(p, q, Kt, Vt, k_new, v_new, sText, blockIdx.x);
+            return;
+        }
     }
 
     // ---------------- vision: kTPW tiles of 16 compressed key rows per wave ----------------
@@ -1032,10 +1035,17 @@ bool launch_b(const Plan &p, const DecodeCall &c)
 
 template <int G> bool launch_a(const Plan &p, const DecodeCall &c)
 {
-    fa_scores<G><<<p.ntext_a + p.nvis_a, 256, 0, c.stream>>>(
-        p, static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc),
-        static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt),
-        static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new));
+    if (p.ntext_a + p.nvis_a == 0) return true;
+    if (p.ntext_a > 0)
+        fa_scores<G, true><<<p.ntext_a + p.nvis_a, 256, 0, c.stream>>>(
+            p, static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc),
+            static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt),
+            static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new));
+    else
+        fa_scores<G, false><<<p.nvis_a, 256, 0, c.stream>>>(
+            p, static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc),
+            static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt),
+            static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new));
     return true;
 }
 
