@@ -387,11 +387,14 @@ __global__ __launch_bounds__(64 * NW) void fb_probs(Plan p, const uint16_t *__re
     const int KS = p.m_pad / 32;
     constexpr int SB = 4 * KS4;
     u32x4 sfr[SB];
-    // (steps of the last group that lie beyond KS are not loaded at all: uniform tests, loads only)
+    // (a step of the last group that lies beyond KS re-reads the last step and is zeroed: loads under
+    // a run-time test, even a uniform one, made the compiler wait for each of them in turn and
+    // shuttle the fragments through accumulator registers when KS4 = 2)
 #pragma unroll
     for (int k = 0; k < SB; ++k) {
         sfr[k] = u32x4_mk(0, 0, 0, 0);
-        if (wave_live && (k < SB - 4 || k < KS)) sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * k);
+        if (wave_live) sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * (k < SB - 4 ? k : min(k, KS - 1)));
+        if (k >= SB - 4 && k >= KS) sfr[k] = u32x4_mk(0, 0, 0, 0);
     }
 
     TS(1, 1);
