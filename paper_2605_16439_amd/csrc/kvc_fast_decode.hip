@@ -945,10 +945,13 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.vis_tiles = p.B * p.Hkv * p.I * p.tiles_per_unit;
     p.nvis_a = (p.vis_tiles + 4 * kTPW - 1) / (4 * kTPW);
     p.UP = units_per_group(p.G);
-    // two MFMA tiles of query rows per workgroup halve the re-streaming of U when the rows are there
-    p.NT = (p.UP && p.B * p.I > p.UP) ? 2 : 1;
-    p.NG = p.UP ? (p.B * p.I + p.NT * p.UP - 1) / (p.NT * p.UP) : 0;
     p.JS = (p.m + kJC - 1) / kJC;
+    // two MFMA tiles of query rows per workgroup halve the re-streaming of U when the rows are there --
+    // unless that leaves half of the CUs without a workgroup: what one CU can pull in per unit of time
+    // bounds fc_fused, so the work is spread first
+    p.NT = (p.UP && p.B * p.I > p.UP) ? 2 : 1;
+    if (p.NT == 2 && static_cast<long>((p.B * p.I + 2 * p.UP - 1) / (2 * p.UP)) * p.Hkv * p.JS <= 128) p.NT = 1;
+    p.NG = p.UP ? (p.B * p.I + p.NT * p.UP - 1) / (p.NT * p.UP) : 0;
     p.NXC = (t + kXC - 1) / kXC;
     // the text chunks are extra workgroups of fc_fused; without vision tokens, of fa_scores
     p.ntext_a = (p.I > 0 && p.UP) ? 0 : p.B * p.Hkv * p.NXC;
