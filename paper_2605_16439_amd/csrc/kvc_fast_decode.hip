@@ -4,12 +4,13 @@
 // (score-space order), with the softmax taken jointly over vision and text keys
 // (Sec. 3.2) by carrying (max, sum) statistics per part and merging them at the end:
 //
-//   fa_scores   vision workgroups stream the compressed keys Kc from HBM once:
-//               S = sigma q Kc^T (Alg. 1 step 1), one 16x16x32 MFMA tile per 16 key rows.
-//               Text workgroups handle 128 rows of the text cache each, completely: logits,
-//               exp relative to the chunk's own maximum, P V_text (V_text transposed through
-//               LDS), and write a finished part record; the one that owns row text_len also
-//               stores the new token's k, v (Sec. 3.2: text KV is kept as it is).
+//   fa_scores   streams the compressed keys Kc from HBM once: S = sigma q Kc^T (Alg. 1 step 1),
+//               one 16x16x32 MFMA tile per 16 key rows.
+//   text_part   (a device function, run by extra workgroups of fc_fused) handles 128 rows of the
+//               text cache completely: logits, exp relative to the chunk's own maximum,
+//               P V_text (V_text transposed through LDS), and writes a finished part record; the
+//               chunk that owns row text_len also stores the new token's k, v (Sec. 3.2: text KV
+//               is kept as it is).
 //   fb_probs    L = S theta (step 2) as a skinny GEMM per KV head, 64 (or 128) query rows x 64
 //               positions per workgroup with the theta chunk transposed into LDS on the way
 //               in; emits P = exp(L - tile max) in bf16 and the tile's (max, sum) per row.
@@ -18,8 +19,8 @@
 //               alpha = exp(tile max - block max) (step 3), then out_part = W Vc over the same
 //               64 rows of the compressed values (step 4; Vc's blocked layout is the MFMA
 //               operand), un-normalised, with the block's (max, sum).
-//   fd_finalize merges the parts of each (batch, query head) with the joint softmax
-//               statistics, adds (sum P_vis) mu, writes out and lse.
+//   fd_finalize_few / fd_finalize  merge the parts of each (batch, query head) with the joint
+//               softmax statistics, add (sum P_vis) mu, write out and lse.
 //
 // Only S and P (bf16), the tile statistics and the part records cross kernel boundaries;
 // K_hat, V_hat and W never exist in memory.
@@ -37,7 +38,9 @@
 //  * loops that feed MFMAs carry no tests (trip counts are template parameters): a guarded loop
 //    makes the compiler move accumulators between register files at every step;
 //  * MFMA results are stored directly (no cross-lane reductions beyond two steps) and code stays
-//    small (cold instruction cache per launch).
+//    small (cold instruction cache per launch);
+//  * what stands in front of a kernel's first load is paid by every workgroup: the arguments are
+//    fetched in one batch (KVC_FETCH_ARGS) and indices are divided by multiplication (quot).
 //
 // Query rows of one KV head are ordered r = (b*I + i)*G + g, so the G query heads of a
 // group and consecutive image blocks share MFMA tiles.
