@@ -76,7 +76,7 @@ struct Plan {
     int B, Hq, Hkv, G, n, I, m, t, t_in, cap;
     int R, R_pad, NRB, RBW, m_pad, m16, NC;   // RBW: waves (16-row tiles) per fb_probs workgroup
     int tiles_per_unit, vis_tiles, nvis_a, ntext_a;   // fa_scores: vision workgroups, text workgroups (these come first)
-    int ntext_c, ntext_c8;          // fc_fused: text workgroups (lowest ids), padded to a multiple of 8
+    int ntext_c;                    // fc_fused: text workgroups (the highest ids)
     int UP, NT, NG, JS, NXC, nparts, rec;
     int merge, nvp;                 // one part per workgroup (its image blocks merged); vision parts per (b, head)
     int nvis_b, nvis_c;
@@ -531,9 +531,8 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
     // head h) picks the XCD: key = h + H_kv ug, class key mod 8; the JS slices of one pair share a
     // class, so its rows of P are fetched into one L2 only, and the rows of U[h] into at most
     // 8 / H_kv of them (one when H_kv >= 8).
-    // The text chunks ride along as the first workgroups (four waves each; they take about as long
-    // as the others and start first).  Their number is padded to a multiple of 8 so that the ids
-    // after them keep their residue class.
+    // The text chunks ride along as the last workgroups (four waves each): they land on the CUs the
+    // others leave idle first, and end before the longest of the others does.
     if (static_cast<int>(blockIdx.x) >= p.nvis_c) {
         if (threadIdx.x < 256) text_part<G>(p, q, Kt, Vt, k_new, v_new, dyn, blockIdx.x - p.nvis_c);
         return;
@@ -959,7 +958,6 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     // the text chunks are extra workgroups of fc_fused; without vision tokens, of fa_scores
     p.ntext_a = (p.I > 0 && p.UP) ? 0 : p.B * p.Hkv * p.NXC;
     p.ntext_c = (p.I > 0 && p.UP) ? p.B * p.Hkv * p.NXC : 0;
-    p.ntext_c8 = static_cast<int>(align_up(p.ntext_c, 8));
     // When every workgroup of fc_fused holds image blocks of one batch element only, it merges them
     // into a single part record (fewer, larger-grained parts for fd_finalize to read)
     p.merge = (p.UP && p.I > 0 && p.I % (p.NT * p.UP) == 0) ? 1 : 0;

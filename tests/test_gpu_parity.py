@@ -442,6 +442,15 @@ def test_fast_path_merged_part_records(hq, hkv, batch, images):
     check_layer(w, 103, steps=(0, 1))
 
 
+def test_fast_path_more_than_64_parts():
+    """42 image blocks are not a multiple of the 4 a fused-kernel workgroup takes, so every (block,
+    slice) keeps its own part record: 84 vision parts + 1 text part per (batch element, KV head),
+    beyond the 64 that the lane-per-part finish handles -- the LDS-based fd_finalize runs."""
+    w = FAST.with_(name="fast_manyparts", index=77, n_q_heads=14, n_kv_heads=2, batch=1, n_images=42,
+                   text_len=20, steps=2)
+    check_layer(w, 103, steps=(0, 1))
+
+
 def test_decode_replayed_from_a_hip_graph():
     """The decode call only enqueues kernels on the caller's stream (no allocation, no memset, no
     synchronisation), so after one warm-up call it can be captured into a HIP graph.  Replays,
