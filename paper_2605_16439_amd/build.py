@@ -13,6 +13,8 @@ SOURCES = ["kvc_api.hip", "kvc_generic.hip", "kvc_fast_decode.hip", "kvc_fast_co
 # wrong results on this hardware, so the compiler must not emit them
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # leading scalar / pointer kernel arguments (up to 14 dwords) arrive in registers at wave start
+         "-mllvm", "-amdgpu-kernarg-preload-count=16",
          "-Wall", "-Wno-unused-function"]
 
 

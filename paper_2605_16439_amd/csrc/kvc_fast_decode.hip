@@ -872,12 +872,31 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
 // The same for at most 64 parts (PB = their number rounded up to eight): a lane per part holds its
 // statistics, so each of the two waves finds the joint maximum and sum with shuffles alone -- no
 // LDS, no barrier -- and all partial outputs are fetched in the same round trip as the statistics.
+// What the kernel needs of the plan comes as 16 dwords of plain arguments: that many the hardware can
+// hand to a wave in registers at its start (kernel-argument preload, see build.py), so that no
+// memory round trip stands in front of the first loads.
 template <int PB>
-__global__ __launch_bounds__(128) void fd_finalize_few(Plan p, const uint16_t *__restrict__ mu,
-                                                       uint16_t *__restrict__ out,
-                                                       float *__restrict__ lse)
+__global__ __launch_bounds__(128) void fd_finalize_few(const float *__restrict__ Ypart, const uint16_t *__restrict__ mu,
+                                                       uint16_t *__restrict__ out, float *__restrict__ lse,
+                                                       int a_Hkv, unsigned a_qHkv, int a_G, unsigned a_qG, int a_nparts,
+                                                       int a_rec, int a_Hq, int a_nvp
+#if defined(KVC_TIMELINE)
+                                                       , unsigned long long *a_tl
+#endif
+                                                       )
 {
-    KVC_FETCH_ARGS(p.B, lse, p.Ypart, p.qHkv, p.qG, p.nparts, p.rec, mu);
+    struct {
+        int Hkv, G, Hq, nparts, rec, nvp;
+        unsigned qHkv, qG;
+        const float *Ypart;
+#if defined(KVC_TIMELINE)
+        unsigned long long *tl;
+#endif
+    } p = {a_Hkv, a_G, a_Hq, a_nparts, a_rec, a_nvp, a_qHkv, a_qG, Ypart
+#if defined(KVC_TIMELINE)
+           , a_tl
+#endif
+    };
     TS(3, 0);
     const int bgi = quot(blockIdx.x, p.qHkv), h = blockIdx.x - bgi * p.Hkv;
     const int b = quot(bgi, p.qG), g = bgi - b * p.G;
@@ -989,8 +1008,13 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
 
 template <int PB> void launch_d1(const Plan &p, const DecodeCall &c)
 {
-    fd_finalize_few<PB><<<p.B * p.Hq, 128, 0, c.stream>>>(p, static_cast<const uint16_t *>(c.mu),
-                                                          static_cast<uint16_t *>(c.out), c.lse);
+    fd_finalize_few<PB><<<p.B * p.Hq, 128, 0, c.stream>>>(p.Ypart, static_cast<const uint16_t *>(c.mu),
+                                                          static_cast<uint16_t *>(c.out), c.lse, p.Hkv, p.qHkv, p.G,
+                                                          p.qG, p.nparts, p.rec, p.Hq, p.nvp
+#if defined(KVC_TIMELINE)
+                                                          , p.tl
+#endif
+                                                          );
 }
 
 void launch_d(const Plan &p, const DecodeCall &c)
