@@ -39,8 +39,10 @@
 //    makes the compiler move accumulators between register files at every step;
 //  * MFMA results are stored directly (no cross-lane reductions beyond two steps) and code stays
 //    small (cold instruction cache per launch);
-//  * what stands in front of a kernel's first load is paid by every workgroup: the arguments are
-//    fetched in one batch (KVC_FETCH_ARGS) and indices are divided by multiplication (quot).
+//  * what stands in front of a kernel's first load is paid by every workgroup: the values it takes
+//    are plain leading kernel arguments, which the hardware hands to a wave in registers (kernel-
+//    argument preload, up to 14 dwords; the rest of the plan is fetched from memory behind the first
+//    loads), and indices are divided by multiplication (quot).
 //
 // Query rows of one KV head are ordered r = (b*I + i)*G + g, so the G query heads of a
 // group and consecutive image blocks share MFMA tiles.
@@ -113,11 +115,11 @@ constexpr size_t kTimelineBytes = 0;
 __device__ inline int quot(int x, unsigned q) { return q ? static_cast<int>(__umulhi(static_cast<unsigned>(x), q)) : x; }
 inline unsigned quot_multiplier(int d) { return d > 1 ? static_cast<unsigned>((1ull << 32) / static_cast<unsigned>(d)) + 1u : 0u; }
 
-// The arguments of a kernel (the plan and the pointers after it) span two 128-byte lines of device
-// memory that no cache holds when a workgroup starts.  Naming one value of each line at the top of
-// the kernel makes the compiler fetch both at once, before the first test that could end the
-// workgroup, instead of paying one memory round trip after the other; naming what the address
-// arithmetic in front of the first loads needs keeps those fetches in the same batch.
+// Where the arguments are not preloaded (fd_finalize): the plan and the pointers after it span two
+// 128-byte lines of device memory that no cache holds when a workgroup starts.  Naming one value of
+// each line at the top of the kernel makes the compiler fetch both at once, before the first test
+// that could end the workgroup, instead of paying one memory round trip after the other; naming what
+// the address arithmetic in front of the first loads needs keeps those fetches in the same batch.
 #define KVC_FETCH_ARGS(first, last, a, b, c, d, e, f) \
     asm volatile("" ::"s"(first), "s"(last), "s"(a), "s"(b), "s"(c), "s"(d), "s"(e), "s"(f))
 
@@ -270,15 +272,17 @@ __device__ __forceinline__ void text_part(const Plan &p, const uint16_t *__restr
 // D[key row][head]; a lane ends up with 4 consecutive key rows of one head.
 // Part record in Ypart: [G][D] floats of un-normalised output, [G] maxima, [G] sums.
 // ------------------------------------------------------------------------------------------
+// (leading arguments: what stands in front of the first loads, preloaded into registers, see fb_probs)
 template <int G, bool TEXT>
-__global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restrict__ q,
-                                                 const uint16_t *__restrict__ Kc,
-                                                 uint16_t *__restrict__ Kt,
-                                                 uint16_t *__restrict__ Vt,
+__global__ __launch_bounds__(256) void fa_scores(const uint16_t *__restrict__ q, const uint16_t *__restrict__ Kc,
+                                                 int a_vis_tiles, unsigned a_qTPU, int a_tiles_per_unit, unsigned a_qI,
+                                                 int a_I, unsigned a_qHkv, int a_Hkv, int a_m, int a_Hq, int a_ntext_a,
+                                                 Plan p, uint16_t *__restrict__ Kt, uint16_t *__restrict__ Vt,
                                                  const uint16_t *__restrict__ k_new,
                                                  const uint16_t *__restrict__ v_new)
 {
-    KVC_FETCH_ARGS(p.B, v_new, q, Kc, p.qTPU, p.qI, p.qHkv, p.m);
+    p.vis_tiles = a_vis_tiles; p.qTPU = a_qTPU; p.tiles_per_unit = a_tiles_per_unit; p.qI = a_qI; p.I = a_I;
+    p.qHkv = a_qHkv; p.Hkv = a_Hkv; p.m = a_m; p.Hq = a_Hq; p.ntext_a = a_ntext_a;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
     TS(0, 0);
@@ -358,10 +362,15 @@ __global__ __launch_bounds__(256) void fa_scores(Plan p, const uint16_t *__restr
 // MFMA tile: A = theta^T (16 positions x 32 j) from LDS, B = S^T (32 j x 16 rows) from
 // memory, D[pos][row]: a lane ends up with 4 consecutive positions of one row.
 // ------------------------------------------------------------------------------------------
+// The leading arguments repeat what stands in front of the first loads (14 dwords: the hardware
+// hands them to every wave in registers at its start); the rest of the plan is fetched behind them.
 template <int KS4, int NW>
-__global__ __launch_bounds__(64 * NW) void fb_probs(Plan p, const uint16_t *__restrict__ theta)
+__global__ __launch_bounds__(64 * NW) void fb_probs(const uint16_t *__restrict__ theta, uint16_t *a_S, unsigned a_qNC,
+                                                    int a_NC, unsigned a_qHkv, int a_Hkv, int a_NRB, int a_R, int a_R_pad,
+                                                    int a_m_pad, int a_m, int a_n, Plan p)
 {
-    KVC_FETCH_ARGS(p.B, theta, p.S, p.qNC, p.qHkv, p.m_pad, p.R, p.R_pad);
+    p.S = a_S; p.qNC = a_qNC; p.NC = a_NC; p.qHkv = a_qHkv; p.Hkv = a_Hkv; p.NRB = a_NRB; p.R = a_R;
+    p.R_pad = a_R_pad; p.m_pad = a_m_pad; p.m = a_m; p.n = a_n;
     extern __shared__ __align__(16) uint16_t lds[];
     constexpr int PC = kPC;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -504,8 +513,11 @@ template <> struct KSplit<16> { static constexpr int KH0 = 8, UCH = 4; };
 template <> struct KSplit<9> { static constexpr int KH0 = 6, UCH = 3; };
 template <> struct KSplit<4> { static constexpr int KH0 = 2, UCH = 2; };
 
+// (leading arguments: what stands in front of the first loads, preloaded into registers, see fb_probs)
 template <int G, int UP, int NT, int NC>
-__global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restrict__ U,
+__global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, uint16_t *a_P, int a_nvis_c,
+                                                unsigned a_qJS, int a_JS, unsigned a_qHkv, int a_Hkv, int a_B, int a_I,
+                                                int a_m, int a_R, int a_R_pad, Plan p,
                                                 const uint16_t *__restrict__ Vc,
                                                 const uint16_t *__restrict__ q,
                                                 uint16_t *__restrict__ Kt, uint16_t *__restrict__ Vt,
@@ -513,7 +525,9 @@ __global__ __launch_bounds__(512) void fc_fused(Plan p, const uint16_t *__restri
                                                 const uint16_t *__restrict__ v_new)
 {
     static_assert(G * UP <= 16, "the rows of a tile must fit one MFMA tile");
-    KVC_FETCH_ARGS(p.B, v_new, p.P, p.stats, U, p.qJS, p.qHkv, p.I);
+    p.P = a_P; p.nvis_c = a_nvis_c; p.qJS = a_qJS; p.JS = a_JS; p.qHkv = a_qHkv; p.Hkv = a_Hkv; p.B = a_B; p.I = a_I;
+    p.m = a_m; p.R = a_R; p.R_pad = a_R_pad;
+    p.NG = (a_B * a_I + NT * UP - 1) / (NT * UP);        // as the host computes it
     constexpr int n = NC * kPC, LDP = n + 8;
     constexpr int NR = 16 * NT;
     constexpr int NU = NT * UP;                          // image blocks per workgroup
@@ -1040,7 +1054,9 @@ template <int KS4, int NW> bool launch_b2(const Plan &p, const DecodeCall &c)
 {
     static bool attr_set[kMaxDevices] = {};
     if (!allow_lds(reinterpret_cast<const void *>(fb_probs<KS4, NW>), kLdsBudget, attr_set)) return false;
-    fb_probs<KS4, NW><<<p.nvis_b, 64 * NW, lds_b(p.m_pad), c.stream>>>(p, static_cast<const uint16_t *>(c.theta));
+    fb_probs<KS4, NW><<<p.nvis_b, 64 * NW, lds_b(p.m_pad), c.stream>>>(static_cast<const uint16_t *>(c.theta), p.S, p.qNC,
+                                                                       p.NC, p.qHkv, p.Hkv, p.NRB, p.R, p.R_pad, p.m_pad,
+                                                                       p.m, p.n, p);
     return true;
 }
 
@@ -1069,12 +1085,14 @@ template <int G> bool launch_a(const Plan &p, const DecodeCall &c)
     if (p.ntext_a + p.nvis_a == 0) return true;
     if (p.ntext_a > 0)
         fa_scores<G, true><<<p.ntext_a + p.nvis_a, 256, 0, c.stream>>>(
-            p, static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc),
+            static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc), p.vis_tiles, p.qTPU,
+            p.tiles_per_unit, p.qI, p.I, p.qHkv, p.Hkv, p.m, p.Hq, p.ntext_a, p,
             static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt),
             static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new));
     else
         fa_scores<G, false><<<p.nvis_a, 256, 0, c.stream>>>(
-            p, static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc),
+            static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc), p.vis_tiles, p.qTPU,
+            p.tiles_per_unit, p.qI, p.I, p.qHkv, p.Hkv, p.m, p.Hq, p.ntext_a, p,
             static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt),
             static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new));
     return true;
@@ -1086,7 +1104,8 @@ template <int G, int UP, int NT, int NC> bool launch_c3(const Plan &p, const Dec
     static bool attr_set[kMaxDevices] = {};
     if (!allow_lds(reinterpret_cast<const void *>(fc_fused<G, UP, NT, NC>), lds, attr_set)) return false;
     fc_fused<G, UP, NT, NC><<<p.nvis_c + p.ntext_c, 512, lds, c.stream>>>(
-        p, static_cast<const uint16_t *>(c.U), static_cast<const uint16_t *>(c.Vc), static_cast<const uint16_t *>(c.q),
+        static_cast<const uint16_t *>(c.U), p.P, p.nvis_c, p.qJS, p.JS, p.qHkv, p.Hkv, p.B, p.I, p.m, p.R, p.R_pad, p,
+        static_cast<const uint16_t *>(c.Vc), static_cast<const uint16_t *>(c.q),
         static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt), static_cast<const uint16_t *>(c.k_new),
         static_cast<const uint16_t *>(c.v_new));
     return true;
