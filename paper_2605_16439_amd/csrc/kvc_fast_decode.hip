@@ -123,6 +123,12 @@ inline unsigned quot_multiplier(int d) { return d > 1 ? static_cast<unsigned>((1
 #define KVC_FETCH_ARGS(first, last, a, b, c, d, e, f) \
     asm volatile("" ::"s"(first), "s"(last), "s"(a), "s"(b), "s"(c), "s"(d), "s"(e), "s"(f))
 
+// Makes the compiler fetch the named arguments (those that are not preloaded) here, in one batch:
+// placed behind the first vector loads, their round trip to device memory hides behind those loads
+// instead of standing in front of the first use of each.
+template <class T> __device__ __forceinline__ void fetch_one(T v) { asm volatile("" ::"s"(v)); }
+template <class... T> __device__ __forceinline__ void fetch_now(T... v) { (fetch_one(v), ...); }
+
 __host__ __device__ inline u32x4 u32x4_mk(unsigned a, unsigned b, unsigned c, unsigned d) { return u32x4{a, b, c, d}; }
 __host__ __device__ inline u32x2 u32x2_mk(unsigned a, unsigned b) { return u32x2{a, b}; }
 __host__ __device__ inline f32x4 f32x4_mk(float a, float b, float c, float d) { return f32x4{a, b, c, d}; }
@@ -149,6 +155,8 @@ __device__ __forceinline__ void text_part(const Plan &p, const uint16_t *__restr
                                           uint16_t *__restrict__ Vt, const uint16_t *__restrict__ k_new,
                                           const uint16_t *__restrict__ v_new, uint16_t *lds, const int id)
 {
+    fetch_now(p.qNXC, p.NXC, p.qHkv, p.Hkv, p.Hq, p.t, p.t_in, p.cap, q, Kt, Vt, k_new, v_new, p.scale, p.Ypart, p.nparts,
+              p.nvp, p.rec);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
     // ---------------- text rows: one chunk of kXC rows of one (batch, KV head) ----------------
@@ -326,6 +334,7 @@ __global__ __launch_bounds__(256) void fa_scores(const uint16_t *__restrict__ q,
         }
         bh_prev = bh;
     }
+    fetch_now(p.scale, p.S, p.R_pad, p.m_pad, p.m16);
     TS(0, 1);
 #pragma unroll
     for (int tt = 0; tt < kTPW; ++tt) {
@@ -434,6 +443,7 @@ __global__ __launch_bounds__(64 * NW) void fb_probs(const uint16_t *__restrict__
                 }
             }
         }
+        fetch_now(p.m16, p.P, p.stats);
 #pragma unroll
         for (int k = 0; k < FB; ++k) {
             const int j = j0 + RPP * k;
@@ -515,9 +525,9 @@ template <> struct KSplit<4> { static constexpr int KH0 = 2, UCH = 2; };
 
 // (leading arguments: what stands in front of the first loads, preloaded into registers, see fb_probs)
 template <int G, int UP, int NT, int NC>
-__global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, uint16_t *a_P, int a_nvis_c,
+__global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, uint16_t *a_P, f32x2 *a_stats,
                                                 unsigned a_qJS, int a_JS, unsigned a_qHkv, int a_Hkv, int a_B, int a_I,
-                                                int a_m, int a_R, int a_R_pad, Plan p,
+                                                int a_m, int a_R_pad, Plan p,
                                                 const uint16_t *__restrict__ Vc,
                                                 const uint16_t *__restrict__ q,
                                                 uint16_t *__restrict__ Kt, uint16_t *__restrict__ Vt,
@@ -525,9 +535,12 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
                                                 const uint16_t *__restrict__ v_new)
 {
     static_assert(G * UP <= 16, "the rows of a tile must fit one MFMA tile");
-    p.P = a_P; p.nvis_c = a_nvis_c; p.qJS = a_qJS; p.JS = a_JS; p.qHkv = a_qHkv; p.Hkv = a_Hkv; p.B = a_B; p.I = a_I;
-    p.m = a_m; p.R = a_R; p.R_pad = a_R_pad;
-    p.NG = (a_B * a_I + NT * UP - 1) / (NT * UP);        // as the host computes it
+    p.P = a_P; p.stats = a_stats; p.qJS = a_qJS; p.JS = a_JS; p.qHkv = a_qHkv; p.Hkv = a_Hkv; p.B = a_B; p.I = a_I;
+    p.m = a_m; p.R_pad = a_R_pad;
+    // as the host computes them
+    p.R = a_B * a_I * G;
+    p.NG = (a_B * a_I + NT * UP - 1) / (NT * UP);
+    p.nvis_c = ((p.NG * a_Hkv + 7) & ~7) * a_JS;
     constexpr int n = NC * kPC, LDP = n + 8;
     constexpr int NR = 16 * NT;
     constexpr int NU = NT * UP;                          // image blocks per workgroup
@@ -607,6 +620,7 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
         }
     };
     load_u(0);
+    fetch_now(Vc, p.Ypart, p.nparts, p.rec, p.merge, p.qI);
     // compressed values: wave w owns channels 16 w ...; the operand (8 rows j of one channel) is 16
     // contiguous bytes in the blocked layout.  Image blocks are handled in batches of UBATCH.
     constexpr int UBATCH = NU < 4 ? NU : 4;
@@ -926,6 +940,7 @@ __global__ __launch_bounds__(128) void fd_finalize_few(const float *__restrict__
 #pragma unroll
     for (int k = 0; k < PB; ++k) v[k] = yc[static_cast<size_t>(min(k, np - 1)) * rec];
     const float muc = bf_lo(mu[static_cast<size_t>(h) * D + c]);
+    fetch_now(p.Hq, p.nvp);
     TS(3, 1);
     if (lane >= np) { ml = -INFINITY; sl = 0.f; }
     const float mx = wave_max(ml);
@@ -1104,7 +1119,7 @@ template <int G, int UP, int NT, int NC> bool launch_c3(const Plan &p, const Dec
     static bool attr_set[kMaxDevices] = {};
     if (!allow_lds(reinterpret_cast<const void *>(fc_fused<G, UP, NT, NC>), lds, attr_set)) return false;
     fc_fused<G, UP, NT, NC><<<p.nvis_c + p.ntext_c, 512, lds, c.stream>>>(
-        static_cast<const uint16_t *>(c.U), p.P, p.nvis_c, p.qJS, p.JS, p.qHkv, p.Hkv, p.B, p.I, p.m, p.R, p.R_pad, p,
+        static_cast<const uint16_t *>(c.U), p.P, p.stats, p.qJS, p.JS, p.qHkv, p.Hkv, p.B, p.I, p.m, p.R_pad, p,
         static_cast<const uint16_t *>(c.Vc), static_cast<const uint16_t *>(c.q),
         static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt), static_cast<const uint16_t *>(c.k_new),
         static_cast<const uint16_t *>(c.v_new));
