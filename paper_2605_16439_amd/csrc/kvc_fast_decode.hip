@@ -67,7 +67,6 @@ constexpr int kPC = 64;         // positions per fb_probs workgroup (one softmax
 constexpr int kTPW = 2;         // 16-row key tiles per wavefront in fa_scores
 constexpr int kJC = 64;         // capsule rows per fc_fused workgroup (one 16-row tile per wave)
 constexpr int kXC = 128;        // text rows per fa_scores text workgroup
-constexpr int kMaxN = 1024;     // fc_fused stages its rows of P (n bf16 each) in LDS
 constexpr int kMaxParts = 256;  // fd_finalize keeps one scale per part in LDS
 constexpr int kSWLD = kXC + 8;  // padded row (bf16) of the text probabilities in LDS
 constexpr int kLDV = kXC + 8;   // padded row (bf16) of the transposed text values in LDS
