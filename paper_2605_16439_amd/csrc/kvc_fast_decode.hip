@@ -44,11 +44,14 @@
 //    argument preload, up to 14 dwords; the rest of the plan is fetched from memory behind the first
 //    loads), and indices are divided by multiplication (quot).
 //
-// Query rows of one KV head are ordered r = (b*I + i)*G + g, so the G query heads of a
-// group and consecutive image blocks share MFMA tiles.
+// Query rows of one KV head: image block ub = b*I + i owns G consecutive rows (one per query head of
+// the group), and UPB = 2^UPBs whole image blocks fill a 64-row block (the rest of its rows unused), so
+// that consecutive image blocks share MFMA tiles and no image block straddles two 64-row blocks.
 #include "kvc_internal.h"
 
 #include <algorithm>
+#include <cstdlib>
+#include <mutex>
 
 namespace kvc {
 namespace {
@@ -72,10 +75,18 @@ constexpr int kSWLD = kXC + 8;  // padded row (bf16) of the text probabilities i
 constexpr int kLDV = kXC + 8;   // padded row (bf16) of the transposed text values in LDS
 constexpr int kWLD = kJC + 8;   // padded row (bf16) of the W tile in LDS
 constexpr size_t kLdsBudget = 150 * 1024;
+constexpr int kCtrStride = 32;  // an arrival counter per 128-byte line
+constexpr int kMaxFlags = 512;  // counters per set
+constexpr int kFlagSets = 16;   // one set per stream in use
+constexpr int kDenseRows = 24;  // "image blocks per 64-row block" = 2^24: the dense layout of the query rows
 
 struct Plan {
     int B, Hq, Hkv, G, n, I, m, t, t_in, cap;
     int R, R_pad, NRB, RBW, m_pad, m16, NC;   // RBW: waves (16-row tiles) per fb_probs workgroup
+    int UPBs, RV;                   // log2 of the image blocks per 64-row block of query rows; valid rows of a full block
+    int fab;                        // fa_scores and fb_probs run as one launch (fab_fused)
+    int wait_ticks;                 // fab_fused: how long a workgroup waits for its siblings (10 ns units)
+    unsigned *flags;                // fab_fused: [Hkv NRB] arrival counters, one per 128-byte line, zero between calls
     int tiles_per_unit, vis_tiles, nvis_a, ntext_a;   // fa_scores: vision workgroups, text workgroups (these come first)
     int ntext_c;                    // fc_fused: text workgroups (the highest ids)
     int UP, NT, NG, JS, NXC, nparts, rec;
@@ -139,6 +150,11 @@ __device__ inline float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff000
 // row are XOR-swizzled with the index of the channel's 16-row MFMA tile: the transposing stores
 // spread over the banks and the operand reads of one tile stay conflict-free
 __device__ inline int vt_index(int c, int x) { return c * kLDV + ((((x >> 3) ^ (c >> 4)) & (kXC / 8 - 1)) << 3) + (x & 7); }
+
+// first query row of image block ub (b*I + i) of a KV head
+__host__ __device__ inline int unit_row(int ub, int UPBs, int G) { return ((ub >> UPBs) << 6) + (ub & ((1 << UPBs) - 1)) * G; }
+// rows of a 64-row block beyond its image blocks, and rows beyond the last image block, hold nothing
+__device__ inline bool row_valid(const Plan &p, int r) { return (r & 63) < p.RV && r < p.R; }
 
 // ------------------------------------------------------------------------------------------
 // text_part: the complete attention part of kXC rows of the text cache of one (batch, KV head),
@@ -347,7 +363,7 @@ __global__ __launch_bounds__(256) void fa_scores(const uint16_t *__restrict__ q,
         const int u = quot(tile, p.qTPU), jt = tile - u * p.tiles_per_unit;
         const int bh = quot(u, p.qI), i = u - bh * p.I;
         const int b = quot(bh, p.qHkv), h = bh - b * p.Hkv;
-        const int r = (b * p.I + i) * G + r16;
+        const int r = unit_row(b * p.I + i, p.UPBs, G) + r16;
         const int j = jt * 16 + 4 * kg;
         uint32_t w[2];
 #pragma unroll
@@ -493,17 +509,274 @@ __global__ __launch_bounds__(64 * NW) void fb_probs(const uint16_t *__restrict__
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     float sum = 0.f;
+    const bool valid = row_valid(p, r);
     uint16_t *prow = p.P + (static_cast<size_t>(h) * p.R_pad + r) * p.n + pc * PC + 4 * kg;
 #pragma unroll
     for (int mt = 0; mt < PC / 16; ++mt) {
         const uint32_t a0 = f32_to_bf16_bits(__expf(acc[mt][0] - mx)), a1 = f32_to_bf16_bits(__expf(acc[mt][1] - mx));
         const uint32_t a2 = f32_to_bf16_bits(__expf(acc[mt][2] - mx)), a3 = f32_to_bf16_bits(__expf(acc[mt][3] - mx));
         sum += __uint_as_float(a0 << 16) + __uint_as_float(a1 << 16) + __uint_as_float(a2 << 16) + __uint_as_float(a3 << 16);
-        if (r < p.R) *reinterpret_cast<u32x2 *>(prow + 16 * mt) = u32x2_mk(a0 | (a1 << 16), a2 | (a3 << 16));
+        if (valid) *reinterpret_cast<u32x2 *>(prow + 16 * mt) = u32x2_mk(a0 | (a1 << 16), a2 | (a3 << 16));
     }
     sum += __shfl_xor(sum, 16, 64);
     sum += __shfl_xor(sum, 32, 64);
-    if (kg == 0 && r < p.R) p.stats[(static_cast<size_t>(h) * p.R_pad + r) * p.NC + pc] = f32x2_mk(mx, sum);
+    if (kg == 0 && valid) p.stats[(static_cast<size_t>(h) * p.R_pad + r) * p.NC + pc] = f32x2_mk(mx, sum);
+    TS(1, 4);
+}
+
+// ------------------------------------------------------------------------------------------
+// fab_fused: fa_scores and fb_probs in one launch, for calls small enough that all its workgroups are
+// resident at once.  The NC chunk workgroups of a (head, 64-row block) pair first compute the pair's
+// rows of S between them (up to TQ tiles of 16 key rows per wave, streamed from HBM while the theta
+// chunk arrives from the L2), then hand them to each other through the L2: a workgroup waits until
+// its stores are acknowledged, adds one to the pair's counter and polls it (with an atomic add of
+// zero, which is carried out in the L2 -- a plain load may be answered by the CU's L1) until all NC
+// have arrived, invalidates its L1 and goes on as fb_probs.
+//  * Workgroup ids of one residue class mod 8 run on one XCD, and a pair's workgroups share a class
+//    (see fb_probs), so counter and data meet in one L2 and neither a write-back nor an invalidation
+//    of it is needed.  This is a matter of speed only: atomics without device scope stay in the
+//    issuing XCD's L2, so a counter can reach NC only through workgroups that share that L2 -- and
+//    then their data is there too.
+//  * A workgroup that does not see NC arrivals within p.wait_ticks (siblings not resident, or on
+//    another XCD) computes all of the pair's rows of S itself and reads those: slower, same result.
+//  * The counters live in memory the library owns (zero when loaded, one set per stream in use); the
+//    finalize kernel of the same call puts them back to zero.
+// ------------------------------------------------------------------------------------------
+template <int KS4, int G>
+__global__ __launch_bounds__(256) void fab_fused(const uint16_t *__restrict__ Kc, unsigned a_qNC, int a_NC, unsigned a_qHkv,
+                                                 int a_Hkv, int a_nkeys, int a_TPU, unsigned a_qTPU, int a_UPBs, int a_I,
+                                                 unsigned a_qI, int a_m, int a_units, Plan p,
+                                                 const uint16_t *__restrict__ theta, const uint16_t *__restrict__ q)
+{
+    constexpr int NW = 4, TQ = 4;
+    p.qNC = a_qNC; p.NC = a_NC; p.qHkv = a_qHkv; p.Hkv = a_Hkv; p.tiles_per_unit = a_TPU; p.qTPU = a_qTPU;
+    p.UPBs = a_UPBs; p.I = a_I; p.qI = a_qI; p.m = a_m;
+    extern __shared__ __align__(16) uint16_t lds[];
+    constexpr int PC = kPC;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r16 = lane & 15, kg = lane >> 4;
+
+    // Workgroup ids are dealt round-robin over the 8 XCDs (private L2s).  The pair (row block rb,
+    // head h) picks the XCD (key = h + H_kv rb, class key mod 8): its rows of S reach one L2 only,
+    // and a chunk of theta[h] at most 8 / H_kv of them.
+    const int w8 = blockIdx.x >> 3;
+    const int w8q = quot(w8, p.qNC);
+    const int pc = w8 - w8q * p.NC, key = w8q * 8 + (blockIdx.x & 7);
+    if (key >= a_nkeys) return;
+    const int rb = quot(key, p.qHkv), h = key - rb * p.Hkv;
+
+    // ---- phase 1: this workgroup's share of S = sigma q Kc^T for the pair's image blocks ---------------
+    // tiles of 16 key rows are numbered (image block of the row block, tile of the block); wave w takes
+    // tiles pc TW + w + 4 t; a tile beyond the share repeats the last one and is not stored
+    const int T = a_TPU << a_UPBs, TW = quot(T + a_NC - 1, a_qNC);
+    // one tile of S: lane (head r16, key rows 4 kg ..) of image block ub, tile jt
+    auto store_tile = [&](const f32x4 &sacc, int ub, int jt) {
+        if (r16 >= G) return;                // columns beyond the group are copies of head G-1
+        const int rr = unit_row(ub, a_UPBs, G) + r16, j = jt * 16 + 4 * kg;
+        uint32_t wv[2];
+#pragma unroll
+        for (int e = 0; e < 4; e += 2) {
+            const uint32_t lo2 = (j + e < p.m) ? f32_to_bf16_bits(sacc[e] * p.scale) : 0u;
+            const uint32_t hi2 = (j + e + 1 < p.m) ? f32_to_bf16_bits(sacc[e + 1] * p.scale) : 0u;
+            wv[e >> 1] = lo2 | (hi2 << 16);
+        }
+        uint16_t *sr = p.S + (static_cast<size_t>(h) * p.R_pad + rr) * p.m_pad + j;
+        *reinterpret_cast<u32x2 *>(sr) = u32x2_mk(wv[0], wv[1]);
+        // the consumer reads whole 32-wide k-steps: keep the padding [m16, m_pad) at zero
+        if (jt == a_TPU - 1 && p.m_pad > p.m16) *reinterpret_cast<u32x2 *>(sr + 16) = u32x2_mk(0u, 0u);
+    };
+    u32x4 kf[TQ][4];
+    int t_ub[TQ], t_jt[TQ];
+    bool t_live[TQ];
+#pragma unroll
+    for (int tq = 0; tq < TQ; ++tq) {
+        const int tw = wave + 4 * tq, tl = min(pc * TW + min(tw, TW - 1), T - 1);
+        const int k = quot(tl, a_qTPU), jt = tl - k * a_TPU;
+        const int ub = min((rb << a_UPBs) + k, a_units - 1);
+        t_live[tq] = tw < TW && pc * TW + tw < T && (rb << a_UPBs) + k < a_units;
+        t_ub[tq] = ub; t_jt[tq] = jt;
+        const int b = quot(ub, a_qI), i = ub - b * a_I;
+        const int u = (b * a_Hkv + h) * a_I + i;
+        const int row = min(jt * 16 + r16, a_m - 1);
+        const u32x4 *kp = reinterpret_cast<const u32x4 *>(Kc + (static_cast<size_t>(u) * a_m + row) * D) + kg;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) kf[tq][ks] = kp[4 * ks];
+    }
+    fetch_now(theta, q, p.Hq, p.n, p.m_pad);
+    u32x4 qf[TQ][4];
+#pragma unroll
+    for (int tq = 0; tq < TQ; ++tq) {
+        const int b = quot(t_ub[tq], a_qI);
+        const u32x4 *qp = reinterpret_cast<const u32x4 *>(q + (static_cast<size_t>(b) * p.Hq + h * G + min(r16, G - 1)) * D) + kg;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) qf[tq][ks] = qp[4 * ks];
+    }
+
+    TS(1, 0);
+    const int LDT = p.m_pad + 8;
+    uint16_t *ThT = lds;                 // [PC][LDT]   theta chunk, transposed: ThT[pos][j]
+
+    TS(1, 1);
+    // ---- stage the theta chunk, transposed, in LDS -------------------------------------------------
+    // a thread owns a pair of consecutive rows j, j+1 and 8 positions; the pair is packed so the
+    // transposed store is one 32-bit word per position
+    constexpr int RPP = 16 * NW;                           // rows of theta per pass of the workgroup
+    const int seg = (lane >> 4) + 4 * (wave & 1);          // 16-byte segment of the chunk row
+    const int jp = (lane & 15) + 16 * (wave >> 1);         // row pair within a pass of RPP rows
+    {
+        const uint16_t *th = theta + static_cast<size_t>(h) * p.m * p.n + pc * PC + 8 * seg;
+        constexpr int FB = 128 * KS4 / RPP;      // passes of RPP rows: RPP FB >= m_pad, all in one batch
+        const int j0 = 2 * jp;
+        u32x4 tv[FB][2];
+#pragma unroll
+        for (int k = 0; k < FB; ++k) {
+            tv[k][0] = u32x4_mk(0, 0, 0, 0);
+            tv[k][1] = u32x4_mk(0, 0, 0, 0);
+            if (k < FB - 2 || RPP * k < p.m) {               // a whole pass beyond m is not loaded (uniform test)
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int j = j0 + RPP * k + e;          // single rows beyond m are clamped, then zeroed
+                    tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(min(j, p.m - 1)) * p.n);
+                    if (j >= p.m) tv[k][e] = u32x4_mk(0, 0, 0, 0);
+                }
+            }
+        }
+        fetch_now(p.m16, p.P, p.stats, p.S, p.scale, p.R_pad, p.R, p.RV, p.flags);
+        // S tiles of this wave
+#pragma unroll
+        for (int tq = 0; tq < TQ; ++tq) {
+            f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[tq][ks]), as_bf16x8(qf[tq][ks]), sacc, 0, 0, 0);
+            if (t_live[tq]) store_tile(sacc, t_ub[tq], t_jt[tq]);
+        }
+#pragma unroll
+        for (int k = 0; k < FB; ++k) {
+            const int j = j0 + RPP * k;
+            if (j < p.m16) {
+                const uint32_t a[4] = {tv[k][0].x, tv[k][0].y, tv[k][0].z, tv[k][0].w};
+                const uint32_t c[4] = {tv[k][1].x, tv[k][1].y, tv[k][1].z, tv[k][1].w};
+                uint32_t *dst = reinterpret_cast<uint32_t *>(ThT + (8 * seg) * LDT + j);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    dst[(2 * e) * (LDT / 2)] = (a[e] & 0xffffu) | (c[e] << 16);
+                    dst[(2 * e + 1) * (LDT / 2)] = (a[e] >> 16) | (c[e] & 0xffff0000u);
+                }
+            }
+        }
+        // zero the k padding of the transposed chunk: columns [m16, m_pad)
+        const int padc = p.m_pad - p.m16;
+        for (int idx = threadIdx.x; idx < PC * padc; idx += 64 * NW) {
+            const int pp = idx / padc, j = p.m16 + idx - pp * padc;
+            ThT[pp * LDT + j] = 0;
+        }
+    }
+    // every wave's stores of S have been acknowledged by the L2 before the counter moves
+    __shared__ int sAlone;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned *flag = p.flags + static_cast<size_t>(key) * kCtrStride;
+        __hip_atomic_fetch_add(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const unsigned long long t0 = wall_clock64();
+        unsigned seen;
+        bool all;
+        do {
+            for (int k = 0; k < 16; ++k) {                   // the clock is read once per 16 polls
+                asm volatile("global_atomic_add %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)"
+                             : "=&v"(seen) : "v"(flag), "v"(0u) : "memory");
+                all = seen >= static_cast<unsigned>(a_NC);
+                if (all) break;
+            }
+        } while (!all && wall_clock64() - t0 < static_cast<unsigned long long>(p.wait_ticks));
+        sAlone = all ? 0 : 1;
+    }
+    __syncthreads();
+    if (sAlone) {
+        // nobody to rely on: all T tiles of the pair, 16 per round (a wave takes tiles base + w + 4 t)
+        for (int base = 0; base < T; base += 16) {
+            for (int tq = 0; tq < 4; ++tq) {
+                const int tl = base + wave + 4 * tq;
+                if (tl >= T) continue;
+                const int k = quot(tl, a_qTPU), jt = tl - k * a_TPU;
+                const int ub = (rb << a_UPBs) + k;
+                if (ub >= a_units) continue;
+                const int b = quot(ub, a_qI), i = ub - b * a_I;
+                const int u = (b * a_Hkv + h) * a_I + i;
+                const u32x4 *kp = reinterpret_cast<const u32x4 *>(Kc + (static_cast<size_t>(u) * a_m + min(jt * 16 + r16, a_m - 1)) * D) + kg;
+                const u32x4 *qp = reinterpret_cast<const u32x4 *>(q + (static_cast<size_t>(b) * p.Hq + h * G + min(r16, G - 1)) * D) + kg;
+                f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kp[4 * ks]), as_bf16x8(qp[4 * ks]), sacc, 0, 0, 0);
+                store_tile(sacc, ub, jt);
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+    asm volatile("buffer_inv sc0" ::: "memory");
+    TS(1, 2);
+    // scores of this wave's 16 rows: first batch of fragments in flight during the LDS fill
+    const int r0 = rb * (16 * NW) + wave * 16;
+    const bool wave_live = r0 < p.R;
+    const int r = r0 + r16;
+    const uint16_t *srow = p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + 8 * kg;
+    // KS = m_pad / 32 k-steps of 32 compressed positions, handled as KS4 groups of four without any
+    // test inside the loops: a step beyond KS multiplies a re-read theta fragment by a zero fragment
+    const int KS = p.m_pad / 32;
+    constexpr int SB = 4 * KS4;
+    u32x4 sfr[SB];
+    // (a step of the last group that lies beyond KS re-reads the last step and is zeroed: loads under
+    // a run-time test, even a uniform one, made the compiler wait for each of them in turn and
+    // shuttle the fragments through accumulator registers when KS4 = 2)
+#pragma unroll
+    for (int k = 0; k < SB; ++k) {
+        sfr[k] = u32x4_mk(0, 0, 0, 0);
+        if (wave_live) sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * (k < SB - 4 ? k : min(k, KS - 1)));
+        if (k >= SB - 4 && k >= KS) sfr[k] = u32x4_mk(0, 0, 0, 0);
+    }
+
+    if (!wave_live) return;
+
+    f32x4 acc[PC / 16];
+#pragma unroll
+    for (int mt = 0; mt < PC / 16; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < SB; ++k) {
+        const int ks = min(k, KS - 1);
+        // scores beyond the compressed length are zeros written by fa_scores
+        const bf16x8 bfrag = as_bf16x8(sfr[k]);
+#pragma unroll
+        for (int mt = 0; mt < PC / 16; ++mt) {
+            const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(ThT + (16 * mt + r16) * LDT + 32 * ks + 8 * kg);
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[mt], 0, 0, 0);
+        }
+    }
+
+    TS(1, 3);
+    // ---- tile-local softmax numerators of row r over the 64 positions ------------------------------
+    float mx = -INFINITY;
+#pragma unroll
+    for (int mt = 0; mt < PC / 16; ++mt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mx = fmaxf(mx, acc[mt][e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float sum = 0.f;
+    const bool valid = row_valid(p, r);
+    uint16_t *prow = p.P + (static_cast<size_t>(h) * p.R_pad + r) * p.n + pc * PC + 4 * kg;
+#pragma unroll
+    for (int mt = 0; mt < PC / 16; ++mt) {
+        const uint32_t a0 = f32_to_bf16_bits(__expf(acc[mt][0] - mx)), a1 = f32_to_bf16_bits(__expf(acc[mt][1] - mx));
+        const uint32_t a2 = f32_to_bf16_bits(__expf(acc[mt][2] - mx)), a3 = f32_to_bf16_bits(__expf(acc[mt][3] - mx));
+        sum += __uint_as_float(a0 << 16) + __uint_as_float(a1 << 16) + __uint_as_float(a2 << 16) + __uint_as_float(a3 << 16);
+        if (valid) *reinterpret_cast<u32x2 *>(prow + 16 * mt) = u32x2_mk(a0 | (a1 << 16), a2 | (a3 << 16));
+    }
+    sum += __shfl_xor(sum, 16, 64);
+    sum += __shfl_xor(sum, 32, 64);
+    if (kg == 0 && valid) p.stats[(static_cast<size_t>(h) * p.R_pad + r) * p.NC + pc] = f32x2_mk(mx, sum);
     TS(1, 4);
 }
 
@@ -526,7 +799,7 @@ template <> struct KSplit<4> { static constexpr int KH0 = 2, UCH = 2; };
 template <int G, int UP, int NT, int NC>
 __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, uint16_t *a_P, f32x2 *a_stats,
                                                 unsigned a_qJS, int a_JS, unsigned a_qHkv, int a_Hkv, int a_B, int a_I,
-                                                int a_m, int a_R_pad, Plan p,
+                                                int a_m, int a_UPBs, Plan p,
                                                 const uint16_t *__restrict__ Vc,
                                                 const uint16_t *__restrict__ q,
                                                 uint16_t *__restrict__ Kt, uint16_t *__restrict__ Vt,
@@ -535,9 +808,9 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
 {
     static_assert(G * UP <= 16, "the rows of a tile must fit one MFMA tile");
     p.P = a_P; p.stats = a_stats; p.qJS = a_qJS; p.JS = a_JS; p.qHkv = a_qHkv; p.Hkv = a_Hkv; p.B = a_B; p.I = a_I;
-    p.m = a_m; p.R_pad = a_R_pad;
+    p.m = a_m;
+    p.R_pad = (unit_row(a_B * a_I - 1, a_UPBs, G) + G + kRB - 1) & ~(kRB - 1);
     // as the host computes them
-    p.R = a_B * a_I * G;
     p.NG = (a_B * a_I + NT * UP - 1) / (NT * UP);
     p.nvis_c = ((p.NG * a_Hkv + 7) & ~7) * a_JS;
     constexpr int n = NC * kPC, LDP = n + 8;
@@ -572,6 +845,9 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
     const int ub0 = ug * NU;
     const int units_total = p.B * p.I;
     const int nunits = min(NU, units_total - ub0);
+    // the workgroup's image blocks are consecutive rows of one 64-row block: 64 / G rounded down to a
+    // multiple of the 2 UP blocks of two tiles, always a power of two for the compiled group sizes
+    const int row0 = unit_row(ub0, a_UPBs, G);
     const int lo = s * kJC, hi = min(p.m, lo + kJC);
     uint16_t *sP = dyn;
 
@@ -584,7 +860,7 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
     const int prow_i = threadIdx.x >> 4, psub = threadIdx.x & 15;
     {
         const int pr = min(prow_i, NR - 1);
-        const int r = min(ub0 * G + (pr >> 4) * (UP * G) + (pr & 15), p.R - 1);
+        const int r = row0 + min((pr >> 4) * (UP * G) + min(pr & 15, UP * G - 1), nunits * G - 1);
         const u32x4 *prow = reinterpret_cast<const u32x4 *>(p.P + (static_cast<size_t>(h) * p.R_pad + r) * n);
 #pragma unroll
         for (int k = 0; k < KP; ++k) pfr[k] = prow[min(16 * k + psub, PCH - 1)];
@@ -594,7 +870,7 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
 #pragma unroll
     for (int k = 0; k < NC; ++k) st[k] = f32x2_mk(0.f, 0.f);
     if (wave == 0) {
-        const int r = min(ub0 * G + min(kg, NT - 1) * (UP * G) + r16, p.R - 1);
+        const int r = row0 + min(min(kg, NT - 1) * (UP * G) + min(r16, UP * G - 1), nunits * G - 1);
         const f32x2 *sp = p.stats + (static_cast<size_t>(h) * p.R_pad + r) * NC;
 #pragma unroll
         for (int k = 0; k < NC; ++k) st[k] = sp[k];
@@ -823,6 +1099,9 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
                                                    uint16_t *__restrict__ out,
                                                    float *__restrict__ lse)
 {
+    // the arrival counters of fab_fused go back to zero
+    if (p.fab && blockIdx.x == 0)
+        for (int i = threadIdx.x; i < p.Hkv * p.NRB; i += 128) p.flags[static_cast<size_t>(i) * kCtrStride] = 0u;
     KVC_FETCH_ARGS(p.B, lse, p.Ypart, p.qHkv, p.qG, p.nparts, p.rec, mu);
     __shared__ float sSc[kMaxParts + 64];
     __shared__ float sRed[2][3];
@@ -906,7 +1185,7 @@ template <int PB>
 __global__ __launch_bounds__(128) void fd_finalize_few(const float *__restrict__ Ypart, const uint16_t *__restrict__ mu,
                                                        uint16_t *__restrict__ out, float *__restrict__ lse,
                                                        int a_Hkv, unsigned a_qHkv, int a_G, unsigned a_qG, int a_nparts,
-                                                       int a_rec, int a_Hq, int a_nvp
+                                                       int a_rec, int a_Hq, int a_nvp, unsigned *a_flags, int a_nflags
 #if defined(KVC_TIMELINE)
                                                        , unsigned long long *a_tl
 #endif
@@ -954,6 +1233,9 @@ __global__ __launch_bounds__(128) void fd_finalize_few(const float *__restrict__
     for (int k = 0; k < PB; ++k) y += __shfl(wgt, k, 64) * v[k];     // clamped duplicates: weight zero
     out[static_cast<size_t>(bg) * D + c] = f32_to_bf16_bits(y);
     if (c == 0 && lse) lse[bg] = mx + __logf(z);
+    // the arrival counters of fab_fused go back to zero
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < a_nflags; i += 128) a_flags[static_cast<size_t>(i) * kCtrStride] = 0u;
     TS(3, 4);
 }
 
@@ -975,13 +1257,23 @@ int units_per_group(int G)
     }
 }
 
-Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *base)
+// padded: the query rows of whole image blocks fill 64-row blocks (what fab_fused needs); otherwise
+// the rows are dense, r = (b I + i) G + g
+Plan make_plan_layout(const kvc_shape &s, int t, int t_in, int cap, float scale, void *base, bool padded)
 {
     Plan p;
     p.B = s.batch; p.Hq = s.n_q_heads; p.Hkv = s.n_kv_heads; p.G = p.Hq / p.Hkv;
     p.n = s.n_img_tokens; p.I = s.n_images; p.m = s.m;
     p.t = t; p.t_in = t_in; p.cap = cap; p.scale = scale;
-    p.R = p.B * p.I * p.G;
+    {
+        const int up = units_per_group(p.G), units = p.B * p.I;
+        const int upb = up ? (64 / p.G) / (2 * up) * (2 * up) : 1;         // 64, 32, 16 or 8
+        p.UPBs = 0;
+        while ((1 << (p.UPBs + 1)) <= upb) ++p.UPBs;
+        p.RV = (1 << p.UPBs) * p.G;
+        if (!padded) { p.UPBs = kDenseRows; p.RV = 64; }                  // unit_row(ub) = ub G, every row valid
+        p.R = units > 0 ? unit_row(units - 1, p.UPBs, p.G) + p.G : 0;
+    }
     p.R_pad = static_cast<int>(align_up(p.R > 0 ? p.R : 1, kRB));
     // 64-row workgroups unless they would need more than two rounds over the CUs: then 128 rows per
     // workgroup re-read the theta chunk half as often
@@ -1027,6 +1319,9 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     p.P = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(p.Hkv) * p.R_pad * p.n * 2));
     p.stats = reinterpret_cast<f32x2 *>(take(static_cast<size_t>(p.Hkv) * p.R_pad * p.NC * 8));
     p.Ypart = reinterpret_cast<float *>(take(static_cast<size_t>(p.B) * p.Hkv * (p.I * p.JS + nxc_max) * p.rec * 4));
+    p.fab = 0;
+    p.flags = nullptr;
+    p.wait_ticks = 0;
     p.bytes = off;
 #if defined(KVC_TIMELINE)
     p.tl = nullptr;
@@ -1034,11 +1329,30 @@ Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *
     return p;
 }
 
+// fa_scores and fb_probs can run as one launch (fab_fused) when all its workgroups are resident at
+// once (one per CU) and a workgroup's share of the score tiles is at most four per wave
+bool fab_shape(const Plan &p)
+{
+    static const bool off = getenv("KVC_DECODE_SEPARATE") != nullptr;          // developer switch
+    if (off || p.I <= 0 || p.UPBs == kDenseRows) return false;
+    const int T = p.tiles_per_unit << p.UPBs, TW = (T + p.NC - 1) / p.NC;
+    return p.RBW == 4 && p.nvis_b > 0 && p.nvis_b <= 256 && TW <= 16 && p.ntext_a == 0 && p.Hkv * p.NRB <= kMaxFlags;
+}
+
+// the padded row layout is used only where fab_fused can run; workspace sizes are taken from it
+Plan make_plan(const kvc_shape &s, int t, int t_in, int cap, float scale, void *base, bool sizing = false)
+{
+    Plan p = make_plan_layout(s, t, t_in, cap, scale, base, true);
+    if (!sizing && !fab_shape(p)) p = make_plan_layout(s, t, t_in, cap, scale, base, false);
+    return p;
+}
+
 template <int PB> void launch_d1(const Plan &p, const DecodeCall &c)
 {
     fd_finalize_few<PB><<<p.B * p.Hq, 128, 0, c.stream>>>(p.Ypart, static_cast<const uint16_t *>(c.mu),
                                                           static_cast<uint16_t *>(c.out), c.lse, p.Hkv, p.qHkv, p.G,
-                                                          p.qG, p.nparts, p.rec, p.Hq, p.nvp
+                                                          p.qG, p.nparts, p.rec, p.Hq, p.nvp, p.flags,
+                                                          p.fab ? p.Hkv * p.NRB : 0
 #if defined(KVC_TIMELINE)
                                                           , p.tl
 #endif
@@ -1072,6 +1386,76 @@ template <int KS4, int NW> bool launch_b2(const Plan &p, const DecodeCall &c)
                                                                        p.NC, p.qHkv, p.Hkv, p.NRB, p.R, p.R_pad, p.m_pad,
                                                                        p.m, p.n, p);
     return true;
+}
+
+// ---- fab_fused: counters owned by the library ----------------------------------------------------
+// kFlagSets sets of kMaxFlags counters, one per 128-byte line, zero when the code object is loaded
+// and zero again after every call that used them.  A set belongs to one stream (calls on one stream
+// run one after the other); a call on a stream without a set, when all are taken, uses the separate
+// kernels.
+static __device__ __align__(256) unsigned g_fab_flags[kFlagSets * kMaxFlags * kCtrStride];
+
+unsigned *fab_flags_for(hipStream_t stream)
+{
+    static std::mutex mu;
+    static unsigned *base[kMaxDevices] = {};
+    static hipStream_t owner[kMaxDevices][kFlagSets] = {};
+    static int used[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!base[dev]) {
+        // the array's name is a host-side stand-in: its address on this device comes from the runtime
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_fab_flags)) != hipSuccess || !ptr) return nullptr;
+        base[dev] = static_cast<unsigned *>(ptr);
+    }
+    int slot = -1;
+    for (int i = 0; i < used[dev]; ++i)
+        if (owner[dev][i] == stream) slot = i;
+    if (slot < 0) {
+        if (used[dev] == kFlagSets) return nullptr;
+        slot = used[dev]++;
+        owner[dev][slot] = stream;
+    }
+    return base[dev] + static_cast<size_t>(slot) * kMaxFlags * kCtrStride;
+}
+
+template <int KS4, int G> bool launch_ab3(const Plan &p, const DecodeCall &c)
+{
+    static bool attr_set[kMaxDevices] = {};
+    if (!allow_lds(reinterpret_cast<const void *>(fab_fused<KS4, G>), kLdsBudget, attr_set)) return false;
+    fab_fused<KS4, G><<<p.nvis_b, 256, lds_b(p.m_pad), c.stream>>>(
+        static_cast<const uint16_t *>(c.Kc), p.qNC, p.NC, p.qHkv, p.Hkv, p.NRB * p.Hkv, p.tiles_per_unit, p.qTPU, p.UPBs,
+        p.I, p.qI, p.m, p.B * p.I, p, static_cast<const uint16_t *>(c.theta), static_cast<const uint16_t *>(c.q));
+    return true;
+}
+
+template <int KS4> bool launch_ab2(const Plan &p, const DecodeCall &c)
+{
+    switch (p.G) {
+    case 1: return launch_ab3<KS4, 1>(p, c);
+    case 2: return launch_ab3<KS4, 2>(p, c);
+    case 4: return launch_ab3<KS4, 4>(p, c);
+    case 6: return launch_ab3<KS4, 6>(p, c);
+    case 7: return launch_ab3<KS4, 7>(p, c);
+    default: return launch_ab3<KS4, 8>(p, c);
+    }
+}
+
+bool launch_ab(const Plan &p, const DecodeCall &c)
+{
+    switch ((p.m_pad / 32 + 3) / 4) {
+    case 1: return launch_ab2<1>(p, c);
+    case 2: return launch_ab2<2>(p, c);
+    case 3: return launch_ab2<3>(p, c);
+    case 4: return launch_ab2<4>(p, c);
+    case 5: return launch_ab2<5>(p, c);
+    case 6: return launch_ab2<6>(p, c);
+    case 7: return launch_ab2<7>(p, c);
+    case 8: return launch_ab2<8>(p, c);
+    default: return false;
+    }
 }
 
 template <int KS4> bool launch_b1(const Plan &p, const DecodeCall &c)
@@ -1118,7 +1502,7 @@ template <int G, int UP, int NT, int NC> bool launch_c3(const Plan &p, const Dec
     static bool attr_set[kMaxDevices] = {};
     if (!allow_lds(reinterpret_cast<const void *>(fc_fused<G, UP, NT, NC>), lds, attr_set)) return false;
     fc_fused<G, UP, NT, NC><<<p.nvis_c + p.ntext_c, 512, lds, c.stream>>>(
-        static_cast<const uint16_t *>(c.U), p.P, p.stats, p.qJS, p.JS, p.qHkv, p.Hkv, p.B, p.I, p.m, p.R_pad, p,
+        static_cast<const uint16_t *>(c.U), p.P, p.stats, p.qJS, p.JS, p.qHkv, p.Hkv, p.B, p.I, p.m, p.UPBs, p,
         static_cast<const uint16_t *>(c.Vc), static_cast<const uint16_t *>(c.q),
         static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt), static_cast<const uint16_t *>(c.k_new),
         static_cast<const uint16_t *>(c.v_new));
@@ -1166,7 +1550,7 @@ bool fast_decode_supported(const kvc_shape &s)
 
 size_t fast_decode_ws_bytes(const kvc_shape &s, int32_t max_text)
 {
-    return make_plan(s, max_text, max_text, max_text, 1.f, nullptr).bytes + kTimelineBytes;
+    return make_plan(s, max_text, max_text, max_text, 1.f, nullptr, true).bytes + kTimelineBytes;
 }
 
 kvc_status fast_decode(const DecodeCall &c)
@@ -1189,9 +1573,19 @@ kvc_status fast_decode(const DecodeCall &c)
                ? reinterpret_cast<unsigned long long *>(static_cast<char *>(c.ws) + ((c.ws_bytes - kTimelineBytes) & ~size_t(255)))
                : nullptr;
 #endif
-    if (!launch_for_group(p, c, true)) return KVC_ERR_HIP;
-    if (p.nvis_b > 0) {
-        if (!launch_b(p, c)) return KVC_ERR_HIP;
+    if (fab_shape(p)) {
+        static const char *ticks = getenv("KVC_FAB_WAIT_TICKS");                   // developer switch (tests)
+        p.flags = fab_flags_for(c.stream);
+        p.fab = p.flags != nullptr;
+        p.wait_ticks = ticks ? atoi(ticks) : 20000;                                // 200 us
+    }
+    if (p.fab) {
+        if (!launch_ab(p, c)) return KVC_ERR_HIP;
+    } else {
+        if (!launch_for_group(p, c, true)) return KVC_ERR_HIP;
+        if (p.nvis_b > 0) {
+            if (!launch_b(p, c)) return KVC_ERR_HIP;
+        }
     }
     if (!launch_for_group(p, c, false)) return KVC_ERR_HIP;
     launch_d(p, c);
