@@ -476,3 +476,47 @@ def test_decode_replayed_from_a_hip_graph():
         g.replay()
         torch.cuda.synchronize()
         assert np.array_equal(f64(L.out), eager), f"replay {rep} differs from the eager call"
+
+
+def test_fused_scores_and_probabilities_when_every_workgroup_computes_alone():
+    """fab_fused hands the compressed scores from workgroup to workgroup through the L2; a workgroup
+    whose siblings do not arrive in time computes all of its row block's scores itself.  With the
+    waiting time set to zero (a developer switch, read once per process, hence the child process)
+    every workgroup takes that path; the results must still meet the bar."""
+    import os
+    import subprocess
+    import sys
+    env = dict(os.environ, KVC_FAB_WAIT_TICKS="0")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_gpu_parity.py", "-q", "-m", "gpu", "-x",
+                        "-k", "merged_part_records or group_sizes or compressed_lengths or many_text_chunks"],
+                       cwd=root, env=env, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+    assert " passed" in r.stdout
+
+
+def test_decode_on_two_streams_at_once():
+    """Two decode calls in flight on two streams (own workspaces, own sets of arrival counters) give
+    what each gives alone."""
+    w = FAST.with_(name="fast_streams", index=48, n_images=8, batch=2)
+    La, Lb = Layer(w, 103), Layer(w, 103, layer=1)
+    La.compress()
+    Lb.compress()
+    qa, kna, vna = (x.to(DEV) for x in synth.make_step_inputs(w, 0, 0))
+    qb, knb, vnb = (x.to(DEV) for x in synth.make_step_inputs(w, 1, 0))
+    alone_a, _ = La.decode(qa, w.text_len, kna, vna)
+    alone_b, _ = Lb.decode(qb, w.text_len, knb, vnb)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        La.out.zero_()
+        Lb.out.zero_()
+        torch.cuda.synchronize()
+        for _ in range(8):                                       # the same step again and again: same result
+            kv.kvc_reconstruct_attend_decode(La.shape, La.params, qa, La.gKc, La.gVc, La.gKt, La.gVt, w.text_len,
+                                             w.text_cap, kna, vna, 0.0, La.out, La.lse, La.ws, stream=sa)
+            kv.kvc_reconstruct_attend_decode(Lb.shape, Lb.params, qb, Lb.gKc, Lb.gVc, Lb.gKt, Lb.gVt, w.text_len,
+                                             w.text_cap, knb, vnb, 0.0, Lb.out, Lb.lse, Lb.ws, stream=sb)
+        torch.cuda.synchronize()
+        assert np.array_equal(f64(La.out), alone_a), f"round {rep}, stream a"
+        assert np.array_equal(f64(Lb.out), alone_b), f"round {rep}, stream b"
