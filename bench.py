@@ -230,7 +230,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic["bytes_per_call"] if traffic else None,
-                     "kernel": "kvc_reconstruct_attend_decode (fa_scores + fb_probs + fc_fused + fd_finalize)",
+                     "kernel": "kvc_reconstruct_attend_decode (fab_fused or fa_scores + fb_probs, fc_fused, fd_finalize)",
                      "algorithmic_bytes_per_launch": abytes, "us_per_launch": call_us,
                      "us_per_launch_event_pair_each": call_us_pairs,
                      "measured_read_ceiling": read_ceiling},

@@ -19,6 +19,11 @@
  *    attribute (dynamic LDS limit); every later call consists of kernel launches
  *    only -- no allocation, memset, copy or synchronisation -- and may be captured
  *    into a HIP graph.
+ *  - Besides the workspace the decode call uses a few counters in device memory
+ *    that the library itself owns (1 MB per GPU, zero when the library is loaded
+ *    and after every call), one set per stream for the first 16 streams that
+ *    call it; further streams are served without them, a little slower.  Two
+ *    launches of one captured graph must not run at the same time.
  *  - Tensors are dense row-major with head_dim fastest unless strides are
  *    passed.  Every pointer must be 16-byte aligned.
  *  - The return value is a kvc_status; a negative value means nothing was

@@ -1,6 +1,7 @@
 // Matrix-core decode path of KVCapsule for gfx950: bf16 storage, head_dim 128.
 //
-// One decode step of one layer = four launches that follow Alg. 1 of the paper
+// One decode step of one layer = four launches (three where the first two run as one, fab_fused)
+// that follow Alg. 1 of the paper
 // (score-space order), with the softmax taken jointly over vision and text keys
 // (Sec. 3.2) by carrying (max, sum) statistics per part and merging them at the end:
 //
@@ -27,7 +28,8 @@
 //
 // What the measurements on this chip dictate:
 //  * kernel boundaries are the only grid-wide synchronisation: a device-scope fence inside a
-//    kernel writes back and invalidates an XCD's whole L2 and costs far more than a launch;
+//    kernel writes back and invalidates an XCD's whole L2 and costs far more than a launch
+//    (fab_fused synchronises the workgroups of one XCD only, through its L2, without fences);
 //  * a load whose lanes use only half of each 128-byte line (what an MFMA operand fetched
 //    straight from a row-major matrix does: 16 rows x 64 bytes) runs at half the L1 rate; for U
 //    in fc_fused, which is bound by L2 bandwidth, that measured equal to staging coalesced loads
