@@ -22,8 +22,9 @@
  *  - Besides the workspace the decode call uses a few counters in device memory
  *    that the library itself owns (1 MB per GPU, zero when the library is loaded
  *    and after every call), one set per stream for the first 16 streams that
- *    call it; further streams are served without them, a little slower.  Two
- *    launches of one captured graph must not run at the same time.
+ *    call it; further streams are served without them, a little slower.  A call
+ *    captured into a graph keeps the counters of the stream it was captured on:
+ *    its replays must not overlap each other, nor calls made on that stream.
  *  - Tensors are dense row-major with head_dim fastest unless strides are
  *    passed.  Every pointer must be 16-byte aligned.
  *  - The return value is a kvc_status; a negative value means nothing was
