@@ -64,6 +64,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 // 16-byte and 8-byte register images as native vectors (HIP's uint4 / float2 structs turn plain
 // copies into memcpy through private memory, which ends up in scratch)
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));     // a 16-byte access at a dword-aligned address
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int D = 128;          // head_dim of this path
@@ -906,37 +907,60 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
     const int wtail = p.m & 7;
     const bool has_tail = wtail != 0 && hi == p.m;       // the shorter last block lives in the last slice
     const int cch = 16 * wave + r16;                     // this lane's channel
+    // Every lane issues the same two 16-byte loads per image block whatever the slice holds (loads under a
+    // run-time test would be waited for on the spot).  Where a lane's 8-row block is the shorter last one,
+    // [D][wtail], its wtail values are 2 wtail consecutive bytes of that block: the lane reads the 16-byte
+    // window around them (dword aligned, kept inside the block) and shift_tail() moves them into place
+    // once the data is there.  Blocks beyond the record are clamped to a valid one, a record shorter than
+    // one block reads its first 16 bytes; whatever lies in rows j >= m meets a zero weight in W.
+    const int tail_off = cch * 2 * wtail;
+    const int tail_a0 = max(min(tail_off & ~3, D * 2 * wtail - 16), 0);
+    const int tail_sh = tail_off - tail_a0;              // 0 .. 14, even; tail_sh + 2 wtail <= 16
+    const int lb = nfull - jb0;                          // the short block's place in this slice: k-step lb / 4, lanes kg == lb % 4
+    uint32_t voffb[2];                                   // byte offsets into a record
+    int tail_ds[2];                                      // whole dwords to shift by (0 for every other lane)
+    uint32_t tail_bs[2];                                 // then 0 or 16 bits
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        const int jbq = jb0 + 4 * ks + kg;
+        const bool mine = has_tail && jbq == nfull;
+        const int jb = min(jbq, max(nfull - 1, 0));
+        voffb[ks] = mine ? static_cast<uint32_t>(nfull * 8 * D * 2 + tail_a0)
+                         : (nfull > 0 ? static_cast<uint32_t>(jb * 8 * D * 2 + cch * 16) : 0u);
+        tail_ds[ks] = mine ? tail_sh >> 2 : 0;
+        tail_bs[ks] = mine ? (tail_sh & 2) * 8u : 0u;
+    }
     auto load_values = [&](int un0, u32x4 (&dst)[UBATCH][2]) {
 #pragma unroll
         for (int a = 0; a < UBATCH; ++a) {
             const int ub = ub0 + min(un0 + a, nunits - 1);
             const int b = quot(ub, p.qI), i = ub - b * p.I;
-            const uint16_t *vbase = Vc + (static_cast<size_t>(b * p.Hkv + h) * p.I + i) * p.m * D;
+            const char *vbase = reinterpret_cast<const char *>(Vc + (static_cast<size_t>(b * p.Hkv + h) * p.I + i) * p.m * D);
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                // blocks beyond the record are clamped: their weights in W are zero
-                // (a record shorter than one block has no complete block: read its first 16 bytes)
-                const int jb = min(jb0 + 4 * ks + kg, max(nfull - 1, 0));
-                const size_t voff = nfull > 0 ? static_cast<size_t>(jb) * 8 * D + cch * 8 : 0;
-                dst[a][ks] = *reinterpret_cast<const u32x4 *>(vbase + voff);
-            }
-            if (nfull == 0) { dst[a][0] = u32x4_mk(0, 0, 0, 0); dst[a][1] = u32x4_mk(0, 0, 0, 0); }
-            if (has_tail) {                              // [D][wtail] block, element granular
-                const int lb = nfull - jb0;              // its position in this slice: k-step lb / 4, lanes kg == lb % 4
-                uint32_t e[8];
-                const uint16_t *tp = vbase + static_cast<size_t>(nfull) * 8 * D + cch * wtail;
-#pragma unroll
-                for (int q2 = 0; q2 < 8; ++q2) e[q2] = (q2 < wtail && kg == (lb & 3)) ? tp[q2] : 0u;
-                const u32x4 tv = u32x4_mk(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
-                if (kg == (lb & 3)) {
-                    if ((lb >> 2) == 0) dst[a][0] = tv; else dst[a][1] = tv;
-                } else if (jb0 + 4 * (lb >> 2) + kg > nfull) {   // blocks after the tail do not exist
-                    if ((lb >> 2) == 0) dst[a][0] = u32x4_mk(0, 0, 0, 0); else dst[a][1] = u32x4_mk(0, 0, 0, 0);
-                }
-            }
+            for (int ks = 0; ks < 2; ++ks) dst[a][ks] = *reinterpret_cast<const u32x4_a4 *>(vbase + voffb[ks]);
         }
     };
-    u32x4 vfr[UBATCH][2];
+    // 128-bit right shift of the windows of the short block (registers only; other lanes shift by nothing)
+    auto shift_tail = [&](u32x4 (&v)[UBATCH][2]) {
+        if (!has_tail) return;
+#pragma unroll
+        for (int a = 0; a < UBATCH; ++a)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                if (ks != (lb >> 2)) continue;
+                const u32x4 wv = v[a][ks];
+                const bool d1 = tail_ds[ks] & 1, d2 = tail_ds[ks] & 2;
+                const uint32_t y0 = d1 ? wv.y : wv.x, y1 = d1 ? wv.z : wv.y, y2 = d1 ? wv.w : wv.z, y3 = d1 ? 0u : wv.w;
+                const uint32_t x0 = d2 ? y2 : y0, x1 = d2 ? y3 : y1, x2 = d2 ? 0u : y2, x3 = d2 ? 0u : y3;
+                v[a][ks] = u32x4_mk(__builtin_amdgcn_alignbit(x1, x0, tail_bs[ks]), __builtin_amdgcn_alignbit(x2, x1, tail_bs[ks]),
+                                    __builtin_amdgcn_alignbit(x3, x2, tail_bs[ks]), x3 >> tail_bs[ks]);
+            }
+    };
+    // batches of image blocks kept in flight ahead of the one being multiplied
+    constexpr int NBATCH = NU / UBATCH;
+    constexpr int DEPTH = NBATCH >= 4 ? 2 : 1;
+    static_assert(NU % UBATCH == 0, "whole batches");
+    u32x4 vfr[DEPTH + 1][UBATCH][2];
 
     TS(2, 1);
     // ---- block statistics: alpha[row][tile] = exp(tile max - block max) ----------------------------------
@@ -972,7 +996,7 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
 #pragma unroll
         for (int step = 0; step < NSTEP; ++step) {
             if (step + 1 < NSTEP) load_u(step + 1);
-            if (step == NSTEP - 1) load_values(0, vfr);
+            if (step == NSTEP - 1) load_values(0, vfr[0]);
             if (step < nstep) {
 #pragma unroll
                 for (int ci = 0; ci < UCH; ++ci) {      // one softmax tile = 64 positions = two k-steps
@@ -991,6 +1015,9 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
                 }
             }
         }
+    }
+    if constexpr (DEPTH == 2) {                          // the registers of the rows of U are free now
+        load_values(UBATCH, vfr[1]);
     }
     // the two k-halves meet in LDS: half 1 parks its partial sums behind the rows of P
     f32x4 *park = reinterpret_cast<f32x4 *>(dyn + NR * LDP) + jt * (64 * NT) + lane;
@@ -1034,11 +1061,12 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
     }
     f32x4 ysum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int un0 = 0; un0 < NU; un0 += UBATCH) {
-        u32x4 cur[UBATCH][2];
-#pragma unroll
-        for (int a = 0; a < UBATCH; ++a) { cur[a][0] = vfr[a][0]; cur[a][1] = vfr[a][1]; }
-        if (un0 + UBATCH < NU && un0 + UBATCH < nunits) load_values(un0 + UBATCH, vfr);
+    for (int kb = 0; kb < NBATCH; ++kb) {
+        const int un0 = kb * UBATCH;
+        u32x4 (&cur)[UBATCH][2] = vfr[kb % (DEPTH + 1)];
+        // (image blocks the workgroup does not have are clamped to its last one: no run-time test around loads)
+        if (kb + DEPTH < NBATCH) load_values(un0 + DEPTH * UBATCH, vfr[(kb + DEPTH) % (DEPTH + 1)]);
+        shift_tail(cur);
 #pragma unroll
         for (int a = 0; a < UBATCH; ++a) {
             const int un = un0 + a;                      // image block within the workgroup
@@ -1294,6 +1322,7 @@ Plan make_plan_layout(const kvc_shape &s, int t, int t_in, int cap, float scale,
     // bounds fc_fused, so the work is spread first
     p.NT = (p.UP && p.B * p.I > p.UP) ? 2 : 1;
     if (p.NT == 2 && static_cast<long>((p.B * p.I + 2 * p.UP - 1) / (2 * p.UP)) * p.Hkv * p.JS <= 128) p.NT = 1;
+    { static const char *force = getenv("KVC_DECODE_NT"); if (force && p.UP && p.B * p.I > p.UP) p.NT = atoi(force) == 1 ? 1 : 2; }
     p.NG = p.UP ? (p.B * p.I + p.NT * p.UP - 1) / (p.NT * p.UP) : 0;
     p.NXC = (t + kXC - 1) / kXC;
     // the text chunks are extra workgroups of fc_fused; without vision tokens, of fa_scores

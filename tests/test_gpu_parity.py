@@ -291,9 +291,10 @@ def test_fast_path_group_sizes(hq, hkv):
     check_layer(w, m, pre=5, post=3, steps=(0, 2))
 
 
-@pytest.mark.parametrize("m", [1, 7, 26, 64, 200, 256])
+@pytest.mark.parametrize("m", [1, 3, 7, 26, 29, 30, 64, 91, 200, 256])
 def test_fast_path_compressed_lengths(m):
-    """One retained row, a single short slice, a slice boundary, a ragged tail, and m = n."""
+    """One retained row, a single short slice, a slice boundary, ragged tails of every length
+    m mod 8 (1, 3, 7, 2, 5, 6, 0, 3), and m = n."""
     w = FAST.with_(name=f"fast_m{m}", index=40)
     check_layer(w, m, steps=(0,))
 
