@@ -449,25 +449,22 @@ __global__ __launch_bounds__(64 * NW) void fb_probs(const uint16_t *__restrict__
         const int j0 = 2 * jp;
         u32x4 tv[FB][2];
 #pragma unroll
-        for (int k = 0; k < FB; ++k) {
-            tv[k][0] = u32x4_mk(0, 0, 0, 0);
-            tv[k][1] = u32x4_mk(0, 0, 0, 0);
-            if (k < FB - 2 || RPP * k < p.m) {               // a whole pass beyond m is not loaded (uniform test)
+        for (int k = 0; k < FB; ++k)
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const int j = j0 + RPP * k + e;          // single rows beyond m are clamped, then zeroed
-                    tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(min(j, p.m - 1)) * p.n);
-                    if (j >= p.m) tv[k][e] = u32x4_mk(0, 0, 0, 0);
-                }
+            for (int e = 0; e < 2; ++e) {
+                // no run-time test around the loads (they would be waited for on the spot): rows beyond m are
+                // clamped to the last one here and replaced by zeros where they are stored
+                const int j = j0 + RPP * k + e;
+                tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(min(j, p.m - 1)) * p.n);
             }
-        }
         fetch_now(p.m16, p.P, p.stats);
 #pragma unroll
         for (int k = 0; k < FB; ++k) {
             const int j = j0 + RPP * k;
             if (j < p.m16) {
-                const uint32_t a[4] = {tv[k][0].x, tv[k][0].y, tv[k][0].z, tv[k][0].w};
-                const uint32_t c[4] = {tv[k][1].x, tv[k][1].y, tv[k][1].z, tv[k][1].w};
+                const uint32_t ka = j < p.m ? 0xffffffffu : 0u, kc = j + 1 < p.m ? 0xffffffffu : 0u;
+                const uint32_t a[4] = {tv[k][0].x & ka, tv[k][0].y & ka, tv[k][0].z & ka, tv[k][0].w & ka};
+                const uint32_t c[4] = {tv[k][1].x & kc, tv[k][1].y & kc, tv[k][1].z & kc, tv[k][1].w & kc};
                 uint32_t *dst = reinterpret_cast<uint32_t *>(ThT + (8 * seg) * LDT + j);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -632,18 +629,14 @@ __global__ __launch_bounds__(256) void fab_fused(const uint16_t *__restrict__ Kc
         const int j0 = 2 * jp;
         u32x4 tv[FB][2];
 #pragma unroll
-        for (int k = 0; k < FB; ++k) {
-            tv[k][0] = u32x4_mk(0, 0, 0, 0);
-            tv[k][1] = u32x4_mk(0, 0, 0, 0);
-            if (k < FB - 2 || RPP * k < p.m) {               // a whole pass beyond m is not loaded (uniform test)
+        for (int k = 0; k < FB; ++k)
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const int j = j0 + RPP * k + e;          // single rows beyond m are clamped, then zeroed
-                    tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(min(j, p.m - 1)) * p.n);
-                    if (j >= p.m) tv[k][e] = u32x4_mk(0, 0, 0, 0);
-                }
+            for (int e = 0; e < 2; ++e) {
+                // no run-time test around the loads (they would be waited for on the spot): rows beyond m are
+                // clamped to the last one here and replaced by zeros where they are stored
+                const int j = j0 + RPP * k + e;
+                tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(min(j, p.m - 1)) * p.n);
             }
-        }
         fetch_now(p.m16, p.P, p.stats, p.S, p.scale, p.R_pad, p.R, p.RV, p.flags);
         // S tiles of this wave
 #pragma unroll
@@ -658,8 +651,9 @@ __global__ __launch_bounds__(256) void fab_fused(const uint16_t *__restrict__ Kc
         for (int k = 0; k < FB; ++k) {
             const int j = j0 + RPP * k;
             if (j < p.m16) {
-                const uint32_t a[4] = {tv[k][0].x, tv[k][0].y, tv[k][0].z, tv[k][0].w};
-                const uint32_t c[4] = {tv[k][1].x, tv[k][1].y, tv[k][1].z, tv[k][1].w};
+                const uint32_t ka = j < p.m ? 0xffffffffu : 0u, kc = j + 1 < p.m ? 0xffffffffu : 0u;
+                const uint32_t a[4] = {tv[k][0].x & ka, tv[k][0].y & ka, tv[k][0].z & ka, tv[k][0].w & ka};
+                const uint32_t c[4] = {tv[k][1].x & kc, tv[k][1].y & kc, tv[k][1].z & kc, tv[k][1].w & kc};
                 uint32_t *dst = reinterpret_cast<uint32_t *>(ThT + (8 * seg) * LDT + j);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
