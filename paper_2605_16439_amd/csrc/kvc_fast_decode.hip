@@ -950,9 +950,10 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
                                     __builtin_amdgcn_alignbit(x3, x2, tail_bs[ks]), x3 >> tail_bs[ks]);
             }
     };
-    // batches of image blocks kept in flight ahead of the one being multiplied
+    // one batch of image blocks is in flight ahead of the one being multiplied (two ahead measured no
+    // better: their registers cost a resident workgroup per CU)
     constexpr int NBATCH = NU / UBATCH;
-    constexpr int DEPTH = NBATCH >= 4 ? 2 : 1;
+    constexpr int DEPTH = 1;
     static_assert(NU % UBATCH == 0, "whole batches");
     u32x4 vfr[DEPTH + 1][UBATCH][2];
 
@@ -1009,9 +1010,6 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
                 }
             }
         }
-    }
-    if constexpr (DEPTH == 2) {                          // the registers of the rows of U are free now
-        load_values(UBATCH, vfr[1]);
     }
     // the two k-halves meet in LDS: half 1 parks its partial sums behind the rows of P
     f32x4 *park = reinterpret_cast<f32x4 *>(dyn + NR * LDP) + jt * (64 * NT) + lane;
@@ -1316,7 +1314,10 @@ Plan make_plan_layout(const kvc_shape &s, int t, int t_in, int cap, float scale,
     // bounds fc_fused, so the work is spread first
     p.NT = (p.UP && p.B * p.I > p.UP) ? 2 : 1;
     if (p.NT == 2 && static_cast<long>((p.B * p.I + 2 * p.UP - 1) / (2 * p.UP)) * p.Hkv * p.JS <= 128) p.NT = 1;
-    { static const char *force = getenv("KVC_DECODE_NT"); if (force && p.UP && p.B * p.I > p.UP) p.NT = atoi(force) == 1 ? 1 : 2; }
+    {   // developer switch: KVC_DECODE_NT=1|2 overrides the rule above
+        static const char *force = getenv("KVC_DECODE_NT");
+        if (force && p.UP && p.B * p.I > p.UP) p.NT = atoi(force) == 1 ? 1 : 2;
+    }
     p.NG = p.UP ? (p.B * p.I + p.NT * p.UP - 1) / (p.NT * p.UP) : 0;
     p.NXC = (t + kXC - 1) / kXC;
     // the text chunks are extra workgroups of fc_fused; without vision tokens, of fa_scores
