@@ -1309,11 +1309,8 @@ Plan make_plan_layout(const kvc_shape &s, int t, int t_in, int cap, float scale,
     p.nvis_a = (p.vis_tiles + 4 * kTPW - 1) / (4 * kTPW);
     p.UP = units_per_group(p.G);
     p.JS = (p.m + kJC - 1) / kJC;
-    // two MFMA tiles of query rows per workgroup halve the re-streaming of U when the rows are there --
-    // unless that leaves half of the CUs without a workgroup: what one CU can pull in per unit of time
-    // bounds fc_fused, so the work is spread first
+    // two MFMA tiles of query rows per workgroup halve the re-streaming of U when the rows are there
     p.NT = (p.UP && p.B * p.I > p.UP) ? 2 : 1;
-    if (p.NT == 2 && static_cast<long>((p.B * p.I + 2 * p.UP - 1) / (2 * p.UP)) * p.Hkv * p.JS <= 128) p.NT = 1;
     {   // developer switch: KVC_DECODE_NT=1|2 overrides the rule above
         static const char *force = getenv("KVC_DECODE_NT");
         if (force && p.UP && p.B * p.I > p.UP) p.NT = atoi(force) == 1 ? 1 : 2;
