@@ -426,14 +426,18 @@ __global__ __launch_bounds__(64 * NW) void fb_probs(const uint16_t *__restrict__
     const int KS = p.m_pad / 32;
     constexpr int SB = 4 * KS4;
     u32x4 sfr[SB];
-    // (a step of the last group that lies beyond KS re-reads the last step and is zeroed: loads under
-    // a run-time test, even a uniform one, made the compiler wait for each of them in turn and
-    // shuttle the fragments through accumulator registers when KS4 = 2)
+    // (a step of the last group that lies beyond KS re-reads the last step and is masked where it is
+    // used: loads under a run-time test, even a uniform one, made the compiler wait for each of them in
+    // turn and shuttle the fragments through accumulator registers when KS4 = 2; an assignment of
+    // zeros under a test lets the compiler move the load under the test again.)  Every lane loads,
+    // also in a wave whose rows lie beyond R: they exist in the workspace up to R_pad, and nothing of
+    // such a wave is stored.
 #pragma unroll
     for (int k = 0; k < SB; ++k) {
-        sfr[k] = u32x4_mk(0, 0, 0, 0);
-        if (wave_live) sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * (k < SB - 4 ? k : min(k, KS - 1)));
-        if (k >= SB - 4 && k >= KS) sfr[k] = u32x4_mk(0, 0, 0, 0);
+        sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * (k < SB - 4 ? k : min(k, KS - 1)));
+        // the first eight are requested here: left alone, the instruction scheduler spreads the loads over
+        // the matrix work below, a few at a time, and every one becomes a round trip of its own
+        if (k == (SB < 8 ? SB : 8) - 1) __builtin_amdgcn_sched_barrier(0);
     }
 
     TS(1, 1);
@@ -491,7 +495,8 @@ __global__ __launch_bounds__(64 * NW) void fb_probs(const uint16_t *__restrict__
     for (int k = 0; k < SB; ++k) {
         const int ks = min(k, KS - 1);
         // scores beyond the compressed length are zeros written by fa_scores
-        const bf16x8 bfrag = as_bf16x8(sfr[k]);
+        const uint32_t keep = (k < SB - 4 || k < KS) ? 0xffffffffu : 0u;
+        const bf16x8 bfrag = as_bf16x8(u32x4_mk(sfr[k].x & keep, sfr[k].y & keep, sfr[k].z & keep, sfr[k].w & keep));
 #pragma unroll
         for (int mt = 0; mt < PC / 16; ++mt) {
             const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(ThT + (16 * mt + r16) * LDT + 32 * ks + 8 * kg);
@@ -725,14 +730,18 @@ __global__ __launch_bounds__(256) void fab_fused(const uint16_t *__restrict__ Kc
     const int KS = p.m_pad / 32;
     constexpr int SB = 4 * KS4;
     u32x4 sfr[SB];
-    // (a step of the last group that lies beyond KS re-reads the last step and is zeroed: loads under
-    // a run-time test, even a uniform one, made the compiler wait for each of them in turn and
-    // shuttle the fragments through accumulator registers when KS4 = 2)
+    // (a step of the last group that lies beyond KS re-reads the last step and is masked where it is
+    // used: loads under a run-time test, even a uniform one, made the compiler wait for each of them in
+    // turn and shuttle the fragments through accumulator registers when KS4 = 2; an assignment of
+    // zeros under a test lets the compiler move the load under the test again.)  Every lane loads,
+    // also in a wave whose rows lie beyond R: they exist in the workspace up to R_pad, and nothing of
+    // such a wave is stored.
 #pragma unroll
     for (int k = 0; k < SB; ++k) {
-        sfr[k] = u32x4_mk(0, 0, 0, 0);
-        if (wave_live) sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * (k < SB - 4 ? k : min(k, KS - 1)));
-        if (k >= SB - 4 && k >= KS) sfr[k] = u32x4_mk(0, 0, 0, 0);
+        sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * (k < SB - 4 ? k : min(k, KS - 1)));
+        // the first eight are requested here: left alone, the instruction scheduler spreads the loads over
+        // the matrix work below, a few at a time, and every one becomes a round trip of its own
+        if (k == (SB < 8 ? SB : 8) - 1) __builtin_amdgcn_sched_barrier(0);
     }
 
     if (!wave_live) return;
@@ -744,7 +753,8 @@ __global__ __launch_bounds__(256) void fab_fused(const uint16_t *__restrict__ Kc
     for (int k = 0; k < SB; ++k) {
         const int ks = min(k, KS - 1);
         // scores beyond the compressed length are zeros written by fa_scores
-        const bf16x8 bfrag = as_bf16x8(sfr[k]);
+        const uint32_t keep = (k < SB - 4 || k < KS) ? 0xffffffffu : 0u;
+        const bf16x8 bfrag = as_bf16x8(u32x4_mk(sfr[k].x & keep, sfr[k].y & keep, sfr[k].z & keep, sfr[k].w & keep));
 #pragma unroll
         for (int mt = 0; mt < PC / 16; ++mt) {
             const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(ThT + (16 * mt + r16) * LDT + 32 * ks + 8 * kg);
