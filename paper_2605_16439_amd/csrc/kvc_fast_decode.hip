@@ -1245,11 +1245,15 @@ __global__ __launch_bounds__(128) void fd_finalize_few(const float *__restrict__
     const int pl = min(lane, np - 1);
     float ml = yb[static_cast<size_t>(pl) * rec + GD + g];
     float sl = yb[static_cast<size_t>(pl) * rec + GD + p.G + g];
+    __builtin_amdgcn_sched_barrier(0);                   // the statistics are requested first: they are needed first
     const float *yc = yb + g * D + c;
     float v[PB];
 #pragma unroll
     for (int k = 0; k < PB; ++k) v[k] = yc[static_cast<size_t>(min(k, np - 1)) * rec];
-    const float muc = bf_lo(mu[static_cast<size_t>(h) * D + c]);
+    const uint16_t mub = mu[static_cast<size_t>(h) * D + c];
+    // all of the above is requested before anything is waited for (the instruction scheduler would move
+    // part of the loads behind the reductions below: a second round trip)
+    __builtin_amdgcn_sched_barrier(0);
     fetch_now(p.Hq, p.nvp);
     TS(3, 1);
     if (lane >= np) { ml = -INFINITY; sl = 0.f; }
@@ -1260,7 +1264,7 @@ __global__ __launch_bounds__(128) void fd_finalize_few(const float *__restrict__
     const float rz = 1.f / z;
     const float wgt = a * rz;
     TS(3, 3);
-    float y = (zv * rz) * muc;
+    float y = (zv * rz) * bf_lo(mub);
 #pragma unroll
     for (int k = 0; k < PB; ++k) y += __shfl(wgt, k, 64) * v[k];     // clamped duplicates: weight zero
     out[static_cast<size_t>(bg) * D + c] = f32_to_bf16_bits(y);
