@@ -573,7 +573,8 @@ __global__ __launch_bounds__(256) void fab_fused(const uint16_t *__restrict__ Kc
     // ---- phase 1: this workgroup's share of S = sigma q Kc^T for the pair's image blocks ---------------
     // tiles of 16 key rows are numbered (image block of the row block, tile of the block); wave w takes
     // tiles pc TW + w + 4 t; a tile beyond the share repeats the last one and is not stored
-    const int T = a_TPU << a_UPBs, TW = quot(T + a_NC - 1, a_qNC);
+    // (T counts the tiles of the image blocks the row block really has)
+    const int T = a_TPU * min(1 << a_UPBs, a_units - (rb << a_UPBs)), TW = quot(T + a_NC - 1, a_qNC);
     // one tile of S: lane (head r16, key rows 4 kg ..) of image block ub, tile jt
     auto store_tile = [&](const f32x4 &sacc, int ub, int jt) {
         if (r16 >= G) return;                // columns beyond the group are copies of head G-1
@@ -1313,8 +1314,8 @@ Plan make_plan_layout(const kvc_shape &s, int t, int t_in, int cap, float scale,
     p.R_pad = static_cast<int>(align_up(p.R > 0 ? p.R : 1, kRB));
     // 64-row workgroups unless they would need more than two rounds over the CUs: then 128 rows per
     // workgroup re-read the theta chunk half as often
-    p.RBW = (p.I > 0 && static_cast<long>(p.R_pad / 64) * p.Hkv * (p.n / kPC) > 512) ? 8 : 4;
-    p.NRB = p.I > 0 ? (p.R_pad + 16 * p.RBW - 1) / (16 * p.RBW) : 0;
+    p.RBW = (p.I > 0 && static_cast<long>((p.R + 63) / 64) * p.Hkv * (p.n / kPC) > 512) ? 8 : 4;
+    p.NRB = p.I > 0 ? (p.R + 16 * p.RBW - 1) / (16 * p.RBW) : 0;       // row blocks that hold rows
     p.m_pad = static_cast<int>(align_up(p.m, 32));
     p.m16 = static_cast<int>(align_up(p.m, 16));
     p.NC = p.n / kPC;
@@ -1367,13 +1368,15 @@ Plan make_plan_layout(const kvc_shape &s, int t, int t_in, int cap, float scale,
 }
 
 // fa_scores and fb_probs can run as one launch (fab_fused) when all its workgroups are resident at
-// once (one per CU) and a workgroup's share of the score tiles is at most four per wave
+// once (asked of the kernel instance, see fab_resident; never more than two per CU) and a
+// workgroup's share of the score tiles is at most four per wave
 bool fab_shape(const Plan &p)
 {
     static const bool off = getenv("KVC_DECODE_SEPARATE") != nullptr;          // developer switch
     if (off || p.I <= 0 || p.UPBs == kDenseRows) return false;
-    const int T = p.tiles_per_unit << p.UPBs, TW = (T + p.NC - 1) / p.NC;
-    return p.RBW == 4 && p.nvis_b > 0 && p.nvis_b <= 256 && TW <= 16 && p.ntext_a == 0 && p.Hkv * p.NRB <= kMaxFlags;
+    const int T = p.tiles_per_unit * std::min(1 << p.UPBs, p.B * p.I), TW = (T + p.NC - 1) / p.NC;
+    // (whether the chip holds all nvis_b workgroups at once is asked of the kernel instance: fab_resident)
+    return p.RBW == 4 && p.nvis_b > 0 && p.nvis_b <= 512 && TW <= 16 && p.ntext_a == 0 && p.Hkv * p.NRB <= kMaxFlags;
 }
 
 // the padded row layout is used only where fab_fused can run; workspace sizes are taken from it
@@ -1458,42 +1461,61 @@ unsigned *fab_flags_for(hipStream_t stream)
     return base[dev] + static_cast<size_t>(slot) * kMaxFlags * kCtrStride;
 }
 
-template <int KS4, int G> bool launch_ab3(const Plan &p, const DecodeCall &c)
+// probe: no launch; true when all p.nvis_b workgroups of this instance can be resident at once (the
+// capacity is taken for the largest LDS size of the instance and kept per device)
+template <int KS4, int G> bool launch_ab3(const Plan &p, const DecodeCall &c, bool probe)
 {
     static bool attr_set[kMaxDevices] = {};
     if (!allow_lds(reinterpret_cast<const void *>(fab_fused<KS4, G>), kLdsBudget, attr_set)) return false;
+    if (probe) {
+        static int capacity[kMaxDevices] = {};           // 0: not asked yet, -1: unknown
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+        if (capacity[dev] == 0) {
+            int per_cu = 0, cus = 0;
+            const bool ok = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fab_fused<KS4, G>, 256, lds_b(128 * KS4)) == hipSuccess &&
+                            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess;
+            capacity[dev] = (ok && per_cu > 0 && cus > 0) ? per_cu * cus : -1;
+            if (!ok) (void)hipGetLastError();
+        }
+        return p.nvis_b <= capacity[dev];
+    }
     fab_fused<KS4, G><<<p.nvis_b, 256, lds_b(p.m_pad), c.stream>>>(
         static_cast<const uint16_t *>(c.Kc), p.qNC, p.NC, p.qHkv, p.Hkv, p.NRB * p.Hkv, p.tiles_per_unit, p.qTPU, p.UPBs,
         p.I, p.qI, p.m, p.B * p.I, p, static_cast<const uint16_t *>(c.theta), static_cast<const uint16_t *>(c.q));
     return true;
 }
 
-template <int KS4> bool launch_ab2(const Plan &p, const DecodeCall &c)
+template <int KS4> bool launch_ab2(const Plan &p, const DecodeCall &c, bool probe)
 {
     switch (p.G) {
-    case 1: return launch_ab3<KS4, 1>(p, c);
-    case 2: return launch_ab3<KS4, 2>(p, c);
-    case 4: return launch_ab3<KS4, 4>(p, c);
-    case 6: return launch_ab3<KS4, 6>(p, c);
-    case 7: return launch_ab3<KS4, 7>(p, c);
-    default: return launch_ab3<KS4, 8>(p, c);
+    case 1: return launch_ab3<KS4, 1>(p, c, probe);
+    case 2: return launch_ab3<KS4, 2>(p, c, probe);
+    case 4: return launch_ab3<KS4, 4>(p, c, probe);
+    case 6: return launch_ab3<KS4, 6>(p, c, probe);
+    case 7: return launch_ab3<KS4, 7>(p, c, probe);
+    default: return launch_ab3<KS4, 8>(p, c, probe);
     }
 }
 
-bool launch_ab(const Plan &p, const DecodeCall &c)
+bool launch_ab(const Plan &p, const DecodeCall &c, bool probe = false)
 {
     switch ((p.m_pad / 32 + 3) / 4) {
-    case 1: return launch_ab2<1>(p, c);
-    case 2: return launch_ab2<2>(p, c);
-    case 3: return launch_ab2<3>(p, c);
-    case 4: return launch_ab2<4>(p, c);
-    case 5: return launch_ab2<5>(p, c);
-    case 6: return launch_ab2<6>(p, c);
-    case 7: return launch_ab2<7>(p, c);
-    case 8: return launch_ab2<8>(p, c);
+    case 1: return launch_ab2<1>(p, c, probe);
+    case 2: return launch_ab2<2>(p, c, probe);
+    case 3: return launch_ab2<3>(p, c, probe);
+    case 4: return launch_ab2<4>(p, c, probe);
+    case 5: return launch_ab2<5>(p, c, probe);
+    case 6: return launch_ab2<6>(p, c, probe);
+    case 7: return launch_ab2<7>(p, c, probe);
+    case 8: return launch_ab2<8>(p, c, probe);
     default: return false;
     }
 }
+
+// fab_fused relies on all its workgroups being resident at once (its waiting workgroups would otherwise
+// sit out their time limit and compute alone: correct, slow)
+bool fab_resident(const Plan &p, const DecodeCall &c) { return launch_ab(p, c, true); }
 
 template <int KS4> bool launch_b1(const Plan &p, const DecodeCall &c)
 {
@@ -1612,7 +1634,7 @@ kvc_status fast_decode(const DecodeCall &c)
 #endif
     if (fab_shape(p)) {
         static const char *ticks = getenv("KVC_FAB_WAIT_TICKS");                   // developer switch (tests)
-        p.flags = fab_flags_for(c.stream);
+        p.flags = fab_resident(p, c) ? fab_flags_for(c.stream) : nullptr;
         p.fab = p.flags != nullptr;
         p.wait_ticks = ticks ? atoi(ticks) : 20000;                                // 200 us
     }
