@@ -864,14 +864,16 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
     // P rows -> LDS: 16 threads per row, 32 rows per pass
     constexpr int PCH = n / 8;                           // 16-byte pieces per row
     constexpr int KP = (PCH + 15) / 16;
-    u32x4 pfr[KP];
+    constexpr int NPASS = (NR + 31) / 32;                // passes of 32 rows
+    u32x4 pfr[NPASS][KP];
     const int prow_i = threadIdx.x >> 4, psub = threadIdx.x & 15;
-    {
-        const int pr = min(prow_i, NR - 1);
+#pragma unroll
+    for (int ps = 0; ps < NPASS; ++ps) {
+        const int pr = min(prow_i + 32 * ps, NR - 1);
         const int r = row0 + min((pr >> 4) * (UP * G) + min(pr & 15, UP * G - 1), nunits * G - 1);
         const u32x4 *prow = reinterpret_cast<const u32x4 *>(p.P + (static_cast<size_t>(h) * p.R_pad + r) * n);
 #pragma unroll
-        for (int k = 0; k < KP; ++k) pfr[k] = prow[min(16 * k + psub, PCH - 1)];
+        for (int k = 0; k < KP; ++k) pfr[ps][k] = prow[min(16 * k + psub, PCH - 1)];
     }
     // tile statistics: lane (kg = MFMA tile, r16 = row) of wave 0 reads one f32x2 per softmax tile
     f32x2 st[NC];
@@ -984,11 +986,13 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
         sMx[16 * kg + r16] = mx;
         sSm[16 * kg + r16] = sm;
     }
-    if (prow_i < NR) {
-        u32x4 *dst = reinterpret_cast<u32x4 *>(sP + prow_i * LDP);
 #pragma unroll
-        for (int k = 0; k < KP; ++k) dst[min(16 * k + psub, PCH - 1)] = pfr[k];   // clamped duplicates carry equal data
-    }
+    for (int ps = 0; ps < NPASS; ++ps)
+        if (prow_i + 32 * ps < NR) {
+            u32x4 *dst = reinterpret_cast<u32x4 *>(sP + (prow_i + 32 * ps) * LDP);
+#pragma unroll
+            for (int k = 0; k < KP; ++k) dst[min(16 * k + psub, PCH - 1)] = pfr[ps][k];   // clamped duplicates carry equal data
+        }
     __syncthreads();
     TS(2, 2);
 
@@ -1326,9 +1330,14 @@ Plan make_plan_layout(const kvc_shape &s, int t, int t_in, int cap, float scale,
     p.JS = (p.m + kJC - 1) / kJC;
     // two MFMA tiles of query rows per workgroup halve the re-streaming of U when the rows are there
     p.NT = (p.UP && p.B * p.I > p.UP) ? 2 : 1;
-    {   // developer switch: KVC_DECODE_NT=1|2 overrides the rule above
+    // four tiles where the image blocks are short (n = 256: U and P are a large share of a workgroup's
+    // bytes) and many: at least two workgroups per CU remain
+    if (p.NT == 2 && p.n == 4 * kPC && !padded &&
+        static_cast<long>((p.B * p.I + 4 * p.UP - 1) / (4 * p.UP)) * p.Hkv * p.JS >= 512)
+        p.NT = 4;
+    {   // developer switch: KVC_DECODE_NT=1|2|4 overrides the rule above
         static const char *force = getenv("KVC_DECODE_NT");
-        if (force && p.UP && p.B * p.I > p.UP) p.NT = atoi(force) == 1 ? 1 : 2;
+        if (force && p.UP && p.B * p.I > p.UP) p.NT = atoi(force) == 1 ? 1 : (atoi(force) == 4 && p.n == 4 * kPC && !padded) ? 4 : 2;
     }
     p.NG = p.UP ? (p.B * p.I + p.NT * p.UP - 1) / (p.NT * p.UP) : 0;
     p.NXC = (t + kXC - 1) / kXC;
@@ -1581,6 +1590,7 @@ template <int G, int UP> bool launch_ac(const Plan &p, const DecodeCall &c, bool
 {
     if (first) return launch_a<G>(p, c);
     if (p.nvis_c == 0) return true;
+    if (p.NT == 4) return launch_c3<G, UP, 4, 4>(p, c);     // compiled for n = 256 only
     return p.NT == 2 ? launch_c2<G, UP, 2>(p, c) : launch_c2<G, UP, 1>(p, c);
 }
 

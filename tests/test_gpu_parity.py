@@ -496,6 +496,23 @@ def test_fused_scores_and_probabilities_when_every_workgroup_computes_alone():
     assert " passed" in r.stdout
 
 
+def test_separate_launches_with_four_row_tiles_per_workgroup():
+    """Small shapes normally run fab_fused and one or two row tiles per fc_fused workgroup.  Two developer
+    switches (read once per process, hence the child process) send them through the other kernels:
+    fa_scores and fb_probs as separate launches, and fc_fused with four row tiles per workgroup (the
+    instance that long videos use), with ragged groups of image blocks."""
+    import os
+    import subprocess
+    import sys
+    env = dict(os.environ, KVC_DECODE_SEPARATE="1", KVC_DECODE_NT="4")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_gpu_parity.py", "-q", "-m", "gpu", "-x",
+                        "-k", "merged_part_records or group_sizes or compressed_lengths or many_text_chunks"],
+                       cwd=root, env=env, capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+    assert " passed" in r.stdout
+
+
 def test_decode_on_two_streams_at_once():
     """Two decode calls in flight on two streams (own workspaces, own sets of arrival counters) give
     what each gives alone."""
