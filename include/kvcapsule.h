@@ -16,9 +16,10 @@
  *    the default stream) and return without synchronising.  Calls that share a
  *    workspace must be ordered on one stream.
  *  - The first call for a kernel variant on a device also sets a function
- *    attribute (dynamic LDS limit); every later call consists of kernel launches
- *    only -- no allocation, memset, copy or synchronisation -- and may be captured
- *    into a HIP graph.
+ *    attribute (dynamic LDS limit) and asks the runtime for the variant's
+ *    occupancy; every later call consists of kernel launches only.  No call
+ *    allocates, copies, sets memory or synchronises, so every call, the first
+ *    included, may be captured into a HIP graph.
  *  - Besides the workspace the decode call uses a few counters in device memory
  *    that the library itself owns (1 MB per GPU, zero when the library is loaded
  *    and after every call), one set per stream for the first 16 streams that

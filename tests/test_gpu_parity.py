@@ -479,6 +479,19 @@ def test_decode_replayed_from_a_hip_graph():
         assert np.array_equal(f64(L.out), eager), f"replay {rep} differs from the eager call"
 
 
+def test_first_decode_call_of_a_process_inside_a_capture():
+    """No warm-up call is needed before a capture: what the library sets up on its first call (kernel
+    attributes, the address of its counters, the occupancy of its kernels) works inside a stream capture
+    too.  The first call has to be the process's first, hence the child process."""
+    import os
+    import subprocess
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    r = subprocess.run([sys.executable, os.path.join(here, "cold_capture_child.py")], cwd=os.path.dirname(here),
+                       capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and r.stdout.strip().endswith("OK"), r.stdout[-1000:] + r.stderr[-2000:]
+
+
 def test_fused_scores_and_probabilities_when_every_workgroup_computes_alone():
     """fab_fused hands the compressed scores from workgroup to workgroup through the L2; a workgroup
     whose siblings do not arrive in time computes all of its row block's scores itself.  With the
