@@ -267,6 +267,41 @@ def test_fast_and_generic_paths_agree():
     assert row_rel_err(oa, ob) <= 2e-2
 
 
+def test_random_shapes_matrix_core_path_against_scalar_path():
+    """Seeded random shapes inside the limits of the matrix-core kernels (every compiled group size,
+    n in {256, 576, 1024}, 1 to 9 image blocks, any compressed length, text from empty to three chunks):
+    the two device code paths must agree on the same inputs.  The scalar path is checked against the
+    oracle by the tests above; here it lends its reach to many more shapes than the oracle has time for."""
+    rng = np.random.default_rng(20260516)
+    for it in range(24):
+        G = int(rng.choice([1, 2, 4, 6, 7, 8]))
+        hkv = int(rng.choice([1, 2, 3, 4, 8]))
+        n = int(rng.choice([256, 576, 1024]))
+        I, B = int(rng.integers(1, 10)), int(rng.integers(1, 6))
+        m = int(rng.integers(1, n + 1)) if rng.random() < 0.7 else int(rng.choice([1, 7, 8, 9, 63, 64, 65, n - 1, n]))
+        t = int(rng.integers(0, 300))
+        w = synth.Workload(f"rnd{it}", 60 + it, 1, B, G * hkv, hkv, 128, "bf16", n, I, 0.5, t, 2)
+        _say(f"[parity] random shape {it}: G={G} Hkv={hkv} n={n} I={I} B={B} m={m} t={t}")
+        pre = int(rng.integers(0, 4))
+        A, Bg = Layer(w, m, pre=pre), Layer(w, m, pre=pre, generic=True)
+        A.compress()
+        Bg.compress()
+        assert torch.equal(A.gKc, Bg.gKc)
+        Bg.gVc.copy_(A.gVc)
+        tt = w.text_len
+        for step in range(2):
+            q, kn, vn = synth.make_step_inputs(w, 0, step)
+            oa, la = A.decode(q.to(DEV), tt, kn.to(DEV), vn.to(DEV))
+            ob, lb = Bg.decode(q.to(DEV), tt, kn.to(DEV), vn.to(DEV))
+            assert row_rel_err(oa, ob) <= 2e-2
+            # log-sum-exp: the matrix-core path keeps the compressed scores in bf16 (absolute error
+            # grows with their size)
+            assert float(np.abs(la - lb).max()) <= 5e-2 * max(1.0, float(np.abs(lb).max()) / 4)
+            tt += 1
+        del A, Bg
+        torch.cuda.empty_cache()
+
+
 def test_repeat_calls_are_deterministic_and_workspace_is_reusable():
     w = SMALL_BF16.with_(index=17)
     L = Layer(w, 36)
