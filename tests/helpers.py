@@ -29,6 +29,13 @@ def row_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float((num / np.maximum(den, 1e-30)).max())
 
 
+def elem_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max over all elements of |got - ref| / rms(ref row): the element-wise companion of
+    row_rel_err (one channel of a row cannot hide behind the row's norm)."""
+    rms = np.sqrt((ref ** 2).mean(axis=-1, keepdims=True))
+    return float((np.abs(got - ref) / np.maximum(rms, 1e-30)).max())
+
+
 def block_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     """max over (b, h, i) blocks of the Frobenius-norm relative error."""
     num = np.sqrt(((got - ref) ** 2).sum(axis=(-1, -2)))

@@ -391,3 +391,73 @@ def test_brute_force_python_loops_on_tiny_case():
                 y = sum(w[x] * vals[x][c] for x in range(len(vals))) / z
                 assert abs(out[b, gq, c] - y) < 1e-12
             assert abs(lse[b, gq] - (mx + math.log(z))) < 1e-12
+
+
+# ---------------------------------------------------------------- storage rounding inside compress
+def test_compress_with_bf16_storage_is_one_rounding_of_the_exact_result():
+    """Sec. 3.1 (Values) gives V_tilde exactly; the stored capsule is that value rounded ONCE to
+    the storage type.  The oracle's compress with a storage type must therefore equal the library's
+    (torch) bf16 / fp32 rounding of its own unrounded result, and the keys must stay exact copies."""
+    r = rng(21)
+    B, Hkv, d, n, I, pre = 2, 2, 16, 24, 2, 3
+    S = pre + I * n + 2
+    K = torch.from_numpy(r.standard_normal((B, Hkv, S, d))).to(torch.bfloat16).to(torch.float64).numpy()
+    V = r.standard_normal((B, Hkv, S, d)) * 3.0
+    idx = np.array([0, 2, 3, 7, 11, 12, 19, 23], dtype=np.int32)
+    m = len(idx)
+    U = r.standard_normal((Hkv, m, n))
+    mu = r.standard_normal((Hkv, d))
+    Kc0, Vc0 = orc.compress(K, V, idx, U, mu, n, I, pre, orc.STORE_NONE)
+    Kc1, Vc1 = orc.compress(K, V, idx, U, mu, n, I, pre, orc.STORE_BF16)
+    Kc2, Vc2 = orc.compress(K, V, idx, U, mu, n, I, pre, orc.STORE_F32)
+    assert np.array_equal(Kc0, Kc1) and np.array_equal(Kc0, Kc2)
+    # double -> float -> bfloat16 would round twice; the exact double is rounded directly here
+    # (values whose double lies within 2^-24 of a bf16 tie are not in this sample: checked below)
+    lib_bf16 = torch.from_numpy(Vc0).to(torch.bfloat16).to(torch.float64).numpy()
+    lib_f32 = Vc0.astype(np.float32).astype(np.float64)
+    assert np.array_equal(Vc2, lib_f32)
+    differs = Vc1 != lib_bf16
+    if differs.any():       # only where float32 rounding moved the value onto a bf16 tie
+        x = Vc0[differs]
+        assert np.all(np.abs(x.astype(np.float32).astype(np.float64) - x) > 0)
+        assert differs.sum() <= 2
+    # one rounding: the error is at most half a unit in the last place of bf16 (8 significand bits)
+    nz = Vc0 != 0
+    assert np.all(np.abs(Vc1[nz] - Vc0[nz]) <= np.abs(Vc0[nz]) * 2.0 ** -8)
+    assert np.abs(Vc1 - Vc0).max() > 0
+
+
+# ---------------------------------------------------------------- softmax shift invariance
+def test_attention_is_invariant_to_a_common_logit_shift_and_survives_large_logits():
+    """softmax(s + c) = softmax(s) (Sec. 3.1, attention equation).  A common shift of all logits
+    is produced exactly by one extra key channel that is constant over all keys: the output must
+    not move and lse must move by the shift, also when the shifted logits (+-800) would overflow
+    or underflow exp() without the subtraction of the maximum."""
+    p = _tiny_problem(31)
+    Khat, Vhat = orc.reconstruct(p["Kc"], p["Vc"], p["theta"], p["U"], p["mu"], p["n"])
+    B, Hkv, d = p["B"], p["Hkv"], p["d"]
+    t = p["t"]
+    out, lse = orc.attend(p["q"], Khat, Vhat, p["Ktxt"], p["Vtxt"], t, scale=1.0)
+    ones_v = np.ones(Khat.shape[:-1] + (1,))
+    ones_t = np.ones(p["Ktxt"].shape[:-1] + (1,))
+    zeros_v = np.zeros(Vhat.shape[:-1] + (1,))
+    zeros_t = np.zeros(p["Vtxt"].shape[:-1] + (1,))
+    for shift in (3.5, 800.0, -800.0):
+        q2 = np.concatenate([p["q"], np.full(p["q"].shape[:-1] + (1,), shift)], -1)
+        out2, lse2 = orc.attend(q2, np.concatenate([Khat, ones_v], -1), np.concatenate([Vhat, zeros_v], -1),
+                                np.concatenate([p["Ktxt"], ones_t], -1), np.concatenate([p["Vtxt"], zeros_t], -1),
+                                t, scale=1.0)
+        assert np.all(np.isfinite(out2)) and np.all(np.isfinite(lse2))
+        assert np.abs(out2[..., :d] - out).max() < 1e-12
+        assert np.abs(out2[..., d]).max() == 0.0
+        assert np.abs(lse2 - (lse + shift)).max() < 1e-10
+    # large spread: logits of +-1000 around the maximum; the winner takes all, nothing is NaN
+    q3 = p["q"] * 300.0
+    out3, lse3 = orc.attend(q3, Khat, Vhat, p["Ktxt"], p["Vtxt"], t, scale=1.0)
+    assert np.all(np.isfinite(out3)) and np.all(np.isfinite(lse3))
+    allK = np.concatenate([Khat, p["Ktxt"][:, :, :t]], 2)
+    G = p["Hq"] // Hkv
+    for b in range(B):
+        for g in range(p["Hq"]):
+            s = allK[b, g // G] @ q3[b, g]
+            assert abs(lse3[b, g] - (s.max() + np.log(np.exp(s - s.max()).sum()))) < 1e-9
