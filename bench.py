@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--generic", action="store_true", help="force the scalar kernels")
+    ap.add_argument("--no-full-baseline", action="store_true",
+                    help="skip the full-cache (All KV) decode that is timed beside the capsule path")
     ap.add_argument("--read-probe", type=int, default=4, metavar="GiB",
                     help="time a plain streaming read over this many GiB and report it as "
                          "roofline.measured_read_ceiling (GB/s); 0 skips it")
@@ -185,6 +187,54 @@ def main():
     torch.cuda.synchronize()
     call_us_pairs = sum(a.elapsed_time(b) for a, b in pairs) * 1e3 / len(pairs)
 
+    # ---- the same decode step without KVCapsule: full-cache attention over N + t rows ------------
+    # (the "All KV" comparison point of the paper's efficiency analysis), every layer with its own
+    # cache, same number of steps, text growing by one token per step
+    full = None
+    if not args.no_full_baseline and not args.generic:
+        del layers
+        torch.cuda.empty_cache()
+        N = w.n_images * w.n_img_tokens
+        fws = torch.empty(kv.kvc_attend_full_workspace_bytes(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim,
+                                                             dt, N + cap) + 256, dtype=torch.uint8, device=dev)
+        caches = [synth.make_prefill_kv(w, lc % L, 0, cap, device=dev) for lc in range(L * copies)]
+        fwp, fwb = kv._ws(fws)
+        ffn = kv.lib().kvc_attend_full_decode
+        code = kv._dtype_code(dt)
+
+        def fmarshal(s, l, t):
+            Kf, Vf = caches[(s % copies) * L + l]
+            return (w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, code, vp(q_all[s, l].data_ptr()),
+                    vp(Kf.data_ptr()), vp(Vf.data_ptr()), Kf.stride(0), Kf.stride(1), Kf.stride(2), N + t,
+                    N + cap, vp(kn_all[s, l].data_ptr()), vp(vn_all[s, l].data_ptr()), ctypes.c_float(0.0),
+                    vp(out[l].data_ptr()), None, fwp, fwb, stream)
+
+        fwarm = [[fmarshal(s, l, w.text_len) for l in range(L)] for s in range(W)]
+        ftimed = [[fmarshal(W + s, l, w.text_len + s) for l in range(L)] for s in range(K)]
+        for step in fwarm:
+            for a in step:
+                if ffn(*a) != kv.KVC_OK:
+                    raise kv.KvcError(-1, "kvc_attend_full_decode")
+        f_beg, f_end = ev(), ev()
+        torch.cuda.synchronize()
+        f_beg.record()
+        for step in ftimed:
+            for a in step:
+                ffn(*a)
+        f_end.record()
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(out.float()).all()), "non-finite full-cache attention output"
+        full_us = f_beg.elapsed_time(f_end) * 1e3 / (K * L)
+        t_avg_f = w.text_len + (K + 1) / 2.0
+        fbytes = 2 * w.batch * w.n_kv_heads * (N + t_avg_f) * w.head_dim * 2 + 2 * w.batch * w.n_q_heads * w.head_dim * 2
+        full = {"us_per_call": full_us, "algorithmic_bytes_per_call": fbytes,
+                "achieved_gbs": fbytes / (full_us * 1e-6) / 1e9,
+                "frac_of_hbm_peak": fbytes / (full_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                "capsule_us_per_call": call_us, "capsule_speedup": full_us / call_us,
+                "what": "kvc_attend_full_decode over the uncompressed cache (%d vision + text rows), "
+                        "same batch, heads, steps and stream" % N}
+        del caches
+
     if args.copy_probe:
         src = torch.empty(args.copy_probe << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -238,6 +288,9 @@ def main():
                      "tflops": 2.0 * w.batch * w.n_kv_heads * w.n_images * (sum(ms) / L)
                      * w.n_img_tokens * w.head_dim / (comp_ms / (L * copies) * 1e-3) / 1e12},
     }
+
+    if full:
+        res["full_kv_baseline"] = full
 
     # ---- CPU oracle on the host cores, bounded sample of the same workload -----------------------
     # Inputs are host-made synthetic arrays of the workload's shapes (nothing the GPU path produced):

@@ -160,35 +160,32 @@ kvc_status kvc_reconstruct_attend_decode(const kvc_shape *shape, const kvc_param
                                          void *out, float *lse_out,
                                          void *workspace, size_t workspace_bytes, void *stream);
 
-/* The same operation and contract as kvc_reconstruct_attend_decode, forced onto
- * the shape-agnostic scalar kernels (any n, m, d <= 256, either dtype).  The
- * main entry point uses these for shapes its matrix-core kernels do not cover;
- * this symbol exists so both code paths can be checked against each other. */
-kvc_status kvc_reconstruct_attend_decode_generic(const kvc_shape *shape, const kvc_params *params,
-                                                 const void *q, const void *Kc, const void *Vc,
-                                                 void *K_text, void *V_text,
-                                                 int32_t text_len, int32_t text_cap,
-                                                 const void *k_new, const void *v_new,
-                                                 float softmax_scale,
-                                                 void *out, float *lse_out,
-                                                 void *workspace, size_t workspace_bytes,
-                                                 void *stream);
-
-/* Same contract as kvc_compress, forced onto the scalar kernels. */
-kvc_status kvc_compress_generic(const kvc_shape *shape, const kvc_params *params,
-                                const void *K, const void *V,
-                                int64_t stride_b, int64_t stride_h, int64_t stride_s,
-                                int32_t vis_start,
-                                void *Kc, void *Vc,
-                                void *workspace, size_t workspace_bytes, void *stream);
-
-/* Measurement aid (no part of the method): a plain streaming read of `bytes` bytes of device
-   memory at `buf` (16-byte aligned, bytes a multiple of 16), 16 bytes per lane, grid-stride, every
-   value folded into a checksum that is written to `sink` (device, at least 4 bytes) only if it
-   equals a fixed pattern.  Timing it over a buffer much larger than the caches gives the
-   streaming-read rate this chip reaches, to set beside the published HBM peak.  Asynchronous on
-   `stream`.  Errors: KVC_ERR_NULL, KVC_ERR_ALIGN, KVC_ERR_HIP. */
-kvc_status kvc_probe_read(const void *buf, size_t bytes, void *sink, void *stream);
+/* Full-cache ("All KV") decode attention: the comparison point of the paper's efficiency analysis
+ * (Sec. 4; "All KV" rows of Fig. 5) -- the same decode step without KVCapsule.  One new query token
+ * per sequence attends every row of the uncompressed cache (vision and text alike),
+ *     out[b,g,:] = softmax(scale * q[b,g] . K[b,g/G,:t]^T) V[b,g/G,:t]      (Sec. 3.1, attention equation)
+ * after the new token's k, v have been stored at row kv_len (t = kv_len + 1 then; t = kv_len when
+ * k_new / v_new are NULL).
+ *  q        in : [B][H_q][d]
+ *  K, V  in/out: [B][H_kv][kv_cap][d] with element strides stride_b / stride_h / stride_s (d
+ *             contiguous; strides multiples of 8 elements), first kv_len rows valid
+ *  k_new, v_new in (optional, both or neither): [B][H_kv][d], needs kv_len + 1 <= kv_cap
+ *  softmax_scale: 0 selects 1/sqrt(d)
+ *  out      out: [B][H_q][d];  lse_out out (optional): [B][H_q] float
+ *  workspace : kvc_attend_full_workspace_bytes(...) bytes, 256-byte aligned
+ * bf16 with d = 128 and G <= 16 runs a split-KV matrix-core kernel (any strides); other shapes run
+ * the scalar kernels and need a dense cache (KVC_ERR_UNSUPPORTED otherwise).
+ * Errors: NULL pointers, bad sizes, kv_len outside [0, kv_cap], no key at all, misalignment,
+ * workspace too small. */
+size_t kvc_attend_full_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                                       int32_t head_dim, int32_t dtype, int32_t max_kv_len);
+kvc_status kvc_attend_full_decode(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                  int32_t dtype, const void *q, void *K, void *V,
+                                  int64_t stride_b, int64_t stride_h, int64_t stride_s,
+                                  int32_t kv_len, int32_t kv_cap,
+                                  const void *k_new, const void *v_new, float softmax_scale,
+                                  void *out, float *lse_out,
+                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /* Static string for a status code. */
 const char *kvc_status_string(int32_t status);

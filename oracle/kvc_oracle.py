@@ -141,6 +141,16 @@ def attend(q, Kvis, Vvis, Ktxt, Vtxt, t, scale=None, return_probs=False):
     return (out, lse, probs) if return_probs else (out, lse)
 
 
+def attend_full(q, K, V, t, scale=None):
+    """Full-cache ("All KV") attention of the paper's efficiency comparison: the attention equation
+    of Sec. 3.1 over the first t rows of an uncompressed cache K, V [B,Hkv,cap,d].  This is
+    kvc_oracle_attend with no vision rows; nothing is computed here."""
+    K = np.asarray(K, dtype=np.float64)
+    B, Hkv, _, d = K.shape
+    none = np.zeros((B, Hkv, 0, d))
+    return attend(q, none, none, K, V, t, scale)
+
+
 def reconstruct_attend_decode(q, Kc, Vc, theta, U, mu, n, Ktxt, Vtxt, t, k_new=None, v_new=None,
                               scale=None):
     """One decode step of one layer.  Ktxt/Vtxt must be float64 C-contiguous arrays when

@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvcapsule.so")
-SOURCES = ["kvc_api.hip", "kvc_generic.hip", "kvc_fast_decode.hip", "kvc_fast_compress.hip"]
+SOURCES = ["kvc_api.hip", "kvc_generic.hip", "kvc_fast_decode.hip", "kvc_fast_compress.hip",
+           "kvc_full_decode.hip"]
 # packed-fp32 code generation is switched off on purpose: some packed forms have given
 # wrong results on this hardware, so the compiler must not emit them
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
@@ -23,7 +24,8 @@ def _stale() -> bool:
         return True
     t = os.path.getmtime(LIB)
     deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
-    deps.append(os.path.join(HERE, "..", "include", "kvcapsule.h"))
+    inc = os.path.join(HERE, "..", "include")
+    deps += [os.path.join(inc, f) for f in os.listdir(inc)]
     return any(os.path.getmtime(p) > t for p in deps)
 
 

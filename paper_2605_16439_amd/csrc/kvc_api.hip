@@ -3,6 +3,8 @@
 // nothing touched the device.
 #include <math.h>
 
+#include <algorithm>
+
 #include "kvc_internal.h"
 
 using namespace kvc;
@@ -227,6 +229,84 @@ kvc_status kvc_reconstruct_attend_decode_generic(const kvc_shape *shape, const k
 }
 
 namespace {
+// the shape-agnostic decode kernels serve the full cache as a call without vision tokens
+kvc_shape text_only_shape(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t dtype)
+{
+    kvc_shape s;
+    s.batch = B; s.n_q_heads = Hq; s.n_kv_heads = Hkv; s.head_dim = d;
+    s.n_img_tokens = 1; s.n_images = 0; s.m = 1; s.dtype = dtype;
+    return s;
+}
+}  // namespace
+
+size_t kvc_attend_full_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                                       int32_t head_dim, int32_t dtype, int32_t max_kv_len)
+{
+    const kvc_shape s = text_only_shape(batch, n_q_heads, n_kv_heads, head_dim, dtype);
+    if (check_shape(&s) != KVC_OK || max_kv_len < 1) return 0;
+    size_t need = generic_decode_ws_bytes(s, max_kv_len);
+    if (fast_full_supported(dtype, head_dim, n_q_heads / n_kv_heads))
+        need = std::max(need, fast_full_ws_bytes(batch, n_q_heads, n_kv_heads));
+    return need;
+}
+
+kvc_status kvc_attend_full_decode(int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                  int32_t dtype, const void *q, void *K, void *V, int64_t stride_b,
+                                  int64_t stride_h, int64_t stride_s, int32_t kv_len, int32_t kv_cap,
+                                  const void *k_new, const void *v_new, float softmax_scale, void *out,
+                                  float *lse_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const kvc_shape s = text_only_shape(batch, n_q_heads, n_kv_heads, head_dim, dtype);
+    kvc_status st = check_shape(&s);
+    if (st != KVC_OK) return st;
+    if (!q || !out || !K || !V) return KVC_ERR_NULL;
+    if (kv_cap < 1 || kv_len < 0 || kv_len > kv_cap) return KVC_ERR_SHAPE;
+    if ((k_new == nullptr) != (v_new == nullptr)) return KVC_ERR_NULL;
+    if (k_new && kv_len + 1 > kv_cap) return KVC_ERR_SHAPE;
+    const int32_t t = kv_len + (k_new ? 1 : 0);
+    if (t == 0) return KVC_ERR_SHAPE;                               // softmax over no key
+    if (!(softmax_scale >= 0.f) || isinf(softmax_scale)) return KVC_ERR_SHAPE;
+    if (stride_s < head_dim || stride_h < 0 || stride_b < 0) return KVC_ERR_SHAPE;
+    if (stride_s % 8 || stride_h % 8 || stride_b % 8) return KVC_ERR_ALIGN;
+    if (!aligned16(q) || !aligned16(out) || !aligned16(K) || !aligned16(V) || !aligned16(k_new) ||
+        !aligned16(v_new) || (reinterpret_cast<uintptr_t>(lse_out) & 3u))
+        return KVC_ERR_ALIGN;
+    if (!workspace) return KVC_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return KVC_ERR_ALIGN;
+    const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf(static_cast<float>(head_dim));
+    if (fast_full_supported(dtype, head_dim, n_q_heads / n_kv_heads)) {
+        FullCall c;
+        c.B = batch; c.Hq = n_q_heads; c.Hkv = n_kv_heads;
+        c.q = q; c.K = K; c.V = V;
+        c.sb = stride_b; c.sh = stride_h; c.ss = stride_s;
+        c.t = t; c.t_in = kv_len;
+        c.k_new = k_new; c.v_new = v_new;
+        c.scale = scale; c.out = out; c.lse = lse_out;
+        c.ws = workspace; c.ws_bytes = workspace_bytes;
+        c.stream = static_cast<hipStream_t>(stream);
+        c.cus = 0;
+        return fast_full_decode(c);
+    }
+    // scalar kernels: dense cache only
+    if (stride_s != head_dim || stride_h != static_cast<int64_t>(kv_cap) * head_dim ||
+        stride_b != stride_h * n_kv_heads)
+        return KVC_ERR_UNSUPPORTED;
+    DecodeCall c;
+    c.s = s;
+    c.theta = q; c.U = q; c.mu = q;          // never multiplied by anything but zero without vision tokens
+    c.q = q; c.Kc = q; c.Vc = q;
+    c.Kt = K; c.Vt = V;
+    c.t = t; c.t_in = kv_len; c.cap = kv_cap;
+    c.k_new = k_new; c.v_new = v_new;
+    c.scale = scale; c.out = out; c.lse = lse_out;
+    c.ws = workspace; c.ws_bytes = workspace_bytes;
+    c.stream = static_cast<hipStream_t>(stream);
+    return generic_decode(c);
+}
+
+void kvc_dev_full_decode_chunk_steps(int32_t steps) { full_decode_set_chunk_steps(steps); }
+
+namespace {
 __global__ __launch_bounds__(256) void probe_read(const uint4 *__restrict__ p, size_t n16, unsigned *sink)
 {
     size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -267,6 +347,6 @@ const char *kvc_status_string(int32_t status)
     }
 }
 
-const char *kvc_version(void) { return "0.1"; }
+const char *kvc_version(void) { return "0.2"; }
 
 }  // extern "C"

@@ -1608,6 +1608,25 @@ bool launch_for_group(const Plan &p, const DecodeCall &c, bool first)
 
 }  // namespace
 
+kvc_status finalize_parts(const float *Ypart, int nparts, int nvp, int rec, int B, int Hq, int Hkv, const void *mu,
+                          void *out, float *lse, hipStream_t stream)
+{
+    if (nparts < 1 || nparts > 64) return KVC_ERR_UNSUPPORTED;
+    Plan p;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = Hq / Hkv;
+    p.qHkv = quot_multiplier(Hkv); p.qG = quot_multiplier(p.G);
+    p.nparts = nparts; p.nvp = nvp; p.rec = rec;
+    p.Ypart = const_cast<float *>(Ypart);
+    p.flags = nullptr; p.fab = 0; p.NRB = 0;
+#if defined(KVC_TIMELINE)
+    p.tl = nullptr;
+#endif
+    DecodeCall c;
+    c.mu = mu; c.out = out; c.lse = lse; c.stream = stream;
+    launch_d(p, c);
+    return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
+}
+
 bool fast_decode_supported(const kvc_shape &s)
 {
     if (s.dtype != KVC_BF16 || s.head_dim != D) return false;

@@ -21,6 +21,8 @@
 // Bound: HBM (2 B H_kv (S + 1) d 2 bytes are read once; 4 flop per byte).
 #include "kvc_internal.h"
 
+#include <algorithm>
+
 namespace kvc {
 namespace {
 
@@ -232,7 +234,7 @@ FullPlan make_full_plan(const FullCall &c, void *ws)
     }
     while ((steps_total + cs - 1) / cs > kMaxSplits) ++cs;
     p.chunk = cs * kStep;
-    p.nit = cs;
+    p.nit = std::min(cs, steps_total);
     p.NS = (c.t + p.chunk - 1) / p.chunk;
     p.rec = static_cast<int>(align_up(static_cast<size_t>(p.G) * D + 2 * p.G, 4));
     p.qNS = quot_multiplier(p.NS);

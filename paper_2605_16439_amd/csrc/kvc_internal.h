@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "../../include/kvcapsule.h"
+#include "../../include/kvcapsule_dev.h"
 
 namespace kvc {
 
@@ -85,6 +86,24 @@ struct CompressCall {
     hipStream_t stream;
 };
 
+// full-cache decode attention (the "All KV" comparison point), validated
+struct FullCall {
+    int B, Hq, Hkv;
+    const void *q;
+    void *K, *V;
+    long sb, sh, ss;  // element strides of the cache [B][H_kv][cap][d]
+    int32_t t;        // rows attended (new token included when appended)
+    int32_t t_in;     // rows valid before the call; the new token goes to this row
+    const void *k_new, *v_new;
+    float scale;
+    void *out;
+    float *lse;
+    void *ws;
+    size_t ws_bytes;
+    hipStream_t stream;
+    int cus;          // compute units of the device (0: ask the runtime)
+};
+
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Raises a kernel's dynamic-LDS limit once per device (the attribute is per device); `done` is the
@@ -109,6 +128,16 @@ kvc_status generic_compress(const CompressCall &c);
 bool fast_decode_supported(const kvc_shape &s);
 size_t fast_decode_ws_bytes(const kvc_shape &s, int32_t max_text);
 kvc_status fast_decode(const DecodeCall &c);
+// merges nparts part records ([G][128] un-normalised outputs, [G] maxima, [G] sums; the first nvp
+// of them vision parts, whose probability mass multiplies mu) of every (batch element, query
+// head) into out / lse; nparts <= 64
+kvc_status finalize_parts(const float *Ypart, int nparts, int nvp, int rec, int B, int Hq, int Hkv, const void *mu,
+                          void *out, float *lse, hipStream_t stream);
+// full-cache decode, bf16, head_dim 128
+bool fast_full_supported(int dtype, int head_dim, int G);
+size_t fast_full_ws_bytes(int B, int Hq, int Hkv);
+kvc_status fast_full_decode(const FullCall &c);
+void full_decode_set_chunk_steps(int steps);
 bool fast_compress_supported(const kvc_shape &s);
 size_t fast_compress_ws_bytes(const kvc_shape &s);
 kvc_status fast_compress(const CompressCall &c);

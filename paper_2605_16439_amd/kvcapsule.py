@@ -30,6 +30,7 @@ EXPORTS = [
     "kvc_compressed_len", "kvc_workspace_bytes", "kvc_memory_footprint", "kvc_compress",
     "kvc_reconstruct_attend_decode", "kvc_reconstruct_attend_decode_generic",
     "kvc_compress_generic", "kvc_probe_read", "kvc_status_string", "kvc_version",
+    "kvc_attend_full_workspace_bytes", "kvc_attend_full_decode", "kvc_dev_full_decode_chunk_steps",
 ]
 
 
@@ -81,6 +82,13 @@ def lib() -> ctypes.CDLL:
         for name in ("kvc_reconstruct_attend_decode", "kvc_reconstruct_attend_decode_generic"):
             getattr(L, name).restype = i32
             getattr(L, name).argtypes = dec
+        L.kvc_attend_full_workspace_bytes.restype = ctypes.c_size_t
+        L.kvc_attend_full_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
+        L.kvc_attend_full_decode.restype = i32
+        L.kvc_attend_full_decode.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, i64, i64, i64, i32, i32,
+                                             vp, vp, ctypes.c_float, vp, vp, vp, ctypes.c_size_t, vp]
+        L.kvc_dev_full_decode_chunk_steps.restype = None
+        L.kvc_dev_full_decode_chunk_steps.argtypes = [i32]
         L.kvc_probe_read.restype = i32
         L.kvc_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         L.kvc_status_string.restype = ctypes.c_char_p
@@ -189,4 +197,25 @@ def kvc_reconstruct_attend_decode(shape: KvcShape, params: KvcParams, q, Kc, Vc,
             ctypes.c_float(softmax_scale), _ptr(out), _ptr(lse_out), wp, wb, _stream(stream))
     if check and st != KVC_OK:
         raise KvcError(st, "kvc_reconstruct_attend_decode")
+    return st
+
+
+def kvc_attend_full_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, dtype, max_kv_len) -> int:
+    code = dtype if isinstance(dtype, int) else _dtype_code(dtype)
+    return int(lib().kvc_attend_full_workspace_bytes(batch, n_q_heads, n_kv_heads, head_dim, code,
+                                                     int(max_kv_len)))
+
+
+def kvc_attend_full_decode(q, K, V, kv_len: int, k_new, v_new, softmax_scale: float, out, lse_out,
+                           workspace, stream=None, check: bool = True) -> int:
+    """Full-cache decode attention.  q, out: [B, H_q, d]; K, V: [B, H_kv, kv_cap, d] (d contiguous)."""
+    assert K.stride() == V.stride() and K.stride(3) == 1
+    B, Hq, d = q.shape
+    wp, wb = _ws(workspace)
+    st = lib().kvc_attend_full_decode(B, Hq, K.shape[1], d, _dtype_code(q.dtype), _ptr(q), _ptr(K), _ptr(V),
+                                      K.stride(0), K.stride(1), K.stride(2), int(kv_len), K.shape[2],
+                                      _ptr(k_new), _ptr(v_new), ctypes.c_float(softmax_scale), _ptr(out),
+                                      _ptr(lse_out), wp, wb, _stream(stream))
+    if check and st != KVC_OK:
+        raise KvcError(st, "kvc_attend_full_decode")
     return st

@@ -14,7 +14,10 @@ GOLDEN = os.path.join(ROOT, "tests", "golden")
 
 
 def header_functions():
-    txt = open(os.path.join(ROOT, "include", "kvcapsule.h")).read()
+    txt = ""
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if name.endswith(".h"):
+            txt += open(os.path.join(ROOT, "include", name)).read()
     txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
     return sorted(set(re.findall(r"\b(kvc_[a-z_0-9]+)\s*\(", txt)))
 

@@ -264,6 +264,30 @@ def test_text_only_is_plain_sdpa():
     assert np.abs(out - sdpa(p["q"], p["Ktxt"], p["Vtxt"], 0.3)).max() < 1e-13
 
 
+def test_full_cache_attention_is_library_sdpa_on_the_concatenation():
+    """The "All KV" comparison point (Sec. 4 / Fig. 5): attention over [K_vis ; K_txt] with nothing
+    compressed.  Both ways of handing the rows to the oracle (two buffers, or one full cache) equal
+    the library's attention on the concatenated rows, GQA included; rows beyond t are ignored."""
+    r = rng(41)
+    B, Hq, Hkv, d, N, t, cap = 2, 6, 2, 8, 11, 5, 8
+    q = r.standard_normal((B, Hq, d))
+    Kv, Vv = r.standard_normal((B, Hkv, N, d)), r.standard_normal((B, Hkv, N, d))
+    Kt, Vt = r.standard_normal((B, Hkv, cap, d)), r.standard_normal((B, Hkv, cap, d))
+    scale = 0.41
+    Kall = np.concatenate([Kv, Kt[:, :, :t]], 2)
+    Vall = np.concatenate([Vv, Vt[:, :, :t]], 2)
+    ref = sdpa(q, Kall, Vall, scale)
+    out, lse = orc.attend(q, Kv, Vv, Kt, Vt, t, scale)
+    assert np.abs(out - ref).max() < 1e-13
+    pad = r.standard_normal((B, Hkv, 3, d)) * 50.0                  # garbage beyond the valid rows
+    out2, lse2 = orc.attend_full(q, np.concatenate([Kall, pad], 2), np.concatenate([Vall, pad], 2), N + t, scale)
+    assert np.abs(out2 - ref).max() < 1e-13
+    assert np.abs(lse2 - lse).max() < 1e-13
+    G = Hq // Hkv
+    s = scale * np.einsum("bgd,bgxd->bgx", q, Kall.repeat(G, axis=1))
+    assert np.abs(lse2 - np.log(np.exp(s).sum(-1))).max() < 1e-12
+
+
 def test_block_diagonal_dense_form_matches_library():
     """Independent construction: per-block reconstruction written as one dense
     block-diagonal matrix (kron), then library matmul + library SDPA."""
