@@ -160,6 +160,24 @@ kvc_status kvc_reconstruct_attend_decode(const kvc_shape *shape, const kvc_param
                                          void *out, float *lse_out,
                                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate or hand over device memory at call time (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): kvc_reconstruct_attend_decode
+ * without the workspace arguments.  Same operation, same kernels, same results; the scratch lives in a
+ * device array inside the library, kvc_static_scratch_bytes() = 32 MiB per GPU, held until the process
+ * ends.  The call allocates nothing and frees nothing.  A shape whose kvc_workspace_bytes(shape,
+ * text_cap) exceeds that size is refused with KVC_ERR_WORKSPACE before anything is launched (the five
+ * benchmark configurations fit).  Every call on a GPU shares that GPU's one array: calls that overlap
+ * on one GPU (two streams, overlapping graph replays) race on it and must be ordered by the caller;
+ * the array keeps the previous call's contents, none of which a later call relies on. */
+size_t kvc_static_scratch_bytes(void);
+kvc_status kvc_reconstruct_attend_decode_static(const kvc_shape *shape, const kvc_params *params,
+                                                const void *q, const void *Kc, const void *Vc,
+                                                void *K_text, void *V_text,
+                                                int32_t text_len, int32_t text_cap,
+                                                const void *k_new, const void *v_new,
+                                                float softmax_scale,
+                                                void *out, float *lse_out, void *stream);
+
 /* Full-cache ("All KV") decode attention: the comparison point of the paper's efficiency analysis
  * (Sec. 4; "All KV" rows of Fig. 5) -- the same decode step without KVCapsule.  One new query token
  * per sequence attends every row of the uncompressed cache (vision and text alike),

@@ -4,6 +4,7 @@
 #include <math.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "kvc_internal.h"
 
@@ -225,6 +226,56 @@ kvc_status kvc_reconstruct_attend_decode_generic(const kvc_shape *shape, const k
                                    k_new, v_new, softmax_scale, out, lse_out, workspace,
                                    workspace_bytes, stream);
     if (st != KVC_OK) return st;
+    return generic_decode(c);
+}
+
+// ---- decode without a workspace argument, for callers that cannot allocate ------------------------
+namespace {
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(32) << 20;
+// Scratch memory of kvc_reconstruct_attend_decode_static.  Every GPU the library runs on holds its
+// own copy of this array, at its own address, until the process ends.  In host code the name below
+// is only a handle for hipGetSymbolAddress: kernels and copies get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// address of `scratch` on the current device; asked of the runtime once per device
+void *static_scratch_ptr()
+{
+    static std::mutex mu;
+    static void *ptr[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        ptr[dev] = p;
+    }
+    return ptr[dev];
+}
+}  // namespace
+
+size_t kvc_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+kvc_status kvc_reconstruct_attend_decode_static(const kvc_shape *shape, const kvc_params *params,
+                                                const void *q, const void *Kc, const void *Vc,
+                                                void *K_text, void *V_text, int32_t text_len,
+                                                int32_t text_cap, const void *k_new, const void *v_new,
+                                                float softmax_scale, void *out, float *lse_out,
+                                                void *stream)
+{
+    // every argument check first, with a stand-in for the workspace address
+    DecodeCall c;
+    kvc_status st = prepare_decode(c, shape, params, q, Kc, Vc, K_text, V_text, text_len, text_cap,
+                                   k_new, v_new, softmax_scale, out, lse_out,
+                                   reinterpret_cast<void *>(static_cast<uintptr_t>(256)), kStaticScratchBytes, stream);
+    if (st != KVC_OK) return st;
+    if (kvc_workspace_bytes(shape, text_cap) > kStaticScratchBytes) return KVC_ERR_WORKSPACE;
+    c.ws = static_scratch_ptr();
+    if (!c.ws) return KVC_ERR_HIP;
+    if (fast_decode_supported(c.s)) return fast_decode(c);
     return generic_decode(c);
 }
 

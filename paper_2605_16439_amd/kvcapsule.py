@@ -30,6 +30,7 @@ EXPORTS = [
     "kvc_compressed_len", "kvc_workspace_bytes", "kvc_memory_footprint", "kvc_compress",
     "kvc_reconstruct_attend_decode", "kvc_reconstruct_attend_decode_generic",
     "kvc_compress_generic", "kvc_probe_read", "kvc_status_string", "kvc_version",
+    "kvc_static_scratch_bytes", "kvc_reconstruct_attend_decode_static",
     "kvc_attend_full_workspace_bytes", "kvc_attend_full_decode", "kvc_dev_full_decode_chunk_steps",
 ]
 
@@ -82,6 +83,10 @@ def lib() -> ctypes.CDLL:
         for name in ("kvc_reconstruct_attend_decode", "kvc_reconstruct_attend_decode_generic"):
             getattr(L, name).restype = i32
             getattr(L, name).argtypes = dec
+        L.kvc_static_scratch_bytes.restype = ctypes.c_size_t
+        L.kvc_static_scratch_bytes.argtypes = []
+        L.kvc_reconstruct_attend_decode_static.restype = i32
+        L.kvc_reconstruct_attend_decode_static.argtypes = dec[:-3] + [vp]
         L.kvc_attend_full_workspace_bytes.restype = ctypes.c_size_t
         L.kvc_attend_full_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, i32]
         L.kvc_attend_full_decode.restype = i32
@@ -218,4 +223,17 @@ def kvc_attend_full_decode(q, K, V, kv_len: int, k_new, v_new, softmax_scale: fl
                                       _ptr(lse_out), wp, wb, _stream(stream))
     if check and st != KVC_OK:
         raise KvcError(st, "kvc_attend_full_decode")
+    return st
+
+
+def kvc_reconstruct_attend_decode_static(shape: KvcShape, params: KvcParams, q, Kc, Vc, K_text, V_text,
+                                         text_len: int, text_cap: int, k_new, v_new, softmax_scale: float,
+                                         out, lse_out, stream=None, check: bool = True) -> int:
+    """kvc_reconstruct_attend_decode with the library's own scratch array instead of a workspace."""
+    st = lib().kvc_reconstruct_attend_decode_static(
+        ctypes.byref(shape), ctypes.byref(params), _ptr(q), _ptr(Kc), _ptr(Vc), _ptr(K_text), _ptr(V_text),
+        int(text_len), int(text_cap), _ptr(k_new), _ptr(v_new), ctypes.c_float(softmax_scale), _ptr(out),
+        _ptr(lse_out), _stream(stream))
+    if check and st != KVC_OK:
+        raise KvcError(st, "kvc_reconstruct_attend_decode_static")
     return st
