@@ -125,6 +125,13 @@ kvc_status prepare_compress(CompressCall &c, const kvc_shape *shape, const kvc_p
     return KVC_OK;
 }
 
+// the matrix-core kernels where the shape allows it, else the scalar kernels
+kvc_status dispatch_decode(const DecodeCall &c)
+{
+    if (fast_decode_supported(c.s)) return fast_decode(c);
+    return generic_decode(c);
+}
+
 }  // namespace
 
 extern "C" {
@@ -209,8 +216,7 @@ kvc_status kvc_reconstruct_attend_decode(const kvc_shape *shape, const kvc_param
                                    k_new, v_new, softmax_scale, out, lse_out, workspace,
                                    workspace_bytes, stream);
     if (st != KVC_OK) return st;
-    if (fast_decode_supported(c.s)) return fast_decode(c);
-    return generic_decode(c);
+    return dispatch_decode(c);
 }
 
 kvc_status kvc_reconstruct_attend_decode_generic(const kvc_shape *shape, const kvc_params *params,
@@ -275,8 +281,7 @@ kvc_status kvc_reconstruct_attend_decode_static(const kvc_shape *shape, const kv
     if (kvc_workspace_bytes(shape, text_cap) > kStaticScratchBytes) return KVC_ERR_WORKSPACE;
     c.ws = static_scratch_ptr();
     if (!c.ws) return KVC_ERR_HIP;
-    if (fast_decode_supported(c.s)) return fast_decode(c);
-    return generic_decode(c);
+    return dispatch_decode(c);
 }
 
 namespace {
@@ -356,6 +361,8 @@ kvc_status kvc_attend_full_decode(int32_t batch, int32_t n_q_heads, int32_t n_kv
 }
 
 void kvc_dev_full_decode_chunk_steps(int32_t steps) { full_decode_set_chunk_steps(steps); }
+
+
 
 namespace {
 __global__ __launch_bounds__(256) void probe_read(const uint4 *__restrict__ p, size_t n16, unsigned *sink)

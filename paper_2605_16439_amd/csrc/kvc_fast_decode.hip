@@ -49,7 +49,7 @@
 // Query rows of one KV head: image block ub = b*I + i owns G consecutive rows (one per query head of
 // the group), and UPB = 2^UPBs whole image blocks fill a 64-row block (the rest of its rows unused), so
 // that consecutive image blocks share MFMA tiles and no image block straddles two 64-row blocks.
-#include "kvc_internal.h"
+#include "kvc_decode_dev.h"
 
 #include <algorithm>
 #include <cstdlib>
@@ -58,238 +58,7 @@
 namespace kvc {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-// 16-byte and 8-byte register images as native vectors (HIP's uint4 / float2 structs turn plain
-// copies into memcpy through private memory, which ends up in scratch)
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef u32x4 u32x4_a4 __attribute__((aligned(4)));     // a 16-byte access at a dword-aligned address
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
-constexpr int D = 128;          // head_dim of this path
-constexpr int kRB = 128;        // query rows are padded to this: fb_probs workgroups take 64 or 128 (4 or 8 waves)
-constexpr int kPC = 64;         // positions per fb_probs workgroup (one softmax tile)
-constexpr int kTPW = 2;         // 16-row key tiles per wavefront in fa_scores
-constexpr int kJC = 64;         // capsule rows per fc_fused workgroup (one 16-row tile per wave)
-constexpr int kXC = 128;        // text rows per fa_scores text workgroup
-constexpr int kMaxParts = 256;  // fd_finalize keeps one scale per part in LDS
-constexpr int kSWLD = kXC + 8;  // padded row (bf16) of the text probabilities in LDS
-constexpr int kLDV = kXC + 8;   // padded row (bf16) of the transposed text values in LDS
-constexpr int kWLD = kJC + 8;   // padded row (bf16) of the W tile in LDS
-constexpr size_t kLdsBudget = 150 * 1024;
-constexpr int kCtrStride = 32;  // an arrival counter per 128-byte line
-constexpr int kMaxFlags = 512;  // counters per set
-constexpr int kFlagSets = 16;   // one set per stream in use
-constexpr int kDenseRows = 24;  // "image blocks per 64-row block" = 2^24: the dense layout of the query rows
-
-struct Plan {
-    int B, Hq, Hkv, G, n, I, m, t, t_in, cap;
-    int R, R_pad, NRB, RBW, m_pad, m16, NC;   // RBW: waves (16-row tiles) per fb_probs workgroup
-    int UPBs, RV;                   // log2 of the image blocks per 64-row block of query rows; valid rows of a full block
-    int fab;                        // fa_scores and fb_probs run as one launch (fab_fused)
-    int wait_ticks;                 // fab_fused: how long a workgroup waits for its siblings (10 ns units)
-    unsigned *flags;                // fab_fused: [Hkv NRB] arrival counters, one per 128-byte line, zero between calls
-    int tiles_per_unit, vis_tiles, nvis_a, ntext_a;   // fa_scores: vision workgroups, text workgroups (these come first)
-    int ntext_c;                    // fc_fused: text workgroups (the highest ids)
-    int UP, NT, NG, JS, NXC, nparts, rec;
-    int merge, nvp;                 // one part per workgroup (its image blocks merged); vision parts per (b, head)
-    int nvis_b, nvis_c;
-    // multipliers for the divisions by NXC, Hkv, tiles_per_unit, I, NC, JS and G (see quot())
-    unsigned qNXC, qHkv, qTPU, qI, qNC, qJS, qG;
-    float scale;
-#if defined(KVC_TIMELINE)
-    unsigned long long *tl;         // timeline slots, see TS()
-#endif
-    uint16_t *S;
-    uint16_t *P;
-    f32x2 *stats;
-    float *Ypart;
-    size_t bytes;
-};
-
-// Developer aid, compiled in only with -DKVC_TIMELINE: thread 0 of every workgroup records the
-// wall clock at a few points of each kernel (kernel id, slot) in the last MiB of the workspace.
-#if defined(KVC_TIMELINE)
-#define TS(KID, K)                                                                        \
-    do {                                                                                  \
-        if (p.tl && threadIdx.x == 0)                                                     \
-            p.tl[((KID) * 1024 + (blockIdx.x < 1024 ? blockIdx.x : 1023)) * 8 + (K)] = wall_clock64(); \
-    } while (0)
-constexpr size_t kTimelineBytes = 1 << 20;
-#else
-#define TS(KID, K) do { } while (0)
-constexpr size_t kTimelineBytes = 0;
-#endif
-
-// x / d for 0 <= x with x d < 2^32, as one multiplication by q = floor(2^32 / d) + 1 (q = 0 stands
-// for d = 1).  The index arithmetic at the top of every kernel sits in front of its first load; a
-// division by a run-time value costs some thirty dependent instructions there.
-__device__ inline int quot(int x, unsigned q) { return q ? static_cast<int>(__umulhi(static_cast<unsigned>(x), q)) : x; }
-inline unsigned quot_multiplier(int d) { return d > 1 ? static_cast<unsigned>((1ull << 32) / static_cast<unsigned>(d)) + 1u : 0u; }
-
-// Where the arguments are not preloaded (fd_finalize): the plan and the pointers after it span two
-// 128-byte lines of device memory that no cache holds when a workgroup starts.  Naming one value of
-// each line at the top of the kernel makes the compiler fetch both at once, before the first test
-// that could end the workgroup, instead of paying one memory round trip after the other; naming what
-// the address arithmetic in front of the first loads needs keeps those fetches in the same batch.
-#define KVC_FETCH_ARGS(first, last, a, b, c, d, e, f) \
-    asm volatile("" ::"s"(first), "s"(last), "s"(a), "s"(b), "s"(c), "s"(d), "s"(e), "s"(f))
-
-// Makes the compiler fetch the named arguments (those that are not preloaded) here, in one batch:
-// placed behind the first vector loads, their round trip to device memory hides behind those loads
-// instead of standing in front of the first use of each.
-template <class T> __device__ __forceinline__ void fetch_one(T v) { asm volatile("" ::"s"(v)); }
-template <class... T> __device__ __forceinline__ void fetch_now(T... v) { (fetch_one(v), ...); }
-
-__host__ __device__ inline u32x4 u32x4_mk(unsigned a, unsigned b, unsigned c, unsigned d) { return u32x4{a, b, c, d}; }
-__host__ __device__ inline u32x2 u32x2_mk(unsigned a, unsigned b) { return u32x2{a, b}; }
-__host__ __device__ inline f32x4 f32x4_mk(float a, float b, float c, float d) { return f32x4{a, b, c, d}; }
-__host__ __device__ inline f32x2 f32x2_mk(float a, float b) { return f32x2{a, b}; }
-__device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
-__device__ inline float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ inline float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-// element (channel c, row x) of the transposed text-value tile; the 16-byte chunks of a channel
-// row are XOR-swizzled with the index of the channel's 16-row MFMA tile: the transposing stores
-// spread over the banks and the operand reads of one tile stay conflict-free
-__device__ inline int vt_index(int c, int x) { return c * kLDV + ((((x >> 3) ^ (c >> 4)) & (kXC / 8 - 1)) << 3) + (x & 7); }
-
-// first query row of image block ub (b*I + i) of a KV head
-__host__ __device__ inline int unit_row(int ub, int UPBs, int G) { return ((ub >> UPBs) << 6) + (ub & ((1 << UPBs) - 1)) * G; }
-// rows of a 64-row block beyond its image blocks, and rows beyond the last image block, hold nothing
-__device__ inline bool row_valid(const Plan &p, int r) { return (r & 63) < p.RV && r < p.R; }
-
-// ------------------------------------------------------------------------------------------
-// text_part: the complete attention part of kXC rows of the text cache of one (batch, KV head),
-// by four waves; `id` numbers the chunks, `lds` holds kTextLds bytes.  Runs as extra workgroups of
-// fc_fused (its longest launch, bound by the L2s, with CUs and HBM bandwidth to spare), or of
-// fa_scores when there are no vision tokens.
-// Part record in Ypart: [G][D] floats of un-normalised output, [G] maxima, [G] sums.
-// ------------------------------------------------------------------------------------------
-constexpr size_t kTextLds = (16 * kSWLD + D * kLDV) * sizeof(uint16_t) + 2 * 4 * 16 * sizeof(float);
-
-template <int G>
-__device__ __forceinline__ void text_part(const Plan &p, const uint16_t *__restrict__ q, uint16_t *__restrict__ Kt,
-                                          uint16_t *__restrict__ Vt, const uint16_t *__restrict__ k_new,
-                                          const uint16_t *__restrict__ v_new, uint16_t *lds, const int id)
-{
-    fetch_now(p.qNXC, p.NXC, p.qHkv, p.Hkv, p.Hq, p.t, p.t_in, p.cap, q, Kt, Vt, k_new, v_new, p.scale, p.Ypart, p.nparts,
-              p.nvp, p.rec);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int r16 = lane & 15, kg = lane >> 4;
-    // ---------------- text rows: one chunk of kXC rows of one (batch, KV head) ----------------
-    uint16_t (*sWb)[kSWLD] = reinterpret_cast<uint16_t (*)[kSWLD]>(lds);               // probabilities [head][row], bf16
-    uint16_t *sVt = lds + 16 * kSWLD;                                                  // V^T [channel][row]
-    float (*sRed)[4][16] = reinterpret_cast<float (*)[4][16]>(lds + 16 * kSWLD + D * kLDV);   // per-wave maxima / sums per head
-    const int bh = quot(id, p.qNXC), xc = id - bh * p.NXC;
-    const int b = quot(bh, p.qHkv), h = bh - b * p.Hkv;
-    const int lo = xc * kXC, hi = min(p.t, lo + kXC);
-    const bool fresh = k_new != nullptr;                       // row t_in comes from k_new / v_new
-    // value rows of the chunk (16 lanes per row, a lane takes pairs of consecutive rows) and key
-    // rows of this wave's two 16-row tiles
-    const int rowl = wave * 4 + kg, cs = r16;
-    u32x4 vb[kXC / 32][2], kf[2][4], qf[4];
-#pragma unroll
-    for (int it = 0; it < kXC / 32; ++it)
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int x = min(lo + 2 * (rowl + 16 * it) + e, hi - 1);
-            const uint16_t *vrow = (fresh && x == p.t_in) ? v_new + static_cast<size_t>(bh) * D
-                                                          : Vt + (static_cast<size_t>(bh) * p.cap + x) * D;
-            vb[it][e] = *(reinterpret_cast<const u32x4 *>(vrow) + cs);
-        }
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-        const int x = min(lo + 32 * wave + 16 * tt + r16, hi - 1);
-        const uint16_t *krow = (fresh && x == p.t_in) ? k_new + static_cast<size_t>(bh) * D
-                                                      : Kt + (static_cast<size_t>(bh) * p.cap + x) * D;
-        const u32x4 *kp = reinterpret_cast<const u32x4 *>(krow) + kg;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) kf[tt][ks] = kp[4 * ks];
-    }
-    {
-        const u32x4 *qp = reinterpret_cast<const u32x4 *>(q + (static_cast<size_t>(b) * p.Hq + h * G + min(r16, G - 1)) * D) + kg;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) qf[ks] = qp[4 * ks];
-    }
-    TS(0, 1);
-    // logits: lane (head r16, rows 32 wave + 16 tt + 4 kg + e) keeps 8 of them
-    f32x4 sc[2];
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[tt][ks]), as_bf16x8(qf[ks]), acc, 0, 0, 0);
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            sc[tt][e] = (lo + 32 * wave + 16 * tt + 4 * kg + e < hi) ? acc[e] * p.scale : -INFINITY;
-    }
-    float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
-                     fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    if (kg == 0) sRed[0][wave][r16] = mx;
-    // value rows -> LDS transposed: rows (x, x+1) of channel c share one 32-bit word
-#pragma unroll
-    for (int it = 0; it < kXC / 32; ++it) {
-        const int xl2 = 2 * (rowl + 16 * it);
-        const uint32_t a[4] = {vb[it][0].x, vb[it][0].y, vb[it][0].z, vb[it][0].w};
-        const uint32_t c2[4] = {vb[it][1].x, vb[it][1].y, vb[it][1].z, vb[it][1].w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            *reinterpret_cast<uint32_t *>(sVt + vt_index(8 * cs + 2 * e, xl2)) = (a[e] & 0xffffu) | (c2[e] << 16);
-            *reinterpret_cast<uint32_t *>(sVt + vt_index(8 * cs + 2 * e + 1, xl2)) = (a[e] >> 16) | (c2[e] & 0xffff0000u);
-        }
-    }
-    __syncthreads();
-    TS(0, 2);
-    // probabilities relative to the chunk's own maximum, straight from the accumulator layout
-    mx = fmaxf(fmaxf(sRed[0][0][r16], sRed[0][1][r16]), fmaxf(sRed[0][2][r16], sRed[0][3][r16]));
-    float sm = 0.f;
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-        uint32_t eb[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            eb[e] = f32_to_bf16_bits(__expf(sc[tt][e] - mx));       // exp(-inf) = 0 beyond the chunk
-            sm += __uint_as_float(eb[e] << 16);
-        }
-        *reinterpret_cast<u32x2 *>(&sWb[r16][32 * wave + 16 * tt + 4 * kg]) = u32x2_mk(eb[0] | (eb[1] << 16), eb[2] | (eb[3] << 16));
-    }
-    sm += __shfl_xor(sm, 16, 64);
-    sm += __shfl_xor(sm, 32, 64);
-    if (kg == 0) sRed[1][wave][r16] = sm;
-    __syncthreads();
-    TS(0, 3);
-    // out_part^T[c][g] = sum_x V^T[c][x] P[g][x]; each wave owns two 16-channel tiles
-    float *yp = p.Ypart + (static_cast<size_t>(bh) * p.nparts + p.nvp + xc) * p.rec;
-#pragma unroll
-    for (int ct2 = 0; ct2 < 2; ++ct2) {
-        const int ct = 2 * wave + ct2;
-        f32x4 o = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < kXC / 32; ++ks) {
-            const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(sVt + vt_index(16 * ct + r16, 32 * ks + 8 * kg));
-            const bf16x8 bfrag = *reinterpret_cast<const bf16x8 *>(&sWb[r16][32 * ks + 8 * kg]);
-            o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, o, 0, 0, 0);
-        }
-        if (r16 < G) *reinterpret_cast<f32x4 *>(yp + r16 * D + 16 * ct + 4 * kg) = o;
-    }
-    if (threadIdx.x < G) {
-        yp[G * D + threadIdx.x] = mx;            // lanes 0..15 of wave 0 hold the maximum of head r16
-        yp[G * D + G + threadIdx.x] = sRed[1][0][threadIdx.x] + sRed[1][1][threadIdx.x] +
-                                      sRed[1][2][threadIdx.x] + sRed[1][3][threadIdx.x];
-    }
-    // Sec. 3.2: the text cache keeps growing as in the backbone -- store the new token's k, v
-    if (fresh && p.t_in >= lo && p.t_in < hi && threadIdx.x < 32) {
-        const int half = threadIdx.x >> 4, piece = threadIdx.x & 15;
-        const uint16_t *src = (half ? v_new : k_new) + static_cast<size_t>(bh) * D;
-        uint16_t *dst = (half ? Vt : Kt) + (static_cast<size_t>(bh) * p.cap + p.t_in) * D;
-        *(reinterpret_cast<u32x4 *>(dst) + piece) = *(reinterpret_cast<const u32x4 *>(src) + piece);
-    }
-    TS(0, 4);
-}
+using namespace dd;
 
 // ------------------------------------------------------------------------------------------
 // fa_scores: Alg. 1 step 1 on the compressed keys (vision workgroups), and the complete
@@ -318,7 +87,7 @@ __global__ __launch_bounds__(256) void fa_scores(const uint16_t *__restrict__ q,
     if constexpr (TEXT) {
         if (static_cast<int>(blockIdx.x) < p.ntext_a) {
             __shared__ __align__(16) uint16_t sText[kTextLds / 2];
-            text_part<G>(p, q, Kt, Vt, k_new, v_new, sText, blockIdx.x);
+            text_part<G>(p, q, Kt, Vt, k_new, v_new, sText, blockIdx.x, threadIdx.x, true);
             return;
         }
     }
@@ -841,7 +610,7 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
     // The text chunks ride along as the last workgroups (four waves each): they land on the CUs the
     // others leave idle first, and end before the longest of the others does.
     if (static_cast<int>(blockIdx.x) >= p.nvis_c) {
-        if (threadIdx.x < 256) text_part<G>(p, q, Kt, Vt, k_new, v_new, dyn, blockIdx.x - p.nvis_c);
+        if (threadIdx.x < 256) text_part<G>(p, q, Kt, Vt, k_new, v_new, dyn, blockIdx.x - p.nvis_c, threadIdx.x, true);
         return;
     }
     TS(2, 0);
