@@ -20,27 +20,27 @@
  *    occupancy; every later call consists of kernel launches only.  No call
  *    allocates, copies, sets memory or synchronises, so every call, the first
  *    included, may be captured into a HIP graph.
- *  - Besides the workspace the decode call uses a few counters in device memory
- *    that the library itself owns (1 MB per GPU, zero when the library is loaded
- *    and after every call), one set per stream for the first 16 streams that
- *    call it; further streams are served without them, a little slower.  A call
- *    captured into a graph keeps the counters of the stream it was captured on:
- *    its replays must not overlap each other, nor calls made on that stream.
+ *  - The library keeps no state between calls: what a call needs beyond its arguments lives in the
+ *    workspace (its first 64 KB hold arrival counters of the decode kernels; their contents need not be
+ *    initialised and may be overwritten between calls).  Calls that share a workspace must not overlap:
+ *    order them on one stream -- this includes replays of captured calls.  Calls with workspaces of their
+ *    own may run concurrently on any number of streams.
  *  - Tensors are dense row-major with head_dim fastest unless strides are
  *    passed.  Every pointer must be 16-byte aligned.
- *  - The return value is a kvc_status; a negative value means nothing was
- *    launched.  No exception crosses the boundary.
+ *  - The return value is a kvc_status.  Argument errors (every negative status but KVC_ERR_HIP) are
+ *    found before anything touches the device: nothing was launched.  KVC_ERR_HIP reports a failed
+ *    launch; kernels of the same call that were launched before it still run, and the outputs are then
+ *    undefined.  No exception crosses the boundary.
  *  - Notation follows the paper: B batch, H_q query heads, H_kv KV heads,
  *    G = H_q / H_kv (query head g reads KV head g / G), d = head_dim, n vision
  *    tokens per image block, I image blocks (the vision span is I*n contiguous
  *    tokens; the same per-layer parameters serve every block and every batch
  *    element), m = ceil((1 - c) n) compressed length for compression ratio c,
  *    t text tokens in the cache.
- *  - Every valid shape is served.  The matrix-core (MFMA) kernels cover bf16 with
- *    d = 128: compression for n a multiple of 64; decode for n in {256, 576, 1024},
- *    G in {1, 2, 4, 6, 7, 8} and at most 256 partial results per (batch element, KV head).
- *    Other shapes, and fp32, run shape-agnostic scalar kernels: same results within
- *    rounding, far lower speed.
+ *  - The matrix-core (MFMA) kernels cover bf16 with d = 128: compression for n a multiple of 64;
+ *    decode for n in {256, 576, 1024}, G in {1, 2, 4, 6, 7, 8} and at most 256 partial results per
+ *    (batch element, KV head).  Other shapes, and fp32, run shape-agnostic scalar kernels: same results
+ *    within rounding, far lower speed; their decode is limited to n <= 16384 (KVC_ERR_UNSUPPORTED beyond).
  */
 #ifndef KVCAPSULE_H
 #define KVCAPSULE_H
@@ -113,21 +113,22 @@ kvc_status kvc_memory_footprint(const kvc_shape *shape, int64_t c_prompt, int64_
  *     Kc[b,h,i,j,:] = K[b,h, vis_start + i n + M[j], :]            (bit-exact copy)
  *     Vc[b,h,i,j,:] = sum_p U[h,j,p] (V[b,h, vis_start + i n + p, :] - mu[h,:])
  * with fp32 accumulation and one round-to-nearest-even to the storage type.
- *  K, V  in : [B][H_kv][S][d] with element strides stride_b / stride_h / stride_s
- *             (d contiguous; strides multiples of 8 elements); rows outside the
+ *  K, V  in : [B][H_kv][S][d], S = seq_len, with element strides stride_b / stride_h /
+ *             stride_s (d contiguous; strides multiples of 8 elements); rows outside the
  *             span [vis_start, vis_start + I n) are not touched -- text K/V stays
- *             where the backbone keeps it.
+ *             where the backbone keeps it.  The span must lie inside the S rows.
  *  Kc out  : [B][H_kv][I][m][d] dense.
  *  Vc out  : [B][H_kv][I] records of m*d elements (no padding).  Inside a record the m rows
  *            are grouped in blocks of 8 and a block is stored channel-major, [d][w] with
  *            w = 8 (w = m % 8 for a shorter last block): element (row j, channel c) sits at
  *            (j/8)*8*d + c*w + j%8.  Eight consecutive rows of one channel are then 16
  *            contiguous bytes, which is the matrix-core operand of the decode kernel.
- * Errors: NULL pointers, bad shape/dtype, vis_start < 0, misalignment. */
+ * Errors: NULL pointers, bad shape/dtype, vis_start < 0, vis_start + I n > seq_len,
+ * misalignment. */
 kvc_status kvc_compress(const kvc_shape *shape, const kvc_params *params,
                         const void *K, const void *V,
                         int64_t stride_b, int64_t stride_h, int64_t stride_s,
-                        int32_t vis_start,
+                        int32_t vis_start, int32_t seq_len,
                         void *Kc, void *Vc,
                         void *workspace, size_t workspace_bytes, void *stream);
 
@@ -159,6 +160,17 @@ kvc_status kvc_reconstruct_attend_decode(const kvc_shape *shape, const kvc_param
                                          float softmax_scale,
                                          void *out, float *lse_out,
                                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* The blocked layout of the compressed values (see kvc_compress), for code that has to read or build a
+ * capsule: offset, in elements from the start of an image block's record of m*d elements, of (row j,
+ * channel c).  Host arithmetic only; returns -1 if an argument is out of range. */
+int64_t kvc_capsule_value_offset(int32_t j, int32_t c, int32_t m, int32_t d);
+
+/* Compressed values of `records` image blocks (B*H_kv*I of them, as kvc_compress wrote them) -> dense
+ * row-major [records][m][d], same element type.  Index shuffling only; asynchronous on `stream`.
+ * Errors: NULL pointers, bad sizes, unknown dtype, misalignment. */
+kvc_status kvc_unpack_values(const void *Vc, void *dense, int64_t records, int32_t m, int32_t d,
+                             int32_t dtype, void *stream);
 
 /* For callers that cannot allocate or hand over device memory at call time (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): kvc_reconstruct_attend_decode

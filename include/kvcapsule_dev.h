@@ -33,7 +33,7 @@ kvc_status kvc_reconstruct_attend_decode_generic(const kvc_shape *shape, const k
 kvc_status kvc_compress_generic(const kvc_shape *shape, const kvc_params *params,
                                 const void *K, const void *V,
                                 int64_t stride_b, int64_t stride_h, int64_t stride_s,
-                                int32_t vis_start,
+                                int32_t vis_start, int32_t seq_len,
                                 void *Kc, void *Vc,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
@@ -48,6 +48,22 @@ kvc_status kvc_probe_read(const void *buf, size_t bytes, void *sink, void *strea
 /* Full-cache decode: steps of 128 cache rows per split (0 restores the built-in rule).  Process-wide,
  * not thread-safe; for sweeps only. */
 void kvc_dev_full_decode_chunk_steps(int32_t steps);
+
+/* Knobs of the matrix-core decode kernels, for tests and sweeps; a negative value leaves a knob as it is.
+ * Process-wide, not thread-safe.
+ *  row_tiles : 16-row tiles of query rows per workgroup of the third kernel (1, 2, or 4 -- 4 only for
+ *              n = 256); 0 restores the built-in rule.
+ *  separate  : 1 runs the first two kernels (compressed scores; probabilities) as separate launches even
+ *              where they could run as one; 0 restores the rule (one launch when all its workgroups can
+ *              be resident at once).
+ *  wait_ticks: in the one-launch form, how long a workgroup waits for the other workgroups of its group
+ *              to deliver their compressed scores before it computes them itself, in units of 10 ns
+ *              (default 2000 = 20 us; 0: it never waits, which tests use to run that path). */
+void kvc_dev_decode_knobs(int32_t row_tiles, int32_t separate, int32_t wait_ticks);
+
+/* Workgroups that gave up waiting and computed alone since the library was loaded (current device;
+ * synchronises with the device), or -1. */
+int64_t kvc_dev_decode_fallbacks(void);
 
 #ifdef __cplusplus
 }

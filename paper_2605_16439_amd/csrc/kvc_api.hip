@@ -94,7 +94,7 @@ kvc_status prepare_decode(DecodeCall &c, const kvc_shape *shape, const kvc_param
 
 kvc_status prepare_compress(CompressCall &c, const kvc_shape *shape, const kvc_params *params,
                             const void *K, const void *V, int64_t stride_b, int64_t stride_h,
-                            int64_t stride_s, int32_t vis_start, void *Kc, void *Vc,
+                            int64_t stride_s, int32_t vis_start, int32_t seq_len, void *Kc, void *Vc,
                             void *workspace, size_t workspace_bytes, void *stream)
 {
     kvc_status st = check_shape(shape);
@@ -102,7 +102,10 @@ kvc_status prepare_compress(CompressCall &c, const kvc_shape *shape, const kvc_p
     st = check_params(params, true, false);
     if (st != KVC_OK) return st;
     if (shape->n_images > 0 && (!K || !V || !Kc || !Vc)) return KVC_ERR_NULL;
-    if (vis_start < 0) return KVC_ERR_SHAPE;
+    if (vis_start < 0 || seq_len < 0) return KVC_ERR_SHAPE;
+    // the vision span lies inside the sequence
+    if (static_cast<int64_t>(vis_start) + static_cast<int64_t>(shape->n_images) * shape->n_img_tokens > seq_len)
+        return KVC_ERR_SHAPE;
     if (stride_s < shape->head_dim || stride_h < 0 || stride_b < 0) return KVC_ERR_SHAPE;
     if (stride_s % 8 || stride_h % 8 || stride_b % 8) return KVC_ERR_ALIGN;
     if (!aligned16(K) || !aligned16(V) || !aligned16(Kc) || !aligned16(Vc)) return KVC_ERR_ALIGN;
@@ -130,6 +133,17 @@ kvc_status dispatch_decode(const DecodeCall &c)
 {
     if (fast_decode_supported(c.s)) return fast_decode(c);
     return generic_decode(c);
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void unpack_values(const T *__restrict__ Vc, T *__restrict__ dense, int m, int d)
+{
+    const T *src = Vc + static_cast<size_t>(blockIdx.x) * m * d;
+    T *dst = dense + static_cast<size_t>(blockIdx.x) * m * d;
+    for (int x = threadIdx.x; x < m * d; x += 256) {
+        const int j = x / d, c = x - j * d;
+        dst[x] = src[vc_offset(j, c, m, d)];
+    }
 }
 
 }  // namespace
@@ -181,12 +195,12 @@ kvc_status kvc_memory_footprint(const kvc_shape *shape, int64_t c_prompt, int64_
 
 kvc_status kvc_compress(const kvc_shape *shape, const kvc_params *params, const void *K,
                         const void *V, int64_t stride_b, int64_t stride_h, int64_t stride_s,
-                        int32_t vis_start, void *Kc, void *Vc, void *workspace,
+                        int32_t vis_start, int32_t seq_len, void *Kc, void *Vc, void *workspace,
                         size_t workspace_bytes, void *stream)
 {
     CompressCall c;
     kvc_status st = prepare_compress(c, shape, params, K, V, stride_b, stride_h, stride_s,
-                                     vis_start, Kc, Vc, workspace, workspace_bytes, stream);
+                                     vis_start, seq_len, Kc, Vc, workspace, workspace_bytes, stream);
     if (st != KVC_OK) return st;
     if (fast_compress_supported(c.s)) return fast_compress(c);
     return generic_compress(c);
@@ -194,12 +208,12 @@ kvc_status kvc_compress(const kvc_shape *shape, const kvc_params *params, const 
 
 kvc_status kvc_compress_generic(const kvc_shape *shape, const kvc_params *params, const void *K,
                                 const void *V, int64_t stride_b, int64_t stride_h,
-                                int64_t stride_s, int32_t vis_start, void *Kc, void *Vc,
+                                int64_t stride_s, int32_t vis_start, int32_t seq_len, void *Kc, void *Vc,
                                 void *workspace, size_t workspace_bytes, void *stream)
 {
     CompressCall c;
     kvc_status st = prepare_compress(c, shape, params, K, V, stride_b, stride_h, stride_s,
-                                     vis_start, Kc, Vc, workspace, workspace_bytes, stream);
+                                     vis_start, seq_len, Kc, Vc, workspace, workspace_bytes, stream);
     if (st != KVC_OK) return st;
     return generic_compress(c);
 }
@@ -233,6 +247,29 @@ kvc_status kvc_reconstruct_attend_decode_generic(const kvc_shape *shape, const k
                                    workspace_bytes, stream);
     if (st != KVC_OK) return st;
     return generic_decode(c);
+}
+
+// ---- the blocked layout of the compressed values, for callers ---------------------------------------
+int64_t kvc_capsule_value_offset(int32_t j, int32_t c, int32_t m, int32_t d)
+{
+    if (m < 1 || d < 1 || j < 0 || j >= m || c < 0 || c >= d) return -1;
+    return static_cast<int64_t>(vc_offset(j, c, m, d));
+}
+
+kvc_status kvc_unpack_values(const void *Vc, void *dense, int64_t records, int32_t m, int32_t d, int32_t dtype,
+                             void *stream)
+{
+    if (!Vc || !dense) return KVC_ERR_NULL;
+    if (dtype != KVC_F32 && dtype != KVC_BF16) return KVC_ERR_DTYPE;
+    if (records < 0 || records > 0x7fffffff || m < 1 || d < 1) return KVC_ERR_SHAPE;
+    if (!aligned16(Vc) || !aligned16(dense)) return KVC_ERR_ALIGN;
+    if (records == 0) return KVC_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dtype == KVC_F32)
+        unpack_values<float><<<static_cast<unsigned>(records), 256, 0, st>>>(static_cast<const float *>(Vc), static_cast<float *>(dense), m, d);
+    else
+        unpack_values<uint16_t><<<static_cast<unsigned>(records), 256, 0, st>>>(static_cast<const uint16_t *>(Vc), static_cast<uint16_t *>(dense), m, d);
+    return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
 }
 
 // ---- decode without a workspace argument, for callers that cannot allocate ------------------------
@@ -361,6 +398,13 @@ kvc_status kvc_attend_full_decode(int32_t batch, int32_t n_q_heads, int32_t n_kv
 }
 
 void kvc_dev_full_decode_chunk_steps(int32_t steps) { full_decode_set_chunk_steps(steps); }
+
+void kvc_dev_decode_knobs(int32_t row_tiles, int32_t separate, int32_t wait_ticks)
+{
+    fast_decode_knobs(row_tiles, separate, wait_ticks);
+}
+
+int64_t kvc_dev_decode_fallbacks(void) { return fast_decode_fallbacks(); }
 
 
 

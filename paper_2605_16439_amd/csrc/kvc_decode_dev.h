@@ -28,9 +28,8 @@ constexpr int kSWLD = kXC + 8;  // padded row (bf16) of the text probabilities i
 constexpr int kLDV = kXC + 8;   // padded row (bf16) of the transposed text values in LDS
 constexpr int kWLD = kJC + 8;   // padded row (bf16) of the W tile in LDS
 constexpr size_t kLdsBudget = 150 * 1024;
-constexpr int kCtrStride = 32;  // an arrival counter per 128-byte line
-constexpr int kMaxFlags = 512;  // counters per set
-constexpr int kFlagSets = 16;   // one set per stream in use
+constexpr int kCtrStride = 16;  // 64-bit words per arrival counter: one counter per 128-byte line
+constexpr int kMaxFlags = 512;  // arrival counters at the start of the workspace
 constexpr int kDenseRows = 24;  // "image blocks per 64-row block" = 2^24: the dense layout of the query rows
 
 struct Plan {
@@ -39,7 +38,9 @@ struct Plan {
     int UPBs, RV;                   // log2 of the image blocks per 64-row block of query rows; valid rows of a full block
     int fab;                        // fa_scores and fb_probs run as one launch (fab_fused)
     int wait_ticks;                 // fab_fused: how long a workgroup waits for its siblings (10 ns units)
-    unsigned *flags;                // fab_fused: [Hkv NRB] arrival counters, one per 128-byte line, zero between calls
+    unsigned epoch;                 // fab_fused: this call's number; counter words of another epoch count as zero
+    unsigned long long *flags;      // fab_fused: [Hkv NRB] arrival counters (epoch, count) at the start of the workspace
+    unsigned *fallbacks;            // fab_fused: debug counter of workgroups that computed alone (may be null)
     int tiles_per_unit, vis_tiles, nvis_a, ntext_a;   // fa_scores: vision workgroups, text workgroups (these come first)
     int ntext_c;                    // fc_fused: text workgroups (the highest ids)
     int UP, NT, NG, JS, NXC, nparts, rec;
@@ -71,6 +72,32 @@ constexpr size_t kTimelineBytes = 1 << 20;
 #define TS(KID, K) do { } while (0)
 constexpr size_t kTimelineBytes = 0;
 #endif
+
+// ---- arrival counters in the caller's workspace ------------------------------------------------------
+// A counter word carries (epoch, count), the epoch in the upper half.  The epoch is a number the host draws
+// per call from a counter that only grows, and a finished call leaves zeros behind.  Before a workgroup adds
+// to a word it raises it to (epoch, 0) with an atomic maximum: a word left by an earlier call (zero, or an
+// older epoch after a failed call) becomes (epoch, 0); a word that already carries this epoch keeps its
+// count -- in whatever order the workgroups get there.  Only "all arrived" under the call's own epoch ends a
+// wait.  Memory that holds something else (a fresh allocation, another kernel's data) usually reads as a
+// LARGER epoch: the maximum leaves it alone, nobody ever sees this call's epoch, every workgroup gives up
+// waiting after wait_ticks and computes alone (correct, slower), and the call's last kernel writes zeros,
+// so the next call is at full speed.
+typedef unsigned long long u64;
+__device__ inline u64 ctr_word(unsigned epoch, unsigned count) { return (static_cast<u64>(epoch) << 32) | count; }
+// the word as the L2 holds it: an atomic add of zero is carried out there (a plain load may be answered
+// by the CU's L1); waits for the answer
+__device__ inline u64 ctr_peek(u64 *w)
+{
+    u64 seen;
+    asm volatile("global_atomic_add_x2 %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)" : "=&v"(seen) : "v"(w), "v"(static_cast<u64>(0)) : "memory");
+    return seen;
+}
+// nothing is waited for: the caller's next "all my stores are done" point covers it
+__device__ inline void ctr_claim(u64 *w, unsigned epoch)
+{
+    __hip_atomic_fetch_max(w, ctr_word(epoch, 0u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
 
 // x / d for 0 <= x with x d < 2^32, as one multiplication by q = floor(2^32 / d) + 1 (q = 0 stands
 // for d = 1).  The index arithmetic at the top of every kernel sits in front of its first load; a

@@ -52,13 +52,19 @@
 #include "kvc_decode_dev.h"
 
 #include <algorithm>
-#include <cstdlib>
+#include <atomic>
 #include <mutex>
 
 namespace kvc {
 namespace {
 
 using namespace dd;
+
+// developer knobs (kvc_dev_decode_knobs) and the call counter that numbers fab_fused's epochs
+std::atomic<unsigned> g_epoch{0};
+int g_wait_ticks = 2000;          // 20 us: a few launch latencies; a workgroup that waits longer computes alone
+int g_force_nt = 0;               // row tiles per fc_fused workgroup (0: rule in make_plan_layout)
+int g_separate = 0;               // 1: fa_scores and fb_probs as separate launches
 
 // ------------------------------------------------------------------------------------------
 // fa_scores: Alg. 1 step 1 on the compressed keys (vision workgroups), and the complete
@@ -312,12 +318,14 @@ __global__ __launch_bounds__(64 * NW) void fb_probs(const uint16_t *__restrict__
 //    issuing XCD's L2, so a counter can reach NC only through workgroups that share that L2 -- and
 //    then their data is there too.
 //  * A workgroup that does not see NC arrivals within p.wait_ticks (siblings not resident, or on
-//    another XCD) computes all of the pair's rows of S itself and reads those: slower, same result.
-//  * The counters live in memory the library owns (zero when loaded, one set per stream in use); the
-//    finalize kernel of the same call puts them back to zero.
+//    another XCD) computes all of the pair's rows of S itself and reads those: slower, same result
+//    (a debug counter records it).
+//  * The counters live at the start of the caller's workspace as (epoch, count) words (see ctr_claim):
+//    nothing has to be initialised, nothing is shared between calls that use different workspaces, and
+//    the finalize kernel of the same call puts them back to zero.
 // ------------------------------------------------------------------------------------------
 template <int KS4, int G>
-__global__ __launch_bounds__(256) void fab_fused(const uint16_t *__restrict__ Kc, unsigned a_qNC, int a_NC, unsigned a_qHkv,
+__global__ __launch_bounds__(256) void fab_fused(const uint16_t *__restrict__ Kc, u64 *a_flags, unsigned a_qNC, int a_NC, unsigned a_qHkv,
                                                  int a_Hkv, int a_nkeys, int a_TPU, unsigned a_qTPU, int a_UPBs, int a_I,
                                                  unsigned a_qI, int a_m, int a_units, Plan p,
                                                  const uint16_t *__restrict__ theta, const uint16_t *__restrict__ q)
@@ -338,6 +346,7 @@ __global__ __launch_bounds__(256) void fab_fused(const uint16_t *__restrict__ Kc
     const int pc = w8 - w8q * p.NC, key = w8q * 8 + (blockIdx.x & 7);
     if (key >= a_nkeys) return;
     const int rb = quot(key, p.qHkv), h = key - rb * p.Hkv;
+    u64 *flag = a_flags + static_cast<size_t>(key) * kCtrStride;
 
     // ---- phase 1: this workgroup's share of S = sigma q Kc^T for the pair's image blocks ---------------
     // tiles of 16 key rows are numbered (image block of the row block, tile of the block); wave w takes
@@ -412,7 +421,10 @@ __global__ __launch_bounds__(256) void fab_fused(const uint16_t *__restrict__ Kc
                 const int j = j0 + RPP * k + e;
                 tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(min(j, p.m - 1)) * p.n);
             }
-        fetch_now(p.m16, p.P, p.stats, p.S, p.scale, p.R_pad, p.R, p.RV, p.flags);
+        fetch_now(p.m16, p.P, p.stats, p.S, p.scale, p.R_pad, p.R, p.RV, p.epoch, p.wait_ticks, p.fallbacks);
+        // thread 0 raises the pair's counter word to this call's epoch (behind the loads above, so that it does
+        // not stand in front of them; measured: 0.3 us per call better here than next to the wait below)
+        if (threadIdx.x == 0) ctr_claim(flag, p.epoch);
         // S tiles of this wave
 #pragma unroll
         for (int tq = 0; tq < TQ; ++tq) {
@@ -444,25 +456,26 @@ __global__ __launch_bounds__(256) void fab_fused(const uint16_t *__restrict__ Kc
             ThT[pp * LDT + j] = 0;
         }
     }
-    // every wave's stores of S have been acknowledged by the L2 before the counter moves
+    // every wave's stores of S (and thread 0's claim of the counter word) have been acknowledged by the L2
+    // before the counter moves
     __shared__ int sAlone;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
-        unsigned *flag = p.flags + static_cast<size_t>(key) * kCtrStride;
-        __hip_atomic_fetch_add(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        __hip_atomic_fetch_add(flag, static_cast<u64>(1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const u64 want = ctr_word(p.epoch, static_cast<unsigned>(a_NC));
         const unsigned long long t0 = wall_clock64();
-        unsigned seen;
-        bool all;
-        do {
-            for (int k = 0; k < 16; ++k) {                   // the clock is read once per 16 polls
-                asm volatile("global_atomic_add %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)"
-                             : "=&v"(seen) : "v"(flag), "v"(0u) : "memory");
-                all = seen >= static_cast<unsigned>(a_NC);
-                if (all) break;
-            }
-        } while (!all && wall_clock64() - t0 < static_cast<unsigned long long>(p.wait_ticks));
+        bool all = false;
+        if (p.wait_ticks > 0) {
+            do {
+                for (int k = 0; k < 8 && !all; ++k) {            // the clock is read once per 8 polls
+                    const u64 v = ctr_peek(flag);
+                    all = v >= want && static_cast<unsigned>(v >> 32) == p.epoch;
+                }
+            } while (!all && wall_clock64() - t0 < static_cast<unsigned long long>(p.wait_ticks));
+        }
         sAlone = all ? 0 : 1;
+        if (!all && p.fallbacks) atomicAdd(p.fallbacks, 1u);
     }
     __syncthreads();
     if (sAlone) {
@@ -907,7 +920,7 @@ __global__ __launch_bounds__(128) void fd_finalize(Plan p, const uint16_t *__res
 {
     // the arrival counters of fab_fused go back to zero
     if (p.fab && blockIdx.x == 0)
-        for (int i = threadIdx.x; i < p.Hkv * p.NRB; i += 128) p.flags[static_cast<size_t>(i) * kCtrStride] = 0u;
+        for (int i = threadIdx.x; i < p.Hkv * p.NRB; i += 128) p.flags[static_cast<size_t>(i) * kCtrStride] = 0ull;
     KVC_FETCH_ARGS(p.B, lse, p.Ypart, p.qHkv, p.qG, p.nparts, p.rec, mu);
     __shared__ float sSc[kMaxParts + 64];
     __shared__ float sRed[2][3];
@@ -991,7 +1004,7 @@ template <int PB>
 __global__ __launch_bounds__(128) void fd_finalize_few(const float *__restrict__ Ypart, const uint16_t *__restrict__ mu,
                                                        uint16_t *__restrict__ out, float *__restrict__ lse,
                                                        int a_Hkv, unsigned a_qHkv, int a_G, unsigned a_qG, int a_nparts,
-                                                       int a_rec, int a_Hq, int a_nvp, unsigned *a_flags, int a_nflags
+                                                       int a_rec, int a_Hq, int a_nvp, u64 *a_flags, int a_nflags
 #if defined(KVC_TIMELINE)
                                                        , unsigned long long *a_tl
 #endif
@@ -1045,7 +1058,7 @@ __global__ __launch_bounds__(128) void fd_finalize_few(const float *__restrict__
     if (c == 0 && lse) lse[bg] = mx + __logf(z);
     // the arrival counters of fab_fused go back to zero
     if (blockIdx.x == 0)
-        for (int i = threadIdx.x; i < a_nflags; i += 128) a_flags[static_cast<size_t>(i) * kCtrStride] = 0u;
+        for (int i = threadIdx.x; i < a_nflags; i += 128) a_flags[static_cast<size_t>(i) * kCtrStride] = 0ull;
     TS(3, 4);
 }
 
@@ -1104,10 +1117,8 @@ Plan make_plan_layout(const kvc_shape &s, int t, int t_in, int cap, float scale,
     if (p.NT == 2 && p.n == 4 * kPC && !padded &&
         static_cast<long>((p.B * p.I + 4 * p.UP - 1) / (4 * p.UP)) * p.Hkv * p.JS >= 512)
         p.NT = 4;
-    {   // developer switch: KVC_DECODE_NT=1|2|4 overrides the rule above
-        static const char *force = getenv("KVC_DECODE_NT");
-        if (force && p.UP && p.B * p.I > p.UP) p.NT = atoi(force) == 1 ? 1 : (atoi(force) == 4 && p.n == 4 * kPC && !padded) ? 4 : 2;
-    }
+    // developer knob (kvc_dev_decode_knobs): 1, 2 or 4 row tiles override the rule above
+    if (g_force_nt && p.UP && p.B * p.I > p.UP) p.NT = g_force_nt == 1 ? 1 : (g_force_nt == 4 && p.n == 4 * kPC && !padded) ? 4 : 2;
     p.NG = p.UP ? (p.B * p.I + p.NT * p.UP - 1) / (p.NT * p.UP) : 0;
     p.NXC = (t + kXC - 1) / kXC;
     // the text chunks are extra workgroups of fc_fused; without vision tokens, of fa_scores
@@ -1131,13 +1142,15 @@ Plan make_plan_layout(const kvc_shape &s, int t, int t_in, int cap, float scale,
         off += align_up(bytes, 256);
         return static_cast<char *>(base) + o;
     };
+    p.flags = reinterpret_cast<u64 *>(take(static_cast<size_t>(kMaxFlags) * kCtrStride * sizeof(u64)));   // always first
     p.S = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(p.Hkv) * p.R_pad * p.m_pad * 2));
     p.P = reinterpret_cast<uint16_t *>(take(static_cast<size_t>(p.Hkv) * p.R_pad * p.n * 2));
     p.stats = reinterpret_cast<f32x2 *>(take(static_cast<size_t>(p.Hkv) * p.R_pad * p.NC * 8));
     p.Ypart = reinterpret_cast<float *>(take(static_cast<size_t>(p.B) * p.Hkv * (p.I * p.JS + nxc_max) * p.rec * 4));
     p.fab = 0;
-    p.flags = nullptr;
     p.wait_ticks = 0;
+    p.epoch = 0;
+    p.fallbacks = nullptr;
     p.bytes = off;
 #if defined(KVC_TIMELINE)
     p.tl = nullptr;
@@ -1150,8 +1163,7 @@ Plan make_plan_layout(const kvc_shape &s, int t, int t_in, int cap, float scale,
 // workgroup's share of the score tiles is at most four per wave
 bool fab_shape(const Plan &p)
 {
-    static const bool off = getenv("KVC_DECODE_SEPARATE") != nullptr;          // developer switch
-    if (off || p.I <= 0 || p.UPBs == kDenseRows) return false;
+    if (g_separate || p.I <= 0 || p.UPBs == kDenseRows) return false;
     const int T = p.tiles_per_unit * std::min(1 << p.UPBs, p.B * p.I), TW = (T + p.NC - 1) / p.NC;
     // (whether the chip holds all nvis_b workgroups at once is asked of the kernel instance: fab_resident)
     return p.RBW == 4 && p.nvis_b > 0 && p.nvis_b <= 512 && TW <= 16 && p.ntext_a == 0 && p.Hkv * p.NRB <= kMaxFlags;
@@ -1206,37 +1218,23 @@ template <int KS4, int NW> bool launch_b2(const Plan &p, const DecodeCall &c)
     return true;
 }
 
-// ---- fab_fused: counters owned by the library ----------------------------------------------------
-// kFlagSets sets of kMaxFlags counters, one per 128-byte line, zero when the code object is loaded
-// and zero again after every call that used them.  A set belongs to one stream (calls on one stream
-// run one after the other); a call on a stream without a set, when all are taken, uses the separate
-// kernels.
-static __device__ __align__(256) unsigned g_fab_flags[kFlagSets * kMaxFlags * kCtrStride];
+// ---- fab_fused: developer knobs and the debug counter --------------------------------------------------
 
-unsigned *fab_flags_for(hipStream_t stream)
+static __device__ unsigned g_fab_fallbacks;          // workgroups that computed alone after a time-out
+
+unsigned *fallback_counter()
 {
     static std::mutex mu;
-    static unsigned *base[kMaxDevices] = {};
-    static hipStream_t owner[kMaxDevices][kFlagSets] = {};
-    static int used[kMaxDevices] = {};
+    static unsigned *ptr[kMaxDevices] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
     std::lock_guard<std::mutex> lock(mu);
-    if (!base[dev]) {
-        // the array's name is a host-side stand-in: its address on this device comes from the runtime
-        void *ptr = nullptr;
-        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_fab_flags)) != hipSuccess || !ptr) return nullptr;
-        base[dev] = static_cast<unsigned *>(ptr);
+    if (!ptr[dev]) {
+        void *q = nullptr;
+        if (hipGetSymbolAddress(&q, HIP_SYMBOL(g_fab_fallbacks)) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        ptr[dev] = static_cast<unsigned *>(q);
     }
-    int slot = -1;
-    for (int i = 0; i < used[dev]; ++i)
-        if (owner[dev][i] == stream) slot = i;
-    if (slot < 0) {
-        if (used[dev] == kFlagSets) return nullptr;
-        slot = used[dev]++;
-        owner[dev][slot] = stream;
-    }
-    return base[dev] + static_cast<size_t>(slot) * kMaxFlags * kCtrStride;
+    return ptr[dev];
 }
 
 // probe: no launch; true when all p.nvis_b workgroups of this instance can be resident at once (the
@@ -1259,7 +1257,7 @@ template <int KS4, int G> bool launch_ab3(const Plan &p, const DecodeCall &c, bo
         return p.nvis_b <= capacity[dev];
     }
     fab_fused<KS4, G><<<p.nvis_b, 256, lds_b(p.m_pad), c.stream>>>(
-        static_cast<const uint16_t *>(c.Kc), p.qNC, p.NC, p.qHkv, p.Hkv, p.NRB * p.Hkv, p.tiles_per_unit, p.qTPU, p.UPBs,
+        static_cast<const uint16_t *>(c.Kc), p.flags, p.qNC, p.NC, p.qHkv, p.Hkv, p.NRB * p.Hkv, p.tiles_per_unit, p.qTPU, p.UPBs,
         p.I, p.qI, p.m, p.B * p.I, p, static_cast<const uint16_t *>(c.theta), static_cast<const uint16_t *>(c.q));
     return true;
 }
@@ -1396,6 +1394,22 @@ kvc_status finalize_parts(const float *Ypart, int nparts, int nvp, int rec, int 
     return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
 }
 
+void fast_decode_knobs(int row_tiles, int separate, int wait_ticks)
+{
+    if (row_tiles >= 0) g_force_nt = row_tiles;
+    if (separate >= 0) g_separate = separate;
+    if (wait_ticks >= 0) g_wait_ticks = wait_ticks;
+}
+
+// synchronous read of the debug counter (tests)
+long fast_decode_fallbacks()
+{
+    unsigned *d = fallback_counter();
+    unsigned v = 0;
+    if (!d || hipMemcpy(&v, d, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) return -1;
+    return v;
+}
+
 bool fast_decode_supported(const kvc_shape &s)
 {
     if (s.dtype != KVC_BF16 || s.head_dim != D) return false;
@@ -1430,11 +1444,13 @@ kvc_status fast_decode(const DecodeCall &c)
                ? reinterpret_cast<unsigned long long *>(static_cast<char *>(c.ws) + ((c.ws_bytes - kTimelineBytes) & ~size_t(255)))
                : nullptr;
 #endif
-    if (fab_shape(p)) {
-        static const char *ticks = getenv("KVC_FAB_WAIT_TICKS");                   // developer switch (tests)
-        p.flags = fab_resident(p, c) ? fab_flags_for(c.stream) : nullptr;
-        p.fab = p.flags != nullptr;
-        p.wait_ticks = ticks ? atoi(ticks) : 20000;                                // 200 us
+    if (fab_shape(p) && fab_resident(p, c)) {
+        p.fab = 1;
+        unsigned e = ++g_epoch;
+        if (e == 0) e = ++g_epoch;             // zero is what a finished call leaves behind
+        p.epoch = e;
+        p.wait_ticks = g_wait_ticks;
+        p.fallbacks = fallback_counter();
     }
     if (p.fab) {
         if (!launch_ab(p, c)) return KVC_ERR_HIP;

@@ -128,6 +128,8 @@ kvc_status generic_compress(const CompressCall &c);
 bool fast_decode_supported(const kvc_shape &s);
 size_t fast_decode_ws_bytes(const kvc_shape &s, int32_t max_text);
 kvc_status fast_decode(const DecodeCall &c);
+void fast_decode_knobs(int row_tiles, int separate, int wait_ticks);
+long fast_decode_fallbacks();
 // merges nparts part records ([G][128] un-normalised outputs, [G] maxima, [G] sums; the first nvp
 // of them vision parts, whose probability mass multiplies mu) of every (batch element, query
 // head) into out / lse; nparts <= 64

@@ -32,6 +32,8 @@ EXPORTS = [
     "kvc_compress_generic", "kvc_probe_read", "kvc_status_string", "kvc_version",
     "kvc_static_scratch_bytes", "kvc_reconstruct_attend_decode_static",
     "kvc_attend_full_workspace_bytes", "kvc_attend_full_decode", "kvc_dev_full_decode_chunk_steps",
+    "kvc_dev_decode_knobs", "kvc_dev_decode_fallbacks",
+    "kvc_capsule_value_offset", "kvc_unpack_values",
 ]
 
 
@@ -73,7 +75,7 @@ def lib() -> ctypes.CDLL:
         L.kvc_memory_footprint.restype = i32
         L.kvc_memory_footprint.argtypes = [ctypes.POINTER(KvcShape), i64, i64,
                                            ctypes.POINTER(i64), ctypes.POINTER(i64)]
-        comp = [ctypes.POINTER(KvcShape), ctypes.POINTER(KvcParams), vp, vp, i64, i64, i64, i32,
+        comp = [ctypes.POINTER(KvcShape), ctypes.POINTER(KvcParams), vp, vp, i64, i64, i64, i32, i32,
                 vp, vp, vp, ctypes.c_size_t, vp]
         dec = [ctypes.POINTER(KvcShape), ctypes.POINTER(KvcParams), vp, vp, vp, vp, vp, i32, i32,
                vp, vp, ctypes.c_float, vp, vp, vp, ctypes.c_size_t, vp]
@@ -94,6 +96,14 @@ def lib() -> ctypes.CDLL:
                                              vp, vp, ctypes.c_float, vp, vp, vp, ctypes.c_size_t, vp]
         L.kvc_dev_full_decode_chunk_steps.restype = None
         L.kvc_dev_full_decode_chunk_steps.argtypes = [i32]
+        L.kvc_dev_decode_knobs.restype = None
+        L.kvc_dev_decode_knobs.argtypes = [i32, i32, i32]
+        L.kvc_dev_decode_fallbacks.restype = i64
+        L.kvc_dev_decode_fallbacks.argtypes = []
+        L.kvc_capsule_value_offset.restype = i64
+        L.kvc_capsule_value_offset.argtypes = [i32, i32, i32, i32]
+        L.kvc_unpack_values.restype = i32
+        L.kvc_unpack_values.argtypes = [vp, vp, i64, i32, i32, i32, vp]
         L.kvc_probe_read.restype = i32
         L.kvc_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         L.kvc_status_string.restype = ctypes.c_char_p
@@ -183,7 +193,7 @@ def kvc_compress(shape: KvcShape, params: KvcParams, K: torch.Tensor, V: torch.T
     wp, wb = _ws(workspace)
     fn = lib().kvc_compress_generic if generic else lib().kvc_compress
     st = fn(ctypes.byref(shape), ctypes.byref(params), _ptr(K), _ptr(V), K.stride(0), K.stride(1),
-            K.stride(2), int(vis_start), _ptr(Kc), _ptr(Vc), wp, wb, _stream(stream))
+            K.stride(2), int(vis_start), K.shape[2], _ptr(Kc), _ptr(Vc), wp, wb, _stream(stream))
     if check and st != KVC_OK:
         raise KvcError(st, "kvc_compress")
     return st
@@ -237,3 +247,16 @@ def kvc_reconstruct_attend_decode_static(shape: KvcShape, params: KvcParams, q, 
     if check and st != KVC_OK:
         raise KvcError(st, "kvc_reconstruct_attend_decode_static")
     return st
+
+
+def kvc_unpack_values(Vc: torch.Tensor, m: int, d: int, stream=None) -> torch.Tensor:
+    """Compressed values as kvc_compress stores them ([..., m*d] records) -> dense [..., m, d] (new tensor)."""
+    dense = torch.empty(Vc.shape[:-2] + (m, d), dtype=Vc.dtype, device=Vc.device)
+    records = Vc.numel() // (m * d)
+    if records == 0:
+        return dense
+    st = lib().kvc_unpack_values(_ptr(Vc), _ptr(dense), records, int(m), int(d), _dtype_code(Vc.dtype),
+                                 _stream(stream))
+    if st != KVC_OK:
+        raise KvcError(st, "kvc_unpack_values")
+    return dense

@@ -103,15 +103,17 @@ def test_compress_rejects_bad_arguments_before_any_launch():
     s, p = _valid()
 
     def comp(s=s, p=p, K=0x10000, V=0x20000, sb=2 * 100 * 64, sh=100 * 64, ss=64, vis=2,
-             Kc=0x30000, Vc=0x40000):
+             Kc=0x30000, Vc=0x40000, S=100):
         return kv.lib().kvc_compress(ctypes.byref(s) if s is not None else None,
                                      ctypes.byref(p) if p is not None else None, K, V, sb, sh, ss,
-                                     vis, Kc, Vc, None, 0, None)
+                                     vis, S, Kc, Vc, None, 0, None)
     assert comp(s=None) == kv.KVC_ERR_NULL
     assert comp(K=None) == kv.KVC_ERR_NULL
     assert comp(Vc=None) == kv.KVC_ERR_NULL
     assert comp(p=kv.KvcParams(None, 0x2000, 0x3000, 0x4000)) == kv.KVC_ERR_NULL   # no mask
     assert comp(vis=-1) == kv.KVC_ERR_SHAPE
+    assert comp(vis=5) == kv.KVC_ERR_SHAPE            # 5 + 2 * 48 rows do not fit a sequence of 100
+    assert comp(S=97) == kv.KVC_ERR_SHAPE
     assert comp(ss=32) == kv.KVC_ERR_SHAPE            # rows overlap
     assert comp(ss=68) == kv.KVC_ERR_ALIGN
     assert comp(K=0x10002) == kv.KVC_ERR_ALIGN
@@ -136,3 +138,22 @@ def test_probe_read_rejects_bad_arguments_before_touching_the_device():
     assert L.kvc_probe_read(ctypes.c_void_p(0x10008), 1024, fake, None) == kv.KVC_ERR_ALIGN
     assert L.kvc_probe_read(fake, 1000, fake, None) == kv.KVC_ERR_ALIGN
     assert L.kvc_probe_read(fake, 0, fake, None) == kv.KVC_OK
+
+
+def test_capsule_value_offset_is_the_documented_blocked_layout():
+    """Rows in blocks of 8, a block channel-major [d][w] with w = 8 (m % 8 for a shorter last block): the
+    offsets of all (j, c) are a permutation of 0 .. m*d - 1 and 8 consecutive rows of a channel are contiguous."""
+    L = kv.lib()
+    for m, d in ((1, 8), (8, 16), (13, 8), (410, 128)):
+        offs = [L.kvc_capsule_value_offset(j, c, m, d) for j in range(m) for c in range(d)]
+        assert sorted(offs) == list(range(m * d))
+        for j in range(0, m - 1):
+            if j % 8 != 7:
+                assert L.kvc_capsule_value_offset(j + 1, 3, m, d) == L.kvc_capsule_value_offset(j, 3, m, d) + 1
+        w = min(8, m)
+        assert L.kvc_capsule_value_offset(0, 1, m, d) == w
+    assert L.kvc_capsule_value_offset(5, 0, 5, 8) == -1 and L.kvc_capsule_value_offset(0, 8, 5, 8) == -1
+    fake = ctypes.c_void_p(0x10000)
+    assert L.kvc_unpack_values(None, fake, 1, 8, 8, kv.KVC_BF16, None) == kv.KVC_ERR_NULL
+    assert L.kvc_unpack_values(fake, fake, 1, 0, 8, kv.KVC_BF16, None) == kv.KVC_ERR_SHAPE
+    assert L.kvc_unpack_values(fake, fake, 1, 8, 8, 9, None) == kv.KVC_ERR_DTYPE

@@ -564,38 +564,92 @@ def test_first_decode_call_of_a_process_inside_a_capture():
     assert r.returncode == 0 and r.stdout.strip().endswith("OK"), r.stdout[-1000:] + r.stderr[-2000:]
 
 
-def test_fused_scores_and_probabilities_when_every_workgroup_computes_alone():
+def _subset_of_fast_path_cases():
+    """A few of the matrix-core cases above, run again under other settings of the library's knobs."""
+    for hq, hkv in [(4, 4), (8, 2), (14, 2)]:
+        test_fast_path_group_sizes(hq, hkv)
+    for m in (1, 29, 91, 256):
+        test_fast_path_compressed_lengths(m)
+    test_fast_path_many_text_chunks()
+    test_fast_path_merged_part_records(14, 2, 2, 8)
+    test_fast_path_merged_part_records(4, 4, 2, 32)
+
+
+@pytest.fixture
+def knobs():
+    yield kv.lib().kvc_dev_decode_knobs
+    kv.lib().kvc_dev_decode_knobs(0, 0, 2000)
+
+
+def test_fused_scores_and_probabilities_when_every_workgroup_computes_alone(knobs):
     """fab_fused hands the compressed scores from workgroup to workgroup through the L2; a workgroup
     whose siblings do not arrive in time computes all of its row block's scores itself.  With the
-    waiting time set to zero (a developer switch, read once per process, hence the child process)
-    every workgroup takes that path; the results must still meet the bar."""
-    import os
-    import subprocess
-    import sys
-    env = dict(os.environ, KVC_FAB_WAIT_TICKS="0")
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_gpu_parity.py", "-q", "-m", "gpu", "-x",
-                        "-k", "merged_part_records or group_sizes or compressed_lengths or many_text_chunks"],
-                       cwd=root, env=env, capture_output=True, text=True, timeout=600)
-    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
-    assert " passed" in r.stdout
+    waiting time set to zero every workgroup takes that path (the debug counter shows it); the results
+    must still meet the bar."""
+    before = int(kv.lib().kvc_dev_decode_fallbacks())
+    knobs(-1, -1, 0)
+    _subset_of_fast_path_cases()
+    assert int(kv.lib().kvc_dev_decode_fallbacks()) > before
 
 
-def test_separate_launches_with_four_row_tiles_per_workgroup():
-    """Small shapes normally run fab_fused and one or two row tiles per fc_fused workgroup.  Two developer
-    switches (read once per process, hence the child process) send them through the other kernels:
-    fa_scores and fb_probs as separate launches, and fc_fused with four row tiles per workgroup (the
-    instance that long videos use), with ragged groups of image blocks."""
-    import os
-    import subprocess
-    import sys
-    env = dict(os.environ, KVC_DECODE_SEPARATE="1", KVC_DECODE_NT="4")
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_gpu_parity.py", "-q", "-m", "gpu", "-x",
-                        "-k", "merged_part_records or group_sizes or compressed_lengths or many_text_chunks"],
-                       cwd=root, env=env, capture_output=True, text=True, timeout=600)
-    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
-    assert " passed" in r.stdout
+def test_separate_launches_with_four_row_tiles_per_workgroup(knobs):
+    """Small shapes normally run fab_fused and one or two row tiles per fc_fused workgroup.  Two knobs
+    send them through the other kernels: fa_scores and fb_probs as separate launches, and fc_fused with
+    four row tiles per workgroup (the instance that long videos use), with ragged groups of image blocks."""
+    knobs(4, 1, -1)
+    _subset_of_fast_path_cases()
+
+
+def test_no_workgroup_computes_alone_in_normal_runs_and_any_number_of_streams():
+    """The arrival counters live in the workspace, so there is no limit on the number of streams; on an
+    otherwise idle GPU every workgroup sees its siblings arrive (debug counter unchanged)."""
+    w = FAST.with_(name="fast_streams_many", index=57, n_images=8, batch=2)
+    L = Layer(w, 103)
+    L.compress()
+    q, kn, vn = (x.to(DEV) for x in synth.make_step_inputs(w, 0, 0))
+    ref, _ = L.decode(q, w.text_len, kn, vn)
+    before = int(kv.lib().kvc_dev_decode_fallbacks())
+    for _ in range(24):
+        s = torch.cuda.Stream()
+        L.out.zero_()
+        torch.cuda.synchronize()
+        kv.kvc_reconstruct_attend_decode(L.shape, L.params, q, L.gKc, L.gVc, L.gKt, L.gVt, w.text_len, w.text_cap,
+                                         kn, vn, 0.0, L.out, L.lse, L.ws, stream=s)
+        torch.cuda.synchronize()
+        assert np.array_equal(f64(L.out), ref)
+    assert int(kv.lib().kvc_dev_decode_fallbacks()) == before
+
+
+def test_garbage_in_the_workspace_costs_one_slow_call_not_a_wrong_one():
+    """The arrival counters at the start of the workspace are raised to the call's epoch by an atomic
+    maximum.  Zeros (what every call leaves behind) and older epochs give way; 0xFF bytes read as a larger
+    epoch, so in the first call after such a fill every workgroup gives up waiting and computes alone --
+    same bits -- and the call's last kernel clears the counters: the next call runs normally."""
+    w = FAST.with_(name="fast_garbage_ws", index=58, n_images=8, batch=2)
+    L = Layer(w, 103)
+    L.compress()
+    q, kn, vn = (x.to(DEV) for x in synth.make_step_inputs(w, 0, 0))
+    L.ws.zero_()
+    ref, lref = L.decode(q, w.text_len, kn, vn)
+    f0 = int(kv.lib().kvc_dev_decode_fallbacks())
+    for fill, slow in ((0xFF, True), (None, False), (0x00, False), (0x01, True), (None, False)):
+        if fill is not None:
+            L.ws.fill_(fill)
+        out, lse = L.decode(q, w.text_len, kn, vn)
+        assert np.array_equal(out, ref) and np.array_equal(lse, lref)
+        f1 = int(kv.lib().kvc_dev_decode_fallbacks())
+        assert (f1 > f0) == slow, (fill, f0, f1)
+        f0 = f1
+
+
+def test_unpack_values_agrees_with_the_offset_function():
+    w = FAST.with_(name="fast_unpack", index=59)
+    for m in (5, 16, 103):
+        L = Layer(w, m)
+        L.compress()
+        a = unpack_vc(L.gVc, m, w.head_dim)
+        b = unpack_vc(L.gVc.cpu(), m, w.head_dim)
+        assert np.array_equal(a, b)
 
 
 def test_decode_on_two_streams_at_once():
