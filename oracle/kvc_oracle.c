@@ -27,6 +27,11 @@
  *    "P mu" is (sum of vision probabilities) * mu.
  *  - mu is a fixed per-KV-head parameter at inference (Sec. 3.2).
  *
+ *  - the two-layer form of f_theta ("two-layer MLP", Sec. 3.1) acts along the sequence axis per KV head
+ *    with hidden width m and no bias: K_hat = W2^T act(W1^T K_tilde); the static variant of the
+ *    ablation appendix attends the compressed rows themselves (no theta, no U^T, no mu); a ragged batch
+ *    gives every sequence its own number of image blocks and text rows.
+ *
  * Parity pins: every function below is pinned by tests/test_oracle_pins.py
  * (closed forms, invariants, library SDPA, SVD/Eckart-Young, brute force).
  * Accuracy-type claims of the paper (cosine-similarity tables, benchmark
@@ -308,6 +313,111 @@ void kvc_oracle_fused_order(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32
             free(Scomp);
             free(W);
         }
+}
+
+/* ---- activation between the two layers of the key reconstructor ---- */
+#define ORACLE_ACT_IDENTITY 0
+#define ORACLE_ACT_RELU 1
+#define ORACLE_ACT_GELU 2
+static double act_fn(double x, int act)
+{
+    if (act == ORACLE_ACT_RELU) return x > 0.0 ? x : 0.0;
+    if (act == ORACLE_ACT_GELU) return 0.5 * x * (1.0 + erf(x / sqrt(2.0)));   /* exact (erf) form */
+    return x;
+}
+
+/*
+ * Two-layer form of the key reconstructor (Sec. 3.1, Keys: "a lightweight reconstruction network
+ * f_theta implemented as a two-layer MLP"), applied along the sequence axis, per KV head, no bias:
+ *     H[b,h,i,r,:]     = act( sum_j W1[h,j,r] K_tilde[b,h,i,j,:] )        first layer,  r < m
+ *     K_hat[b,h,i,p,:] = sum_r W2[h,r,p] H[b,h,i,r,:]                     second layer, p < n
+ * The first layer depends on the compressed keys only, not on the decode step, so H is what an
+ * implementation may keep in place of K_tilde (same size); the second layer is then the linear
+ * reconstruction with theta = W2.  This function is the first layer; its result is rounded to
+ * store_dtype (the form in which it would be kept).
+ * Kc: [B][H_kv][I][m][d];  W1: [H_kv][m][m] (row j, column r);  H out: [B][H_kv][I][m][d]
+ */
+void kvc_oracle_mlp_hidden(int32_t B, int32_t Hkv, int32_t d, int32_t I, int32_t m, const double *Kc,
+                           const double *W1, int act, int store_dtype, double *H)
+{
+    long units = (long)B * Hkv * I;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long u = 0; u < units; ++u) {
+        int h = (int)((u / I) % Hkv);
+        const double *Kt = Kc + u * (long)m * d;
+        const double *W = W1 + (long)h * m * m;
+        double *Ho = H + u * (long)m * d;
+        for (int r = 0; r < m; ++r)
+            for (int c = 0; c < d; ++c) {
+                double acc = 0.0;
+                for (int j = 0; j < m; ++j) acc += W[(long)j * m + r] * Kt[(long)j * d + c];
+                Ho[(long)r * d + c] = kvc_oracle_round_to(act_fn(acc, act), store_dtype);
+            }
+    }
+}
+
+/*
+ * Static variant of the ablation appendix ("static KVCapsule w/o reconstruction": the compressed KV is
+ * used directly throughout decoding): the I*m compressed rows of a (batch element, KV head) are the
+ * vision keys and values themselves,
+ *     out[b,g,:] = softmax(scale * q[b,g] . [K_tilde ; K_text]^T) [V_tilde ; V_text].
+ * Same append semantics as the decode step above.  Returns 0, or -1 if the append does not fit.
+ */
+int kvc_oracle_static_attend_decode(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t I, int32_t m,
+                                    const double *Kc, const double *Vc, double *Ktxt, double *Vtxt,
+                                    int32_t t, int32_t Tcap, const double *k_new, const double *v_new,
+                                    const double *q, double scale, double *out, double *lse)
+{
+    if (k_new && v_new) {
+        if (t + 1 > Tcap) return -1;
+        for (long bh = 0; bh < (long)B * Hkv; ++bh) {
+            memcpy(Ktxt + (bh * Tcap + t) * d, k_new + bh * d, sizeof(double) * d);
+            memcpy(Vtxt + (bh * Tcap + t) * d, v_new + bh * d, sizeof(double) * d);
+        }
+        t += 1;
+    }
+    /* [B][H_kv][I][m][d] is [B][H_kv][I*m][d] */
+    kvc_oracle_attend(B, Hq, Hkv, d, I * m, Kc, Vc, t, Tcap, Ktxt, Vtxt, q, scale, out, lse, 0);
+    return 0;
+}
+
+/*
+ * Ragged batch: sequence b has n_images[b] <= I image blocks (the first n_images[b] blocks of its I
+ * slots in the capsule) and text_len[b] valid text rows; with k_new/v_new its new token goes to row
+ * text_len[b].  Each sequence is the uniform decode step above on its own data.
+ * Returns 0, or -1 (allocation, an append that does not fit, a count out of range).
+ */
+int kvc_oracle_reconstruct_attend_decode_ragged(int32_t B, int32_t Hq, int32_t Hkv, int32_t d, int32_t n,
+                                                int32_t I, int32_t m, const int32_t *n_images,
+                                                const int32_t *text_len, const double *Kc,
+                                                const double *Vc, const double *theta, const double *U,
+                                                const double *mu, double *Ktxt, double *Vtxt, int32_t Tcap,
+                                                const double *k_new, const double *v_new, const double *q,
+                                                double scale, double *out, double *lse)
+{
+    size_t blk = (size_t)m * d;
+    double *Kb = (double *)malloc(sizeof(double) * ((size_t)Hkv * I * blk + 1));
+    double *Vb = (double *)malloc(sizeof(double) * ((size_t)Hkv * I * blk + 1));
+    if (!Kb || !Vb) { free(Kb); free(Vb); return -1; }
+    int rc = 0;
+    for (int b = 0; b < B && rc == 0; ++b) {
+        int Ib = n_images[b], tb = text_len[b];
+        if (Ib < 0 || Ib > I || tb < 0 || tb > Tcap) { rc = -1; break; }
+        /* the sequence's own capsule: [H_kv][Ib][m][d] */
+        for (int h = 0; h < Hkv; ++h)
+            for (int i = 0; i < Ib; ++i) {
+                memcpy(Kb + ((size_t)h * Ib + i) * blk, Kc + (((size_t)b * Hkv + h) * I + i) * blk, sizeof(double) * blk);
+                memcpy(Vb + ((size_t)h * Ib + i) * blk, Vc + (((size_t)b * Hkv + h) * I + i) * blk, sizeof(double) * blk);
+            }
+        rc = kvc_oracle_reconstruct_attend_decode(
+            1, Hq, Hkv, d, n, Ib, m, Kb, Vb, theta, U, mu, Ktxt + (size_t)b * Hkv * Tcap * d,
+            Vtxt + (size_t)b * Hkv * Tcap * d, tb, Tcap, k_new ? k_new + (size_t)b * Hkv * d : 0,
+            v_new ? v_new + (size_t)b * Hkv * d : 0, q + (size_t)b * Hq * d, scale, out + (size_t)b * Hq * d,
+            lse ? lse + (size_t)b * Hq : 0);
+    }
+    free(Kb);
+    free(Vb);
+    return rc;
 }
 
 /*

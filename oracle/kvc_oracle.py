@@ -21,6 +21,10 @@ STORE_NONE = -1
 STORE_F32 = 0
 STORE_BF16 = 1
 
+ACT_IDENTITY = 0
+ACT_RELU = 1
+ACT_GELU = 2
+
 _lib = None
 
 
@@ -44,6 +48,8 @@ def _load():
         L.kvc_oracle_round_to.argtypes = [ctypes.c_double, ctypes.c_int]
         L.kvc_oracle_reconstruct_attend_decode.restype = ctypes.c_int
         L.kvc_oracle_num_threads.restype = ctypes.c_int
+        L.kvc_oracle_static_attend_decode.restype = ctypes.c_int
+        L.kvc_oracle_reconstruct_attend_decode_ragged.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -192,6 +198,89 @@ def reconstruct_attend_decode(q, Kc, Vc, theta, U, mu, n, Ktxt, Vtxt, t, k_new=N
         out.ctypes.data_as(ctypes.c_void_p), lse.ctypes.data_as(ctypes.c_void_p))
     if rc != 0:
         raise RuntimeError("oracle decode failed (allocation, or append beyond capacity)")
+    return out, lse
+
+
+def mlp_hidden(Kc, W1, act, store_dtype=STORE_NONE):
+    """First layer of the two-layer key reconstructor: Kc [B,Hkv,I,m,d], W1 [Hkv,m,m] -> H [B,Hkv,I,m,d]."""
+    L = _load()
+    Kc, pK = _d(Kc)
+    W1, pW = _d(W1)
+    B, Hkv, I, m, d = Kc.shape
+    assert W1.shape == (Hkv, m, m)
+    H = np.empty_like(Kc)
+    L.kvc_oracle_mlp_hidden(_i32(B), _i32(Hkv), _i32(d), _i32(I), _i32(m), pK, pW, ctypes.c_int(act),
+                            ctypes.c_int(store_dtype), H.ctypes.data_as(ctypes.c_void_p))
+    return H
+
+
+def static_attend_decode(q, Kc, Vc, Ktxt, Vtxt, t, k_new=None, v_new=None, scale=None):
+    """Static variant (no reconstruction): attention over the compressed rows and the text cache."""
+    L = _load()
+    q, pq = _d(q)
+    Kc, pKc = _d(Kc)
+    Vc, pVc = _d(Vc)
+    B, Hq, d = q.shape
+    _, Hkv, I, m, _ = Kc.shape
+    if Ktxt is None:
+        assert t == 0 and k_new is None
+        Ktxt = np.zeros((B, Hkv, 1, d))
+        Vtxt = np.zeros((B, Hkv, 1, d))
+    if k_new is not None:
+        assert Ktxt.dtype == np.float64 and Ktxt.flags.c_contiguous
+        assert Vtxt.dtype == np.float64 and Vtxt.flags.c_contiguous
+    Ktxt, pKt = _d(Ktxt)
+    Vtxt, pVt = _d(Vtxt)
+    Tcap = Ktxt.shape[2]
+    pkn = pvn = None
+    if k_new is not None:
+        k_new, pkn = _d(k_new)
+        v_new, pvn = _d(v_new)
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.empty((B, Hq, d), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64)
+    rc = L.kvc_oracle_static_attend_decode(_i32(B), _i32(Hq), _i32(Hkv), _i32(d), _i32(I), _i32(m), pKc, pVc,
+                                           pKt, pVt, _i32(t), _i32(Tcap), pkn, pvn, pq, ctypes.c_double(scale),
+                                           out.ctypes.data_as(ctypes.c_void_p), lse.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        raise RuntimeError("oracle static decode failed (append beyond capacity)")
+    return out, lse
+
+
+def reconstruct_attend_decode_ragged(q, Kc, Vc, theta, U, mu, n, n_images, text_len, Ktxt, Vtxt,
+                                     k_new=None, v_new=None, scale=None):
+    """Ragged decode step: n_images [B] (<= I), text_len [B]; Ktxt/Vtxt float64 C-contiguous, modified
+    in place when k_new/v_new are given."""
+    L = _load()
+    q, pq = _d(q)
+    Kc, pKc = _d(Kc)
+    Vc, pVc = _d(Vc)
+    theta, pT = _d(theta)
+    U, pU = _d(U)
+    mu, pmu = _d(mu)
+    B, Hq, d = q.shape
+    _, Hkv, I, m, _ = Kc.shape
+    assert Ktxt.dtype == np.float64 and Ktxt.flags.c_contiguous and Vtxt.dtype == np.float64 and Vtxt.flags.c_contiguous
+    Tcap = Ktxt.shape[2]
+    ni = np.ascontiguousarray(n_images, dtype=np.int32)
+    tl = np.ascontiguousarray(text_len, dtype=np.int32)
+    assert ni.shape == (B,) and tl.shape == (B,)
+    pkn = pvn = None
+    if k_new is not None:
+        k_new, pkn = _d(k_new)
+        v_new, pvn = _d(v_new)
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.empty((B, Hq, d), dtype=np.float64)
+    lse = np.empty((B, Hq), dtype=np.float64)
+    rc = L.kvc_oracle_reconstruct_attend_decode_ragged(
+        _i32(B), _i32(Hq), _i32(Hkv), _i32(d), _i32(n), _i32(I), _i32(m), ni.ctypes.data_as(ctypes.c_void_p),
+        tl.ctypes.data_as(ctypes.c_void_p), pKc, pVc, pT, pU, pmu, Ktxt.ctypes.data_as(ctypes.c_void_p),
+        Vtxt.ctypes.data_as(ctypes.c_void_p), _i32(Tcap), pkn, pvn, pq, ctypes.c_double(scale),
+        out.ctypes.data_as(ctypes.c_void_p), lse.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        raise RuntimeError("oracle ragged decode failed")
     return out, lse
 
 

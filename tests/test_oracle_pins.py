@@ -485,3 +485,86 @@ def test_attention_is_invariant_to_a_common_logit_shift_and_survives_large_logit
         for g in range(p["Hq"]):
             s = allK[b, g // G] @ q3[b, g]
             assert abs(lse3[b, g] - (s.max() + np.log(np.exp(s - s.max()).sum()))) < 1e-9
+
+
+# ---------------------------------------------------------------- two-layer key reconstructor
+def test_two_layer_reconstructor_collapses_to_the_linear_one_and_matches_library_ops():
+    """Sec. 3.1 (Keys): f_theta as a two-layer MLP along the sequence axis.  With the identity between
+    the layers it is the linear reconstruction with theta = W1 W2 (App. C's score reconstruction matrix);
+    with ReLU / GELU the first layer equals the library's matmul + activation; keys that the first layer
+    leaves positive pass ReLU unchanged."""
+    r = rng(51)
+    B, Hkv, d, n, I, m = 2, 2, 6, 11, 2, 4
+    Kc = r.standard_normal((B, Hkv, I, m, d))
+    W1 = r.standard_normal((Hkv, m, m))
+    W2 = r.standard_normal((Hkv, m, n))
+    zeroU, mu = np.zeros((Hkv, m, n)), np.zeros((Hkv, d))
+    H0 = orc.mlp_hidden(Kc, W1, orc.ACT_IDENTITY)
+    Khat2, _ = orc.reconstruct(H0, H0, W2, zeroU, mu, n)
+    theta = np.einsum("hjr,hrp->hjp", W1, W2)
+    Khat1, _ = orc.reconstruct(Kc, Kc, theta, zeroU, mu, n)
+    assert np.abs(Khat2 - Khat1).max() < 1e-12
+    lin = torch.einsum("hjr,bhijd->bhird", torch.from_numpy(W1), torch.from_numpy(Kc))
+    assert np.abs(orc.mlp_hidden(Kc, W1, orc.ACT_RELU) - F.relu(lin).numpy()).max() < 1e-13
+    assert np.abs(orc.mlp_hidden(Kc, W1, orc.ACT_GELU) - F.gelu(lin).numpy()).max() < 1e-12
+    assert np.any(lin.numpy() < 0)
+    Kpos, Wpos = np.abs(Kc), np.abs(W1)
+    assert np.array_equal(orc.mlp_hidden(Kpos, Wpos, orc.ACT_RELU), orc.mlp_hidden(Kpos, Wpos, orc.ACT_IDENTITY))
+    # stored form: one rounding of the exact value
+    Hb = orc.mlp_hidden(Kc, W1, orc.ACT_GELU, orc.STORE_BF16)
+    Hx = orc.mlp_hidden(Kc, W1, orc.ACT_GELU)
+    assert np.all(np.abs(Hb - Hx) <= np.abs(Hx) * 2.0 ** -8 + 1e-300) and np.abs(Hb - Hx).max() > 0
+    # transposed W1 must not pass: the first layer contracts the ROW index of W1 with the key rows
+    assert np.abs(orc.mlp_hidden(Kc, np.ascontiguousarray(W1.transpose(0, 2, 1)), orc.ACT_RELU) - F.relu(lin).numpy()).max() > 1e-3
+
+
+# ---------------------------------------------------------------- static variant
+def test_static_variant_is_library_attention_over_the_compressed_rows():
+    """Ablation appendix (static compression without reconstruction): the compressed KV is used directly,
+    i.e. plain attention over the I*m compressed rows and the text rows, new token appended first."""
+    p = _tiny_problem(52)
+    B, Hkv, d, I, m, t = p["B"], p["Hkv"], p["d"], p["I"], p["m"], p["t"]
+    r = rng(53)
+    kn, vn = r.standard_normal((B, Hkv, d)), r.standard_normal((B, Hkv, d))
+    Kt, Vt = p["Ktxt"].copy(), p["Vtxt"].copy()
+    out, lse = orc.static_attend_decode(p["q"], p["Kc"], p["Vc"], Kt, Vt, t, kn, vn, scale=0.3)
+    assert np.array_equal(Kt[:, :, t], kn) and np.array_equal(Vt[:, :, t], vn)
+    Kall = np.concatenate([p["Kc"].reshape(B, Hkv, I * m, d), p["Ktxt"][:, :, :t], kn[:, :, None]], 2)
+    Vall = np.concatenate([p["Vc"].reshape(B, Hkv, I * m, d), p["Vtxt"][:, :, :t], vn[:, :, None]], 2)
+    assert np.abs(out - sdpa(p["q"], Kall, Vall, 0.3)).max() < 1e-13
+    # m = n with identity parameters and mu = 0: reconstruction changes nothing, both variants agree
+    n = p["n"]
+    Kc, Vc = rng(54).standard_normal((B, Hkv, I, n, d)), rng(55).standard_normal((B, Hkv, I, n, d))
+    eye = np.stack([np.eye(n)] * Hkv)
+    a, _ = orc.static_attend_decode(p["q"], Kc, Vc, p["Ktxt"], p["Vtxt"], t)
+    b, _ = orc.reconstruct_attend_decode(p["q"], Kc, Vc, eye, eye, np.zeros((Hkv, d)), n, p["Ktxt"], p["Vtxt"], t)
+    assert np.abs(a - b).max() < 1e-13
+
+
+# ---------------------------------------------------------------- ragged batch
+def test_ragged_batch_equals_the_sequences_taken_one_by_one():
+    p = _tiny_problem(56, B=4, I=3, cap=7)
+    B, Hkv, d, n = p["B"], p["Hkv"], p["d"], p["n"]
+    r = rng(57)
+    kn, vn = r.standard_normal((B, Hkv, d)), r.standard_normal((B, Hkv, d))
+    n_images, text_len = [3, 0, 1, 2], [2, 5, 0, 6]
+    Kt, Vt = p["Ktxt"].copy(), p["Vtxt"].copy()
+    out, lse = orc.reconstruct_attend_decode_ragged(p["q"], p["Kc"], p["Vc"], p["theta"], p["U"], p["mu"], n,
+                                                    n_images, text_len, Kt, Vt, kn, vn)
+    for b in range(B):
+        Ib, tb = n_images[b], text_len[b]
+        Kb, Vb = p["Ktxt"][b:b + 1].copy(), p["Vtxt"][b:b + 1].copy()
+        ref, lref = orc.reconstruct_attend_decode(p["q"][b:b + 1], p["Kc"][b:b + 1, :, :Ib], p["Vc"][b:b + 1, :, :Ib],
+                                                  p["theta"], p["U"], p["mu"], n, Kb, Vb, tb, kn[b:b + 1], vn[b:b + 1])
+        assert np.array_equal(out[b], ref[0]) and np.array_equal(lse[b], lref[0])
+        assert np.array_equal(Kt[b], Kb[0]) and np.array_equal(Vt[b], Vb[0])
+        # blocks beyond the sequence's count and text rows beyond its length do not matter
+    Kc2 = p["Kc"].copy()
+    Kc2[1] = 1e3
+    Kc2[2, :, 1:] = -1e3
+    out2, _ = orc.reconstruct_attend_decode_ragged(p["q"], Kc2, p["Vc"], p["theta"], p["U"], p["mu"], n, n_images,
+                                                   text_len, p["Ktxt"].copy(), p["Vtxt"].copy(), kn, vn)
+    assert np.array_equal(out, out2)
+    with pytest.raises(RuntimeError):
+        orc.reconstruct_attend_decode_ragged(p["q"], p["Kc"], p["Vc"], p["theta"], p["U"], p["mu"], n, [4, 0, 0, 0],
+                                             text_len, p["Ktxt"].copy(), p["Vtxt"].copy())
