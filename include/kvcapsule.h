@@ -161,6 +161,54 @@ kvc_status kvc_reconstruct_attend_decode(const kvc_shape *shape, const kvc_param
                                          void *out, float *lse_out,
                                          void *workspace, size_t workspace_bytes, void *stream);
 
+/* Ragged batch: the decode step for sequences with their own numbers of image blocks and text rows.
+ * Sequence b attends the first n_images[b] of its I = shape->n_images capsule slots and text_len[b]
+ * text rows; with k_new / v_new its new token is stored at row text_len[b] first.  The paper states
+ * the method per image "with size n" and is silent on batching; the same per-layer parameters serve
+ * every block as in the uniform call.
+ *  n_images, text_len in: DEVICE arrays [B] of int32; the host cannot see their values, so they are
+ *             clamped on the device to [0, I] and [0, text_cap] ([0, text_cap - 1] with a new token).
+ *             A sequence left with no key at all gets NaNs.
+ * Everything else as in kvc_reconstruct_attend_decode.  Runs on the shape-agnostic scalar kernels (all
+ * dtypes and shapes; far below the matrix-core kernels' speed).
+ * Errors: as kvc_reconstruct_attend_decode, plus NULL / misaligned count arrays, text_cap < 1. */
+kvc_status kvc_reconstruct_attend_decode_ragged(const kvc_shape *shape, const kvc_params *params,
+                                                const void *q, const void *Kc, const void *Vc,
+                                                void *K_text, void *V_text,
+                                                const int32_t *n_images, const int32_t *text_len,
+                                                int32_t text_cap,
+                                                const void *k_new, const void *v_new, float softmax_scale,
+                                                void *out, float *lse_out,
+                                                void *workspace, size_t workspace_bytes, void *stream);
+
+/* Two-layer form of the key reconstructor (Sec. 3.1, Keys: f_theta "implemented as a two-layer MLP"),
+ * read as acting along the sequence axis per KV head with hidden width m and no bias:
+ *     K_hat = W2^T act(W1^T K_tilde).
+ * The first layer depends on the compressed keys only, not on the decode step, so it is applied once,
+ * after kvc_compress, and its result is kept in place of K_tilde (same size):
+ *     H[b,h,i,r,:] = act( sum_j W1[h,j,r] Kc[b,h,i,j,:] ),   r < m,   rounded once to the storage type.
+ * The decode step is then kvc_reconstruct_attend_decode with Kc = H and theta = W2 (the second layer is
+ * the linear reconstruction).  With KVC_ACT_IDENTITY this is the linear form with theta = W1 W2.
+ *  W1 in : [H_kv][m][m] (row j, column r), element type of the shape;  Kc in, H out: [B][H_kv][I][m][d],
+ *          different buffers.
+ * Runs on a scalar kernel (a one-off step of the prefill).
+ * Errors: NULL pointers, bad shape / activation, Kc == H, misalignment. */
+typedef enum { KVC_ACT_IDENTITY = 0, KVC_ACT_RELU = 1, KVC_ACT_GELU = 2 /* 0.5 x (1 + erf(x / sqrt 2)) */ } kvc_activation;
+kvc_status kvc_mlp_hidden(const kvc_shape *shape, const void *W1, int32_t activation,
+                          const void *Kc, void *H, void *stream);
+
+/* Static variant of the paper's ablation (App. "Static Compression vs. Reconstruction-before-Attention":
+ * reconstruction disabled, the compressed KV used directly throughout decoding): plain attention over
+ * the I*m compressed rows of each (batch element, KV head) and the text rows,
+ *     out[b,g,:] = softmax(scale * q[b,g] . [Kc[b,g/G] ; K_text]^T) [Vc[b,g/G] ; V_text],
+ * no theta, no U^T, no mu.  Arguments as in kvc_reconstruct_attend_decode (Vc in its blocked layout;
+ * shape->n_img_tokens is not used).  Runs on the shape-agnostic scalar kernels. */
+kvc_status kvc_static_attend_decode(const kvc_shape *shape, const void *q, const void *Kc, const void *Vc,
+                                    void *K_text, void *V_text, int32_t text_len, int32_t text_cap,
+                                    const void *k_new, const void *v_new, float softmax_scale,
+                                    void *out, float *lse_out,
+                                    void *workspace, size_t workspace_bytes, void *stream);
+
 /* The blocked layout of the compressed values (see kvc_compress), for code that has to read or build a
  * capsule: offset, in elements from the start of an image block's record of m*d elements, of (row j,
  * channel c).  Host arithmetic only; returns -1 if an argument is out of range. */

@@ -249,6 +249,58 @@ kvc_status kvc_reconstruct_attend_decode_generic(const kvc_shape *shape, const k
     return generic_decode(c);
 }
 
+// ---- variants that run on the shape-agnostic kernels -------------------------------------------------
+kvc_status kvc_reconstruct_attend_decode_ragged(const kvc_shape *shape, const kvc_params *params,
+                                                const void *q, const void *Kc, const void *Vc,
+                                                void *K_text, void *V_text, const int32_t *n_images,
+                                                const int32_t *text_len, int32_t text_cap,
+                                                const void *k_new, const void *v_new, float softmax_scale,
+                                                void *out, float *lse_out, void *workspace,
+                                                size_t workspace_bytes, void *stream)
+{
+    if (!n_images || !text_len) return KVC_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(n_images) & 3u) || (reinterpret_cast<uintptr_t>(text_len) & 3u)) return KVC_ERR_ALIGN;
+    if (text_cap < 1) return KVC_ERR_SHAPE;
+    // validated as the uniform call with the longest text that fits
+    const int32_t t_max = text_cap - (k_new ? 1 : 0);
+    DecodeCall c;
+    kvc_status st = prepare_decode(c, shape, params, q, Kc, Vc, K_text, V_text, t_max, text_cap, k_new, v_new,
+                                   softmax_scale, out, lse_out, workspace, workspace_bytes, stream);
+    if (st != KVC_OK) return st;
+    c.n_images_dev = n_images;
+    c.text_len_dev = text_len;
+    return generic_decode(c);
+}
+
+kvc_status kvc_static_attend_decode(const kvc_shape *shape, const void *q, const void *Kc, const void *Vc,
+                                    void *K_text, void *V_text, int32_t text_len, int32_t text_cap,
+                                    const void *k_new, const void *v_new, float softmax_scale, void *out,
+                                    float *lse_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    // theta, U and mu are not part of this variant; q stands in for them (never read)
+    kvc_params none;
+    none.key_idx = nullptr; none.theta = q; none.U = q; none.mu = q;
+    DecodeCall c;
+    kvc_status st = prepare_decode(c, shape, &none, q, Kc, Vc, K_text, V_text, text_len, text_cap, k_new, v_new,
+                                   softmax_scale, out, lse_out, workspace, workspace_bytes, stream);
+    if (st != KVC_OK) return st;
+    c.static_variant = true;
+    return generic_decode(c);
+}
+
+kvc_status kvc_mlp_hidden(const kvc_shape *shape, const void *W1, int32_t activation, const void *Kc, void *H,
+                          void *stream)
+{
+    kvc_status st = check_shape(shape);
+    if (st != KVC_OK) return st;
+    if (activation < KVC_ACT_IDENTITY || activation > KVC_ACT_GELU) return KVC_ERR_SHAPE;
+    if (!W1) return KVC_ERR_NULL;
+    if (shape->n_images > 0 && (!Kc || !H)) return KVC_ERR_NULL;
+    if (Kc == H) return KVC_ERR_SHAPE;                       // every output row reads all input rows
+    if (!aligned16(W1) || !aligned16(Kc) || !aligned16(H)) return KVC_ERR_ALIGN;
+    return generic_mlp_hidden(*shape, W1, activation, Kc, H, static_cast<hipStream_t>(stream));
+}
+
 // ---- the blocked layout of the compressed values, for callers ---------------------------------------
 int64_t kvc_capsule_value_offset(int32_t j, int32_t c, int32_t m, int32_t d)
 {

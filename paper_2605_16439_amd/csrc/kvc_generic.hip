@@ -14,10 +14,16 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 
 // ---- append the new token's k, v to the text cache (Sec. 3.2: text KV unchanged) ----
+// per-sequence counts of a ragged call (null pointers: the uniform values); clamped to what the buffers hold
+__device__ inline int seq_images(const int32_t *n_img, int b, int I) { return n_img ? min(max(n_img[b], 0), I) : I; }
+__device__ inline int seq_text(const int32_t *tlen, int b, int t_uniform, int t_max) { return tlen ? min(max(tlen[b], 0), t_max) : t_uniform; }
+
 template <class T>
-__global__ void g_append(T *Kt, T *Vt, const T *k_new, const T *v_new, int d, int cap, int row)
+__global__ void g_append(T *Kt, T *Vt, const T *k_new, const T *v_new, int d, int cap, int row_uniform, int Hkv,
+                         const int32_t *tlen)
 {
     size_t bh = blockIdx.x;
+    const int row = seq_text(tlen, static_cast<int>(bh / Hkv), row_uniform, cap - 1);
     for (int c = threadIdx.x; c < d; c += blockDim.x) {
         Kt[(bh * cap + row) * d + c] = k_new[bh * d + c];
         Vt[(bh * cap + row) * d + c] = v_new[bh * d + c];
@@ -30,21 +36,25 @@ template <class T>
 __global__ void g_scores(const T *__restrict__ q, const T *__restrict__ Kc,
                          const T *__restrict__ Kt, float *__restrict__ Svis,
                          float *__restrict__ Stxt, int Hq, int Hkv, int d, int Im, int t, int cap,
-                         int tstride, float scale)
+                         int tstride, float scale, int m, const int32_t *n_img, const int32_t *tlen, int append)
 {
     const int G = Hq / Hkv;
     const size_t bh = blockIdx.y;
     const int b = static_cast<int>(bh / Hkv), h = static_cast<int>(bh % Hkv);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int rows = Im + t;
+    const int rows = Im + t;                                   // t: the longest text of the call
+    const int Imb = seq_images(n_img, b, Im / max(m, 1)) * m;  // this sequence's compressed rows
+    const int tb = tlen ? seq_text(tlen, b, 0, cap - append) + append : t;
     for (int r = blockIdx.x * kWaves + wave; r < rows; r += gridDim.x * kWaves) {
+        const bool live = r < Im ? r < Imb : r - Im < tb;      // rows the sequence does not have score -inf
         const T *k = r < Im ? Kc + (bh * Im + r) * d : Kt + (bh * cap + (r - Im)) * d;
         for (int g = 0; g < G; ++g) {
             const size_t bg = static_cast<size_t>(b) * Hq + h * G + g;
             const T *qr = q + bg * d;
             float acc = 0.f;
-            for (int c = lane; c < d; c += 64) acc += to_f(qr[c]) * to_f(k[c]);
-            acc = wave_sum(acc) * scale;
+            if (live)
+                for (int c = lane; c < d; c += 64) acc += to_f(qr[c]) * to_f(k[c]);
+            acc = live ? wave_sum(acc) * scale : -INFINITY;
             if (lane == 0) {
                 if (r < Im) Svis[bg * Im + r] = acc;
                 else Stxt[bg * tstride + (r - Im)] = acc;
@@ -57,21 +67,35 @@ __global__ void g_scores(const T *__restrict__ q, const T *__restrict__ Kc,
 // L[b,g,i,p] = sum_j S[b,g,i,j] theta[h,j,p];  grid = (p chunks, I, B*Hq)
 template <class T>
 __global__ void g_expand(const float *__restrict__ Svis, const T *__restrict__ theta,
-                         float *__restrict__ L, int Hq, int Hkv, int n, int m, int I)
+                         float *__restrict__ L, int Hq, int Hkv, int n, int m, int I, const int32_t *n_img)
 {
     extern __shared__ float sS[];
     const size_t bg = blockIdx.z;
     const int g = static_cast<int>(bg % Hq), h = g / (Hq / Hkv), i = blockIdx.y;
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= seq_images(n_img, static_cast<int>(bg / Hq), I)) {      // a block the sequence does not have
+        if (p < n) L[(bg * I + i) * n + p] = -INFINITY;
+        return;
+    }
     const float *Srow = Svis + (bg * I + i) * m;
     for (int j = threadIdx.x; j < m; j += blockDim.x) sS[j] = Srow[j];
     __syncthreads();
-    const int p = blockIdx.x * blockDim.x + threadIdx.x;
     if (p < n) {
         const T *th = theta + static_cast<size_t>(h) * m * n + p;
         float acc = 0.f;
         for (int j = 0; j < m; ++j) acc += sS[j] * to_f(th[static_cast<size_t>(j) * n]);
         L[(bg * I + i) * n + p] = acc;
     }
+}
+
+// ---- static variant: the compressed scores are the vision logits; their probabilities are the weights ----
+__global__ void g_static_weights(const float *__restrict__ Svis, const float *__restrict__ stats,
+                                 float *__restrict__ W, int Im)
+{
+    const size_t bg = blockIdx.y;
+    const float mx = stats[bg * 4 + 0], inv = 1.f / stats[bg * 4 + 1];
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r < Im) W[bg * Im + r] = __expf(Svis[bg * Im + r] - mx) * inv;
 }
 
 // ---- joint softmax statistics per (b, query head): max, denominator, vision mass ----
@@ -140,7 +164,8 @@ __global__ void g_output(const float *__restrict__ W, const float *__restrict__ 
                          const float *__restrict__ stats, const T *__restrict__ Vc,
                          const T *__restrict__ Vt, const T *__restrict__ mu, T *__restrict__ out,
                          float *__restrict__ lse, int Hq, int Hkv, int d, int Im, int m, int t,
-                         int cap, int tstride)
+                         int cap, int tstride, const int32_t *n_img, const int32_t *tlen, int append,
+                         int with_mu)
 {
     __shared__ float red[kThreads];
     const size_t bg = blockIdx.x;
@@ -149,13 +174,15 @@ __global__ void g_output(const float *__restrict__ W, const float *__restrict__ 
     const int slices = kThreads / d;          // d <= 256
     const int c = threadIdx.x % d, sl = threadIdx.x / d;
     const float mx = stats[bg * 4 + 0], inv = 1.f / stats[bg * 4 + 1];
+    const int Imb = seq_images(n_img, b, Im / m) * m;
+    const int tb = tlen ? seq_text(tlen, b, 0, cap - append) + append : t;
     float acc = 0.f;
     if (sl < slices) {
-        for (int r = sl; r < Im; r += slices) {
+        for (int r = sl; r < Imb; r += slices) {
             const int i = r / m, j = r - i * m;
             acc += W[bg * Im + r] * to_f(Vc[(bh * Im + static_cast<size_t>(i) * m) * d + vc_offset(j, c, m, d)]);
         }
-        for (int x = sl; x < t; x += slices)
+        for (int x = sl; x < tb; x += slices)
             acc += __expf(Stxt[bg * tstride + x] - mx) * inv * to_f(Vt[(bh * cap + x) * d + c]);
     }
     red[threadIdx.x] = acc;
@@ -163,7 +190,7 @@ __global__ void g_output(const float *__restrict__ W, const float *__restrict__ 
     if (threadIdx.x < d) {
         float y = 0.f;
         for (int s2 = 0; s2 < slices; ++s2) y += red[s2 * d + c];
-        y += stats[bg * 4 + 2] * to_f(mu[static_cast<size_t>(h) * d + c]);
+        if (with_mu) y += stats[bg * 4 + 2] * to_f(mu[static_cast<size_t>(h) * d + c]);
         out[bg * d + c] = from_f<T>(y);
     }
     if (threadIdx.x == 0 && lse) lse[bg] = mx + __logf(stats[bg * 4 + 1]);
@@ -214,6 +241,39 @@ __global__ void g_vproject(const T *__restrict__ V, const T *__restrict__ U,
         Vc[(bh * I + i) * m * d + vc_offset(j0 + jj, c, m, d)] = from_f<T>(acc[jj]);
 }
 
+// ---- first layer of the two-layer key reconstructor (Sec. 3.1, Keys) --------------------------------
+// H[b,h,i,r,c] = act(sum_j W1[h,j,r] Kc[b,h,i,j,c]);  grid = (r groups of kRH, I, B*Hkv), a thread per channel
+constexpr int kRH = 8;
+__device__ inline float act_apply(float x, int act)
+{
+    if (act == 1) return fmaxf(x, 0.f);
+    if (act == 2) return 0.5f * x * (1.f + erff(x * 0.70710678118654752f));     // GELU, erf form
+    return x;
+}
+template <class T>
+__global__ void g_mlp_hidden(const T *__restrict__ Kc, const T *__restrict__ W1, T *__restrict__ H, int Hkv, int d,
+                             int m, int I, int act)
+{
+    const size_t bh = blockIdx.z;
+    const int h = static_cast<int>(bh % Hkv), i = blockIdx.y, r0 = blockIdx.x * kRH;
+    const int c = threadIdx.x;
+    if (c >= d) return;
+    const T *Kb = Kc + (bh * I + i) * static_cast<size_t>(m) * d + c;
+    const T *Wb = W1 + static_cast<size_t>(h) * m * m + r0;
+    const int rn = min(kRH, m - r0);
+    float acc[kRH];
+#pragma unroll
+    for (int rr = 0; rr < kRH; ++rr) acc[rr] = 0.f;
+    for (int j = 0; j < m; ++j) {
+        const float k = to_f(Kb[static_cast<size_t>(j) * d]);
+#pragma unroll
+        for (int rr = 0; rr < kRH; ++rr)
+            if (rr < rn) acc[rr] += to_f(Wb[static_cast<size_t>(j) * m + rr]) * k;
+    }
+    for (int rr = 0; rr < rn; ++rr)
+        H[((bh * I + i) * static_cast<size_t>(m) + r0 + rr) * d + c] = from_f<T>(act_apply(acc[rr], act));
+}
+
 struct GenericWs {
     float *Svis, *Stxt, *L, *stats, *W;
     size_t bytes;
@@ -248,29 +308,37 @@ template <class T> kvc_status decode_t(const DecodeCall &c)
     const int Im = I * m, t = c.t;
     GenericWs w = carve(s, c.cap, c.ws);
     const int tstride = c.cap > 0 ? c.cap : 1;
+    const int append = c.k_new ? 1 : 0;
     if (c.k_new)
         g_append<T><<<B * Hkv, 64, 0, c.stream>>>(static_cast<T *>(c.Kt), static_cast<T *>(c.Vt),
                                                   static_cast<const T *>(c.k_new),
-                                                  static_cast<const T *>(c.v_new), d, c.cap, c.t_in);
+                                                  static_cast<const T *>(c.v_new), d, c.cap, c.t_in, Hkv, c.text_len_dev);
     const int rows = Im + t;
     int gx = (rows + kWaves - 1) / kWaves;
     if (gx > 4096) gx = 4096;
     g_scores<T><<<dim3(gx, B * Hkv), kThreads, 0, c.stream>>>(
         static_cast<const T *>(c.q), static_cast<const T *>(c.Kc), static_cast<const T *>(c.Kt),
-        w.Svis, w.Stxt, Hq, Hkv, d, Im, t, c.cap, tstride, c.scale);
-    if (I > 0) {
-        g_expand<T><<<dim3((n + kThreads - 1) / kThreads, I, B * Hq), kThreads, m * sizeof(float),
-                      c.stream>>>(w.Svis, static_cast<const T *>(c.theta), w.L, Hq, Hkv, n, m, I);
-    }
-    g_stats<<<B * Hq, kThreads, 0, c.stream>>>(w.L, w.Stxt, w.stats, I * n, t, tstride);
-    if (I > 0) {
-        g_project<T><<<dim3((m + kJB - 1) / kJB, I, B * Hq), kThreads, n * sizeof(float), c.stream>>>(
-            w.L, w.stats, static_cast<const T *>(c.U), w.W, Hq, Hkv, n, m, I);
+        w.Svis, w.Stxt, Hq, Hkv, d, Im, t, c.cap, tstride, c.scale, m, c.n_images_dev, c.text_len_dev, append);
+    if (c.static_variant) {
+        // the compressed rows are the vision keys and values themselves: softmax over [Svis ; Stxt]
+        g_stats<<<B * Hq, kThreads, 0, c.stream>>>(w.Svis, w.Stxt, w.stats, Im, t, tstride);
+        if (Im > 0)
+            g_static_weights<<<dim3((Im + kThreads - 1) / kThreads, B * Hq), kThreads, 0, c.stream>>>(w.Svis, w.stats, w.W, Im);
+    } else {
+        if (I > 0) {
+            g_expand<T><<<dim3((n + kThreads - 1) / kThreads, I, B * Hq), kThreads, m * sizeof(float),
+                          c.stream>>>(w.Svis, static_cast<const T *>(c.theta), w.L, Hq, Hkv, n, m, I, c.n_images_dev);
+        }
+        g_stats<<<B * Hq, kThreads, 0, c.stream>>>(w.L, w.Stxt, w.stats, I * n, t, tstride);
+        if (I > 0) {
+            g_project<T><<<dim3((m + kJB - 1) / kJB, I, B * Hq), kThreads, n * sizeof(float), c.stream>>>(
+                w.L, w.stats, static_cast<const T *>(c.U), w.W, Hq, Hkv, n, m, I);
+        }
     }
     g_output<T><<<B * Hq, kThreads, 0, c.stream>>>(
         w.W, w.Stxt, w.stats, static_cast<const T *>(c.Vc), static_cast<const T *>(c.Vt),
         static_cast<const T *>(c.mu), static_cast<T *>(c.out), c.lse, Hq, Hkv, d, Im, m, t, c.cap,
-        tstride);
+        tstride, c.n_images_dev, c.text_len_dev, append, c.static_variant ? 0 : 1);
     return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
 }
 
@@ -302,6 +370,20 @@ kvc_status generic_decode(const DecodeCall &c)
     if (static_cast<size_t>(c.s.n_img_tokens) * sizeof(float) > 64 * 1024) return KVC_ERR_UNSUPPORTED;
     if (carve(c.s, c.cap, nullptr).bytes > c.ws_bytes) return KVC_ERR_WORKSPACE;
     return c.s.dtype == KVC_F32 ? decode_t<float>(c) : decode_t<bf16_t>(c);
+}
+
+kvc_status generic_mlp_hidden(const kvc_shape &s, const void *W1, int act, const void *Kc, void *H, hipStream_t stream)
+{
+    if (s.n_images == 0) return KVC_OK;
+    const dim3 grid((s.m + kRH - 1) / kRH, s.n_images, s.batch * s.n_kv_heads);
+    const int threads = ((s.head_dim + 63) / 64) * 64;
+    if (s.dtype == KVC_F32)
+        g_mlp_hidden<float><<<grid, threads, 0, stream>>>(static_cast<const float *>(Kc), static_cast<const float *>(W1),
+                                                          static_cast<float *>(H), s.n_kv_heads, s.head_dim, s.m, s.n_images, act);
+    else
+        g_mlp_hidden<bf16_t><<<grid, threads, 0, stream>>>(static_cast<const bf16_t *>(Kc), static_cast<const bf16_t *>(W1),
+                                                           static_cast<bf16_t *>(H), s.n_kv_heads, s.head_dim, s.m, s.n_images, act);
+    return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
 }
 
 kvc_status generic_compress(const CompressCall &c)

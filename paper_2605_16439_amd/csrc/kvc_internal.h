@@ -71,6 +71,10 @@ struct DecodeCall {
     void *ws;
     size_t ws_bytes;
     hipStream_t stream;
+    // ragged call (scalar kernels): per-sequence image-block and text-row counts in device memory, or null;
+    // t and t_in then hold the largest values any sequence may have
+    const int32_t *n_images_dev = nullptr, *text_len_dev = nullptr;
+    bool static_variant = false;      // attend the compressed rows themselves (no theta, U, mu)
 };
 
 struct CompressCall {
@@ -123,6 +127,7 @@ inline bool allow_lds(const void *fn, size_t bytes, bool *done)
 size_t generic_decode_ws_bytes(const kvc_shape &s, int32_t max_text);
 kvc_status generic_decode(const DecodeCall &c);
 kvc_status generic_compress(const CompressCall &c);
+kvc_status generic_mlp_hidden(const kvc_shape &s, const void *W1, int act, const void *Kc, void *H, hipStream_t stream);
 
 // matrix-core path for bf16, head_dim 128
 bool fast_decode_supported(const kvc_shape &s);

@@ -25,6 +25,9 @@ KVC_ERR_UNSUPPORTED = -6
 KVC_ERR_HIP = -7
 KVC_F32 = 0
 KVC_BF16 = 1
+KVC_ACT_IDENTITY = 0
+KVC_ACT_RELU = 1
+KVC_ACT_GELU = 2
 
 EXPORTS = [
     "kvc_compressed_len", "kvc_workspace_bytes", "kvc_memory_footprint", "kvc_compress",
@@ -34,6 +37,7 @@ EXPORTS = [
     "kvc_attend_full_workspace_bytes", "kvc_attend_full_decode", "kvc_dev_full_decode_chunk_steps",
     "kvc_dev_decode_knobs", "kvc_dev_decode_fallbacks",
     "kvc_capsule_value_offset", "kvc_unpack_values",
+    "kvc_reconstruct_attend_decode_ragged", "kvc_mlp_hidden", "kvc_static_attend_decode",
 ]
 
 
@@ -100,6 +104,15 @@ def lib() -> ctypes.CDLL:
         L.kvc_dev_decode_knobs.argtypes = [i32, i32, i32]
         L.kvc_dev_decode_fallbacks.restype = i64
         L.kvc_dev_decode_fallbacks.argtypes = []
+        L.kvc_reconstruct_attend_decode_ragged.restype = i32
+        L.kvc_reconstruct_attend_decode_ragged.argtypes = [ctypes.POINTER(KvcShape), ctypes.POINTER(KvcParams), vp, vp, vp,
+                                                           vp, vp, vp, vp, i32, vp, vp, ctypes.c_float, vp, vp, vp,
+                                                           ctypes.c_size_t, vp]
+        L.kvc_mlp_hidden.restype = i32
+        L.kvc_mlp_hidden.argtypes = [ctypes.POINTER(KvcShape), vp, i32, vp, vp, vp]
+        L.kvc_static_attend_decode.restype = i32
+        L.kvc_static_attend_decode.argtypes = [ctypes.POINTER(KvcShape), vp, vp, vp, vp, vp, i32, i32, vp, vp,
+                                               ctypes.c_float, vp, vp, vp, ctypes.c_size_t, vp]
         L.kvc_capsule_value_offset.restype = i64
         L.kvc_capsule_value_offset.argtypes = [i32, i32, i32, i32]
         L.kvc_unpack_values.restype = i32
@@ -260,3 +273,38 @@ def kvc_unpack_values(Vc: torch.Tensor, m: int, d: int, stream=None) -> torch.Te
     if st != KVC_OK:
         raise KvcError(st, "kvc_unpack_values")
     return dense
+
+
+def kvc_reconstruct_attend_decode_ragged(shape: KvcShape, params: KvcParams, q, Kc, Vc, K_text, V_text,
+                                         n_images: torch.Tensor, text_len: torch.Tensor, text_cap: int, k_new,
+                                         v_new, softmax_scale: float, out, lse_out, workspace, stream=None,
+                                         check: bool = True) -> int:
+    """n_images, text_len: int32 device tensors [B]."""
+    assert n_images.dtype == torch.int32 and text_len.dtype == torch.int32
+    wp, wb = _ws(workspace)
+    st = lib().kvc_reconstruct_attend_decode_ragged(
+        ctypes.byref(shape), ctypes.byref(params), _ptr(q), _ptr(Kc), _ptr(Vc), _ptr(K_text), _ptr(V_text),
+        _ptr(n_images), _ptr(text_len), int(text_cap), _ptr(k_new), _ptr(v_new), ctypes.c_float(softmax_scale),
+        _ptr(out), _ptr(lse_out), wp, wb, _stream(stream))
+    if check and st != KVC_OK:
+        raise KvcError(st, "kvc_reconstruct_attend_decode_ragged")
+    return st
+
+
+def kvc_mlp_hidden(shape: KvcShape, W1: torch.Tensor, activation: int, Kc: torch.Tensor, H: torch.Tensor,
+                   stream=None, check: bool = True) -> int:
+    st = lib().kvc_mlp_hidden(ctypes.byref(shape), _ptr(W1), int(activation), _ptr(Kc), _ptr(H), _stream(stream))
+    if check and st != KVC_OK:
+        raise KvcError(st, "kvc_mlp_hidden")
+    return st
+
+
+def kvc_static_attend_decode(shape: KvcShape, q, Kc, Vc, K_text, V_text, text_len: int, text_cap: int, k_new, v_new,
+                             softmax_scale: float, out, lse_out, workspace, stream=None, check: bool = True) -> int:
+    wp, wb = _ws(workspace)
+    st = lib().kvc_static_attend_decode(ctypes.byref(shape), _ptr(q), _ptr(Kc), _ptr(Vc), _ptr(K_text), _ptr(V_text),
+                                        int(text_len), int(text_cap), _ptr(k_new), _ptr(v_new),
+                                        ctypes.c_float(softmax_scale), _ptr(out), _ptr(lse_out), wp, wb, _stream(stream))
+    if check and st != KVC_OK:
+        raise KvcError(st, "kvc_static_attend_decode")
+    return st
