@@ -65,6 +65,13 @@ void kvc_dev_decode_knobs(int32_t row_tiles, int32_t separate, int32_t wait_tick
  * synchronises with the device), or -1. */
 int64_t kvc_dev_decode_fallbacks(void);
 
+/* Developer switches of the matrix-core compress kernel (process-wide; negative leaves a setting
+ * unchanged).
+ *  waves: 4 or 8 wavefronts per workgroup; 0 restores the built-in rule (8 when a workgroup owns more
+ *         than 4 tiles of 16 rows of U).
+ *  jt   : workgroups per image block (clamped to what the kernel supports); 0 restores the cost model. */
+void kvc_dev_compress_knobs(int32_t waves, int32_t jt);
+
 #ifdef __cplusplus
 }
 #endif

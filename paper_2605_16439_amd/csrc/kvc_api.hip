@@ -458,6 +458,8 @@ void kvc_dev_decode_knobs(int32_t row_tiles, int32_t separate, int32_t wait_tick
 
 int64_t kvc_dev_decode_fallbacks(void) { return fast_decode_fallbacks(); }
 
+void kvc_dev_compress_knobs(int32_t waves, int32_t jt) { fast_compress_knobs(waves, jt); }
+
 
 
 namespace {

@@ -2,18 +2,25 @@
 //
 // Values (Sec. 3.1, "Sequence-Level Low-Rank Compression for Values"):
 //     Vc[b,h,i] = U[h] (V[b,h,block i] - 1 mu[h]^T) = U[h] V - (U[h] 1) mu[h]^T
-// is one GEMM per image block, [m x n] . [n x d].  A workgroup owns up to 64 MT rows j of one
-// block (MT <= 4): each of its 4 wavefronts keeps MT tiles of 16 rows x 128 channels of
+// is one GEMM per image block, [m x n] . [n x d].  A workgroup of NW wavefronts owns up to
+// 16 NW MT rows j of one block: each wavefront keeps MT tiles of 16 rows x 128 channels of
 // accumulators.  Per 64 positions, the workgroup's rows of U are read with whole 128-byte
 // lines and staged in LDS in row order (an MFMA operand is then 16 bytes of one row), and the
 // V tile is transposed on its way into LDS (V is stored position-major, the B operand needs 8
-// consecutive positions of one channel per lane).  Every LDS fragment of V feeds MT MFMAs.  The row sums U 1 come out of the same pass as one extra MFMA against a tile of
-// ones, already in the accumulator layout, so the centring costs no extra read of V.
-// The result is rounded once to bf16 and stored in the blocked channel-major layout that the
-// decode kernel reads as MFMA operands.
+// consecutive positions of one channel per lane).  Every LDS fragment of V feeds MT MFMAs.
+// The row sums U 1 come out of the same pass as one extra MFMA against a tile of ones, already
+// in the accumulator layout, so the centring costs no extra read of V.  The result is rounded
+// once to bf16 and stored in the blocked channel-major layout that the decode kernel reads as
+// MFMA operands.
 //
-// Keys (Sec. 3.1, "Selective Retention and Reconstruction for Keys"): every workgroup first copies
-// the key rows that the mask selects for its own rows j, 16 bytes per lane.
+// With NW = 8 two wavefronts share a SIMD: while one waits for LDS or at the barrier the other
+// issues MFMAs, which a workgroup of four wavefronts (one per SIMD) cannot do.  At the shapes of
+// the paper's workloads the kernel is bound by what the L2s deliver to the compute units (every
+// workgroup streams its rows of U and its block of V once), not by the matrix cores.
+//
+// Keys (Sec. 3.1, "Selective Retention and Reconstruction for Keys"): every workgroup copies the
+// key rows that the mask selects for its own rows j, 16 bytes per lane, one pass of rows per step
+// of the projection, so the copy (and its writes) overlap the projection instead of preceding it.
 #include "kvc_internal.h"
 
 namespace kvc {
@@ -26,14 +33,28 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int D = 128;
 constexpr int kKT = 64;        // positions per LDS tile
 constexpr int kLD = kKT + 8;   // padded row of the transposed V tile (bf16 elements)
-constexpr int kMaxMT = 4;      // 16-row tiles of U per wavefront, at most
+constexpr int kMaxRows = 256;  // rows of U per workgroup, at most (LDS: two stages of U and V tiles)
 
 struct CPlan {
     int B, Hkv, n, I, m, vis0;
     int tiles, TPW, JT;         // 16-row tiles of U, tiles per workgroup, workgroups per image block
     int nproj;
+    int per_xcd;                // workgroups per XCD when they divide evenly over the 8 XCDs, else 0
     int64_t sb, sh, ss;
+#if defined(KVC_TIMELINE)
+    unsigned long long *tl;     // timeline slots, see TSC()
+#endif
 };
+
+// Developer aid, compiled in only with -DKVC_TIMELINE: thread 0 of every workgroup records the wall
+// clock at a few points, in the last MiB of the workspace.
+#if defined(KVC_TIMELINE)
+#define TSC(K) do { if (p.tl && threadIdx.x == 0 && blockIdx.x < 1024) p.tl[blockIdx.x * 8 + (K)] = wall_clock64(); } while (0)
+#else
+#define TSC(K) do { } while (0)
+#endif
+
+int g_force_nw = 0, g_force_jt = 0;     // developer switches (0: the cost model decides)
 
 __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -42,62 +63,52 @@ __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, 
 // spread over the banks and the operand reads of one tile stay conflict-free
 __device__ inline int sv_index(int c, int p) { return c * kLD + ((((p >> 3) ^ (c >> 4)) & 7) << 3) + (p & 7); }
 
-// MT = tiles per wavefront: a workgroup covers up to 64 MT rows of U, so V is read
-// ceil(m / (64 MT)) times per image block and every LDS fragment of V feeds MT MFMAs.
-template <int MT>
-__global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__restrict__ K,
-                                                   const uint16_t *__restrict__ V,
-                                                   const int32_t *__restrict__ idx,
-                                                   const uint16_t *__restrict__ U,
-                                                   const uint16_t *__restrict__ mu,
-                                                   uint16_t *__restrict__ Kc,
-                                                   uint16_t *__restrict__ Vc)
+
+// NW wavefronts, MT tiles per wavefront: a workgroup covers up to 16 NW MT rows of U, so V is read
+// ceil(m / (16 NW MT)) times per image block and every LDS fragment of V feeds MT MFMAs.
+template <int NW, int MT>
+__global__ __launch_bounds__(64 * NW) void fk_compress(CPlan p, const uint16_t *__restrict__ K,
+                                                       const uint16_t *__restrict__ V,
+                                                       const int32_t *__restrict__ idx,
+                                                       const uint16_t *__restrict__ U,
+                                                       const uint16_t *__restrict__ mu,
+                                                       uint16_t *__restrict__ Kc,
+                                                       uint16_t *__restrict__ Vc)
 {
+    constexpr int NT = 64 * NW;          // threads
+    constexpr int RP = NT / 16;          // rows (or pairs of positions) one pass of 16 lanes each covers
+    constexpr int NV = 512 / NT;         // V tile items (pair of positions, 8 channels) per thread
+    constexpr int R = 16 * NW * MT;      // rows of U held by the workgroup
     __shared__ __align__(16) uint16_t sVt[2][D * kLD];
-    extern __shared__ __align__(16) uint16_t sU[];          // [2][64 MT][kLD] rows of U, 64 positions each
+    extern __shared__ __align__(16) uint16_t sU[];          // [2][R][kLD] rows of U, 64 positions each
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
 
-    // ---------------- values: up to 4 MT tiles of 16 rows j of one image block ----------------
-    const int u = blockIdx.x / p.JT, jt = blockIdx.x - u * p.JT;
+    // Workgroups are dealt to the 8 XCDs round-robin by the hardware.  Logical workgroups are numbered
+    // so that one XCD gets a contiguous run: the JT workgroups of one image block (same V) and the
+    // image blocks of one head (same U) then share an L2.
+    const int bx = blockIdx.x;
+    const int wg = p.per_xcd ? (bx & 7) * p.per_xcd + (bx >> 3) : bx;
+    const int u = wg / p.JT, jt = wg - u * p.JT;
     const int bh = u / p.I, i = u - bh * p.I;
     const int b = bh / p.Hkv, h = bh - b * p.Hkv;
     const int tile0 = jt * p.TPW, ntile = min(p.TPW, p.tiles - tile0);
-    // tile q of this wave is tile0 + wave + 4 q; rows beyond the workgroup's share repeat the last
+    // tile q of this wave is tile0 + wave + NW q; rows beyond the workgroup's share repeat the last
     // row of U and their results are dropped, so the main loop carries no tests
     int j0[MT];
 #pragma unroll
-    for (int q = 0; q < MT; ++q) j0[q] = 16 * (tile0 + wave + 4 * q);
+    for (int q = 0; q < MT; ++q) j0[q] = 16 * (tile0 + wave + NW * q);
     // U loads: item = (row of the workgroup, 16-byte piece of its 64 positions); 2 MT per thread
     const uint16_t *usrc[2 * MT];
 #pragma unroll
     for (int k = 0; k < 2 * MT; ++k) {
-        const int row = (static_cast<int>(threadIdx.x) + 256 * k) >> 3;
+        const int row = (static_cast<int>(threadIdx.x) + NT * k) >> 3;
         usrc[k] = U + (static_cast<size_t>(h) * p.m + min(16 * tile0 + row, p.m - 1)) * p.n + 8 * (threadIdx.x & 7);
     }
-    // ---- keys (Sec. 3.1): Kc[u][j][:] = K[b,h, vis0 + i n + M[j], :] for this workgroup's rows j -------
-    // 16 lanes per row, 16 rows per pass; all rows are requested before the first is stored, and the
-    // stores drain while the projection below starts
-    {
-        const uint16_t *ksrc = K + b * p.sb + h * p.sh + (static_cast<int64_t>(p.vis0) + static_cast<int64_t>(i) * p.n) * p.ss;
-        const int rl = threadIdx.x >> 4, c16 = threadIdx.x & 15;
-        const int jend = min(16 * (tile0 + ntile), p.m);
-        u32x4 kv[4 * MT];
-#pragma unroll
-        for (int k = 0; k < 4 * MT; ++k) {
-            const int j = min(16 * (tile0 + k) + rl, p.m - 1);
-            const int row = min(max(idx[j], 0), p.n - 1);      // an index outside the block must not leave it
-            kv[k] = *(reinterpret_cast<const u32x4 *>(ksrc + static_cast<int64_t>(row) * p.ss) + c16);
-        }
-#pragma unroll
-        for (int k = 0; k < 4 * MT; ++k) {
-            const int j = 16 * (tile0 + k) + rl;
-            if (j < jend) *(reinterpret_cast<u32x4 *>(Kc + (static_cast<size_t>(u) * p.m + j) * D) + c16) = kv[k];
-        }
-    }
-    const uint16_t *vsrc = V + b * p.sb + h * p.sh + (static_cast<int64_t>(p.vis0) + static_cast<int64_t>(i) * p.n) * p.ss;
-    // V tile loads: item = (pair of positions, 8 channels); 512 items, two per thread
-    const int pair0 = threadIdx.x >> 4, cs = threadIdx.x & 15;      // second item: pair0 + 16
+    const int64_t blk = b * p.sb + h * p.sh + (static_cast<int64_t>(p.vis0) + static_cast<int64_t>(i) * p.n) * p.ss;
+    const uint16_t *vsrc = V + blk;
+    // V tile loads: item = (pair of positions, 8 channels); 512 items
+    const int pair0 = threadIdx.x >> 4, cs = threadIdx.x & 15;      // further items: pair0 + RP q
 
     f32x4 acc[MT][8], accs[MT];
 #pragma unroll
@@ -109,29 +120,31 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
     const uint32_t one2 = 0x3f803f80u;
     const bf16x8 ones = as_bf16x8(make_uint4(one2, one2, one2, one2));
 
-    // Two register stages rotate by name (the loop is unrolled by two): a tile's loads are issued
-    // right after the barrier of the previous tile and have that tile's MFMA work to arrive; nothing
-    // is copied between stages.
-    u32x4 vaA[2][2], uaA[2 * MT], vaB[2][2], uaB[2 * MT];
-    auto load_tile = [&](int kt, u32x4 (&va)[2][2], u32x4 (&ua)[2 * MT]) {
+    // Software pipeline, one barrier per step.  Step s multiplies tile s out of LDS buffer s & 1 and,
+    // between its MFMAs, packs tile s + 1 from registers into the other buffer and asks memory for
+    // tile s + 3 in the registers this frees: memory requests, packing and LDS stores ride under the
+    // matrix work of the same wave instead of preceding it.  Two register stages rotate by name (the
+    // loop is unrolled by two); X holds even tiles, Y odd ones.
+    u32x4 vaX[NV][2], uaX[2 * MT], vaY[NV][2], uaY[2 * MT];
+    const int NK = p.n / kKT;
+    auto load_tile = [&](int kt, u32x4 (&va)[NV][2], u32x4 (&ua)[2 * MT]) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
+        for (int q = 0; q < NV; ++q)
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                const int pp = kt * kKT + 2 * (pair0 + 16 * q) + e;
+                const int pp = kt * kKT + 2 * (pair0 + RP * q) + e;
                 va[q][e] = *(reinterpret_cast<const u32x4 *>(vsrc + static_cast<int64_t>(pp) * p.ss) + cs);
             }
 #pragma unroll
         for (int k = 0; k < 2 * MT; ++k) ua[k] = *reinterpret_cast<const u32x4 *>(usrc[k] + kt * kKT);
     };
-    const int NK = p.n / kKT;
-    auto step = [&](int kt, u32x4 (&va)[2][2], u32x4 (&ua)[2 * MT]) {
+    auto store_tile = [&](int kt, const u32x4 (&va)[NV][2], const u32x4 (&ua)[2 * MT]) {
         uint16_t *buf = sVt[kt & 1];
-        uint16_t *ubuf = sU + (kt & 1) * (64 * MT * kLD);
+        uint16_t *ubuf = sU + (kt & 1) * (R * kLD);
         // transposed store: positions (2 pair, 2 pair + 1) of channel c share one 32-bit word
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int pl = 2 * (pair0 + 16 * q);
+        for (int q = 0; q < NV; ++q) {
+            const int pl = 2 * (pair0 + RP * q);
             const uint32_t a[4] = {va[q][0].x, va[q][0].y, va[q][0].z, va[q][0].w};
             const uint32_t c2[4] = {va[q][1].x, va[q][1].y, va[q][1].z, va[q][1].w};
 #pragma unroll
@@ -142,44 +155,84 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
         }
 #pragma unroll
         for (int k = 0; k < 2 * MT; ++k) {
-            const int row = (static_cast<int>(threadIdx.x) + 256 * k) >> 3;
+            const int row = (static_cast<int>(threadIdx.x) + NT * k) >> 3;
             *reinterpret_cast<u32x4 *>(ubuf + row * kLD + 8 * (threadIdx.x & 7)) = ua[k];
         }
-        __syncthreads();
-        load_tile(min(kt + 2, NK - 1), va, ua);          // past the end: the last tile again, unused
-        // every fragment of the tile is requested from LDS before the first MFMA: the reads of one
-        // wave then overlap the matrix work instead of being waited for one by one
-        bf16x8 af[2][MT], bq[2][8];
+    };
+    TSC(0);
+    load_tile(0, vaX, uaX);
+    load_tile(min(1, NK - 1), vaY, uaY);
+
+    // ---- keys (Sec. 3.1): Kc[u][j][:] = K[b,h, vis0 + i n + M[j], :] for this workgroup's rows j -------
+    // 16 lanes per row, RP rows per pass, 4 MT passes, one pass per step of the projection and three
+    // steps deep: tick t asks for the mask entry of pass t, for the key row of pass t - 1 and stores
+    // the row of pass t - 2, so no wait of the copy is ever exposed.
+    const int rl = threadIdx.x >> 4;
+    const int jend = min(16 * (tile0 + ntile), p.m);
+    int krow = 0;
+    u32x4 kvrow = {0u, 0u, 0u, 0u};
+    auto keys_tick = [&](int t) {
+        if (t >= 2 && t - 2 < 4 * MT) {
+            const int j = 16 * tile0 + RP * (t - 2) + rl;
+            if (j < jend) *(reinterpret_cast<u32x4 *>(Kc + (static_cast<size_t>(u) * p.m + j) * D) + cs) = kvrow;
+        }
+        if (t >= 1 && t - 1 < 4 * MT) {
+            const int row = min(max(krow, 0), p.n - 1);         // an index outside the block must not leave it
+            kvrow = *(reinterpret_cast<const u32x4 *>(K + blk + static_cast<int64_t>(row) * p.ss) + cs);
+        }
+        if (t < 4 * MT) krow = idx[min(16 * tile0 + RP * t + rl, p.m - 1)];
+    };
+
+    auto step = [&](int kt, u32x4 (&va)[NV][2], u32x4 (&ua)[2 * MT]) {
+        const uint16_t *buf = sVt[kt & 1];
+        const uint16_t *ubuf = sU + (kt & 1) * (R * kLD);
+        // only LDS is handed over here: wait for this wave's LDS stores, then for the other waves.
+        // (__syncthreads() would also wait for the global loads in flight.)
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        // The fragments of V are requested a few ahead of the MFMAs that use them (a rolling window
+        // keeps the wave within its registers); the order is pinned, or the compiler waits for every
+        // fragment right after asking for it.
+        constexpr int AH = 4;
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 af[2][MT], bq[16];
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int q = 0; q < MT; ++q)
-                af[ks][q] = *reinterpret_cast<const bf16x8 *>(ubuf + (16 * (wave + 4 * q) + r16) * kLD + 32 * ks + 8 * kg);
+                af[ks][q] = *reinterpret_cast<const bf16x8 *>(ubuf + (16 * (wave + NW * q) + r16) * kLD + 32 * ks + 8 * kg);
+        auto vfrag = [&](int f) {       // fragment f = 8 ks + nt
+            return *reinterpret_cast<const bf16x8 *>(buf + sv_index(16 * (f & 7) + r16, 32 * (f >> 3) + 8 * kg));
+        };
 #pragma unroll
-            for (int nt = 0; nt < 8; ++nt)
-                bq[ks][nt] = *reinterpret_cast<const bf16x8 *>(buf + sv_index(16 * nt + r16, 32 * ks + 8 * kg));
-        }
-        __builtin_amdgcn_sched_barrier(0);
+        for (int f = 0; f < AH; ++f) bq[f] = vfrag(f);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int f = 0; f < 16; ++f) {
+            if (f + AH < 16) bq[f + AH] = vfrag(f + AH);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int nt = 0; nt < 8; ++nt)
+            for (int q = 0; q < MT; ++q)
+                acc[q][f & 7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[f >> 3][q], bq[f], acc[q][f & 7], 0, 0, 0);
+            if ((f & 7) == 7) {
 #pragma unroll
                 for (int q = 0; q < MT; ++q)
-                    acc[q][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks][q], bq[ks][nt], acc[q][nt], 0, 0, 0);
-#pragma unroll
-            for (int q = 0; q < MT; ++q)
-                accs[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[ks][q], ones, accs[q], 0, 0, 0);
+                    accs[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[f >> 3][q], ones, accs[q], 0, 0, 0);
+            }
+            if (f == 3 && kt + 1 < NK) store_tile(kt + 1, va, ua);      // the same for every wave: plain branches
+            if (f == 10 && kt + 3 < NK) load_tile(kt + 3, va, ua);
+            if (f == 12) keys_tick(kt);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
-    load_tile(0, vaA, uaA);
-    load_tile(min(1, NK - 1), vaB, uaB);
-    int kt = 0;
-    for (; kt + 2 <= NK; kt += 2) {                      // no tests inside the loop body
-        step(kt, vaA, uaA);
-        step(kt + 1, vaB, uaB);
+    store_tile(0, vaX, uaX);
+    load_tile(min(2, NK - 1), vaX, uaX);
+    TSC(1);
+    for (int kt = 0; kt < NK; kt += 2) {
+        if (kt == 2) TSC(2);
+        step(kt, vaY, uaY);
+        if (kt + 1 < NK) step(kt + 1, vaX, uaX);
     }
-    if (kt < NK) step(kt, vaA, uaA);
+    TSC(4);
+    for (int t = NK; t < 4 * MT + 2; ++t) keys_tick(t);     // passes a short block left over
 
     // ---- epilogue: centre, round once, store in the blocked layout -----------------------------------
     // lane holds rows j = j0 + 4 kg + e (e = 0..3) of channel c = 16 nt + r16; accs[e] = sum_p U[j][p]
@@ -189,7 +242,7 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
         muc[nt] = __uint_as_float(static_cast<uint32_t>(mu[static_cast<size_t>(h) * D + 16 * nt + r16]) << 16);
 #pragma unroll
     for (int q = 0; q < MT; ++q) {
-        if (wave + 4 * q >= ntile) continue;
+        if (wave + NW * q >= ntile) continue;
         const int jb = (j0[q] + 4 * kg) >> 3, jr = (j0[q] + 4 * kg) & 7;
         const int w = min(8, p.m - 8 * jb);                     // width of the block these rows sit in
         uint16_t *vout = Vc + static_cast<size_t>(u) * p.m * D + static_cast<size_t>(jb) * 8 * D;
@@ -208,21 +261,46 @@ __global__ __launch_bounds__(256) void fk_compress(CPlan p, const uint16_t *__re
             }
         }
     }
+    TSC(5);
 }
 
-template <int MT> bool launch(const CPlan &p, const CompressCall &c)
+template <int NW, int MT> bool launch(const CPlan &p, const CompressCall &c)
 {
-    const size_t lds = static_cast<size_t>(2) * 64 * MT * kLD * sizeof(uint16_t);
+    static_assert(16 * NW * MT <= kMaxRows, "rows of U per workgroup");
+    const size_t lds = static_cast<size_t>(2) * 16 * NW * MT * kLD * sizeof(uint16_t);
     static bool attr_set[kMaxDevices] = {};
-    if (!allow_lds(reinterpret_cast<const void *>(fk_compress<MT>), lds, attr_set)) return false;
-    fk_compress<MT><<<p.nproj, 256, lds, c.stream>>>(
+    if (!allow_lds(reinterpret_cast<const void *>(fk_compress<NW, MT>), lds, attr_set)) return false;
+    fk_compress<NW, MT><<<p.nproj, 64 * NW, lds, c.stream>>>(
         p, static_cast<const uint16_t *>(c.K), static_cast<const uint16_t *>(c.V), c.key_idx,
         static_cast<const uint16_t *>(c.U), static_cast<const uint16_t *>(c.mu),
         static_cast<uint16_t *>(c.Kc), static_cast<uint16_t *>(c.Vc));
     return true;
 }
 
+// compute units of the current device, asked once per device
+int device_cus()
+{
+    static int cus[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+    if (cus[dev] == 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) {
+            (void)hipGetLastError();
+            v = 256;
+        }
+        cus[dev] = v;
+    }
+    return cus[dev];
+}
+
 }  // namespace
+
+void fast_compress_knobs(int nw, int jt)
+{
+    if (nw >= 0) g_force_nw = nw;
+    if (jt >= 0) g_force_jt = jt;
+}
 
 bool fast_compress_supported(const kvc_shape &s)
 {
@@ -238,33 +316,46 @@ kvc_status fast_compress(const CompressCall &c)
     CPlan p;
     p.B = s.batch; p.Hkv = s.n_kv_heads; p.n = s.n_img_tokens; p.I = s.n_images; p.m = s.m;
     p.vis0 = c.vis_start;
-    // The 16-row tiles of U are shared out evenly over JT workgroups per image block, each wave taking
-    // MT = ceil(tiles per workgroup / 4) of them.  JT is chosen by a small cost model fitted to
-    // measurements on MI355X: time per round of resident workgroups grows with MT (fewer, fatter
-    // workgroups read V less often but leave one workgroup per CU), MT = 1 fits two per CU.
+    // The 16-row tiles of U are shared out evenly over JT workgroups per image block, at most 16 per
+    // workgroup.  A workgroup's time has a part that does not depend on its share (it streams the
+    // whole block of V) and a part that grows with it, about 20 : 1 per tile on MI355X; JT minimises
+    // rounds of resident workgroups (one per compute unit) times that cost, which at the paper's shapes
+    // is the smallest JT the kernel supports.
     p.tiles = (s.m + 15) / 16;
     const int units = p.B * p.Hkv * p.I;
+    const int max_tpw = kMaxRows / 16;
     {
-        static const int round_cost[kMaxMT + 1] = {0, 27, 30, 36, 42};
-        const int cus = 256;
+        const int cus = device_cus();
+        const int jt_min = (p.tiles + max_tpw - 1) / max_tpw, jt_max = (p.tiles + 3) / 4;
         long best = -1;
-        for (int jt = (p.tiles + 4 * kMaxMT - 1) / (4 * kMaxMT); jt <= (p.tiles + 3) / 4; ++jt) {
-            const int tpw = (p.tiles + jt - 1) / jt, mt = (tpw + 3) / 4;
-            const long slots = mt == 1 ? 2L * cus : cus;
-            const long rounds = (static_cast<long>(units) * jt + slots - 1) / slots;
-            const long cost = rounds * round_cost[mt];
+        for (int jt = jt_min; jt <= jt_max; ++jt) {
+            const int tpw = (p.tiles + jt - 1) / jt;
+            const long rounds = (static_cast<long>(units) * jt + cus - 1) / cus;
+            const long cost = rounds * (20 + tpw);
             if (best < 0 || cost < best) { best = cost; p.JT = jt; }
         }
+        if (g_force_jt > 0) p.JT = std::min(std::max(g_force_jt, jt_min), p.tiles);
     }
     p.TPW = (p.tiles + p.JT - 1) / p.JT;
     p.nproj = units * p.JT;
+    p.per_xcd = p.nproj % 8 == 0 ? p.nproj / 8 : 0;
     p.sb = c.stride_b; p.sh = c.stride_h; p.ss = c.stride_s;
+#if defined(KVC_TIMELINE)
+    p.tl = (c.ws && c.ws_bytes >= (2u << 20))
+               ? reinterpret_cast<unsigned long long *>((reinterpret_cast<uintptr_t>(c.ws) + c.ws_bytes - (1u << 20)) & ~uintptr_t(7))
+               : nullptr;
+#endif
+    const int nw = g_force_nw == 4 || g_force_nw == 8 ? g_force_nw : (p.TPW > 4 ? 8 : 4);
     bool ok;
-    switch ((p.TPW + 3) / 4) {
-    case 1: ok = launch<1>(p, c); break;
-    case 2: ok = launch<2>(p, c); break;
-    case 3: ok = launch<3>(p, c); break;
-    default: ok = launch<4>(p, c); break;
+    if (nw == 8) {
+        ok = p.TPW > 8 ? launch<8, 2>(p, c) : launch<8, 1>(p, c);
+    } else {
+        switch ((p.TPW + 3) / 4) {
+        case 1: ok = launch<4, 1>(p, c); break;
+        case 2: ok = launch<4, 2>(p, c); break;
+        case 3: ok = launch<4, 3>(p, c); break;
+        default: ok = launch<4, 4>(p, c); break;
+        }
     }
     return ok && hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
 }

@@ -148,5 +148,6 @@ void full_decode_set_chunk_steps(int steps);
 bool fast_compress_supported(const kvc_shape &s);
 size_t fast_compress_ws_bytes(const kvc_shape &s);
 kvc_status fast_compress(const CompressCall &c);
+void fast_compress_knobs(int waves, int jt);
 
 }  // namespace kvc

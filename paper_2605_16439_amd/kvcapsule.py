@@ -35,7 +35,7 @@ EXPORTS = [
     "kvc_compress_generic", "kvc_probe_read", "kvc_status_string", "kvc_version",
     "kvc_static_scratch_bytes", "kvc_reconstruct_attend_decode_static",
     "kvc_attend_full_workspace_bytes", "kvc_attend_full_decode", "kvc_dev_full_decode_chunk_steps",
-    "kvc_dev_decode_knobs", "kvc_dev_decode_fallbacks",
+    "kvc_dev_decode_knobs", "kvc_dev_decode_fallbacks", "kvc_dev_compress_knobs",
     "kvc_capsule_value_offset", "kvc_unpack_values",
     "kvc_reconstruct_attend_decode_ragged", "kvc_mlp_hidden", "kvc_static_attend_decode",
 ]
@@ -104,6 +104,8 @@ def lib() -> ctypes.CDLL:
         L.kvc_dev_decode_knobs.argtypes = [i32, i32, i32]
         L.kvc_dev_decode_fallbacks.restype = i64
         L.kvc_dev_decode_fallbacks.argtypes = []
+        L.kvc_dev_compress_knobs.restype = None
+        L.kvc_dev_compress_knobs.argtypes = [i32, i32]
         L.kvc_reconstruct_attend_decode_ragged.restype = i32
         L.kvc_reconstruct_attend_decode_ragged.argtypes = [ctypes.POINTER(KvcShape), ctypes.POINTER(KvcParams), vp, vp, vp,
                                                            vp, vp, vp, vp, i32, vp, vp, ctypes.c_float, vp, vp, vp,
