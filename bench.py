@@ -34,14 +34,32 @@ def algorithmic_bytes(w, m, t_avg, b=2):
     return capsule + text + params + qout
 
 
-def read_traffic():
-    """Measured HBM bytes per decode call from the committed rocprofv3 counter summary."""
+def compress_report(w, ms, ms_per_layer, b=2):
+    """One kvc_compress call per layer (event pair around each call): time, matrix-core rate and the
+    HBM bytes it must move (V block and the retained key rows read, both capsule halves written, U,
+    mu and the mask read once) against the HBM peak."""
+    m = sum(ms) / len(ms)
+    units = w.batch * w.n_kv_heads * w.n_images
+    flops = 2.0 * units * m * w.n_img_tokens * w.head_dim
+    nbytes = units * (w.n_img_tokens + 3 * m) * w.head_dim * b + w.n_kv_heads * (m * w.n_img_tokens + w.head_dim) * b + 4 * m
+    sec = ms_per_layer * 1e-3
+    return {"ms_per_layer": ms_per_layer, "tflops": flops / sec / 1e12,
+            "algorithmic_bytes_per_layer": nbytes, "achieved_gbs": nbytes / sec / 1e9,
+            "hbm_frac": nbytes / sec / 1e9 / HBM_PEAK_GBS}
+
+
+def read_traffic(workload, compression, kernels, pyramid):
+    """Measured HBM bytes per decode call from the committed rocprofv3 counter summary; None unless
+    that summary was taken on this very workload, compression and kernel path."""
     path = os.path.join(ROOT, "profiles", "decode_traffic.json")
     try:
         with open(path) as f:
-            return json.load(f)
+            t = json.load(f)
     except (OSError, ValueError):
         return None
+    same = (t.get("workload_name") == workload and abs(t.get("compression", -1.0) - compression) < 1e-9
+            and t.get("kernels") == kernels and not pyramid)
+    return t if same else None
 
 
 def main():
@@ -262,7 +280,7 @@ def main():
     t_avg = w.text_len + (K + 1) / 2.0      # rows attended, new token included
     abytes = sum(algorithmic_bytes(w, ml, t_avg) for ml in ms) / L        # mean over the layers
     achieved = abytes / (call_us * 1e-6) / 1e9
-    traffic = read_traffic()
+    traffic = read_traffic(w.name, w.compression, "generic" if args.generic else "mfma", args.pyramid)
     res = {
         "metric": "decode attention steps/s + achieved HBM GB/s (% peak) at 60% vision-KV compression",
         "value": K / wall, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -280,13 +298,12 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic["bytes_per_call"] if traffic else None,
-                     "kernel": "kvc_reconstruct_attend_decode (fab_fused or fa_scores + fb_probs, fc_fused, fd_finalize)",
+                     "kernel": "kvc_reconstruct_attend_decode (kernels fab_fused, fc_fused, fd_finalize_few; the scalar "
+                               "kernels with --generic)",
                      "algorithmic_bytes_per_launch": abytes, "us_per_launch": call_us,
                      "us_per_launch_event_pair_each": call_us_pairs,
                      "measured_read_ceiling": read_ceiling},
-        "compress": {"ms_per_layer": comp_ms / (L * copies),
-                     "tflops": 2.0 * w.batch * w.n_kv_heads * w.n_images * (sum(ms) / L)
-                     * w.n_img_tokens * w.head_dim / (comp_ms / (L * copies) * 1e-3) / 1e12},
+        "compress": compress_report(w, ms, comp_ms / (L * copies)),
     }
 
     if full:
