@@ -32,7 +32,11 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
 constexpr int kKT = 64;        // positions per LDS tile
-constexpr int kLD = kKT + 8;   // padded row of the transposed V tile (bf16 elements)
+// Padded row of the LDS tiles in bf16 elements.  Rows 160 bytes apart are the stride at which the
+// 16-byte operand reads of 16 rows meet no bank conflict (measured: 3.5 cycles per wave instruction
+// against 6.0 at 144 bytes); workgroups of at most 128 rows keep 144 bytes, with which two of them fit
+// one compute unit's LDS.
+constexpr int ld_of(int rows) { return rows <= 128 ? kKT + 8 : kKT + 16; }
 constexpr int kMaxRows = 256;  // rows of U per workgroup, at most (LDS: two stages of U and V tiles)
 
 struct CPlan {
@@ -61,7 +65,7 @@ __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, 
 // element (channel c, position p of the tile) of the transposed tile; 16-byte chunks of a row
 // are XOR-swizzled with the index of the channel's 16-row MFMA tile: the transposing stores
 // spread over the banks and the operand reads of one tile stay conflict-free
-__device__ inline int sv_index(int c, int p) { return c * kLD + ((((p >> 3) ^ (c >> 4)) & 7) << 3) + (p & 7); }
+template <int LD> __device__ inline int sv_index(int c, int p) { return c * LD + ((((p >> 3) ^ (c >> 4)) & 7) << 3) + (p & 7); }
 
 
 // NW wavefronts, MT tiles per wavefront: a workgroup covers up to 16 NW MT rows of U, so V is read
@@ -79,8 +83,11 @@ __global__ __launch_bounds__(64 * NW) void fk_compress(CPlan p, const uint16_t *
     constexpr int RP = NT / 16;          // rows (or pairs of positions) one pass of 16 lanes each covers
     constexpr int NV = 512 / NT;         // V tile items (pair of positions, 8 channels) per thread
     constexpr int R = 16 * NW * MT;      // rows of U held by the workgroup
-    __shared__ __align__(16) uint16_t sVt[2][D * kLD];
-    extern __shared__ __align__(16) uint16_t sU[];          // [2][R][kLD] rows of U, 64 positions each
+    constexpr int kLD = ld_of(R);
+    extern __shared__ __align__(16) uint16_t dyn[];
+    uint16_t *const sVt = dyn;                              // [2][D][kLD] V tiles, transposed
+    uint16_t *const sU = dyn + 2 * D * kLD;                 // [2][R][kLD] rows of U, 64 positions each
+    __shared__ int sIdx[kMaxRows];                          // mask entries of the workgroup's rows
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
 
@@ -139,7 +146,7 @@ __global__ __launch_bounds__(64 * NW) void fk_compress(CPlan p, const uint16_t *
         for (int k = 0; k < 2 * MT; ++k) ua[k] = *reinterpret_cast<const u32x4 *>(usrc[k] + kt * kKT);
     };
     auto store_tile = [&](int kt, const u32x4 (&va)[NV][2], const u32x4 (&ua)[2 * MT]) {
-        uint16_t *buf = sVt[kt & 1];
+        uint16_t *buf = sVt + (kt & 1) * (D * kLD);
         uint16_t *ubuf = sU + (kt & 1) * (R * kLD);
         // transposed store: positions (2 pair, 2 pair + 1) of channel c share one 32-bit word
 #pragma unroll
@@ -149,8 +156,8 @@ __global__ __launch_bounds__(64 * NW) void fk_compress(CPlan p, const uint16_t *
             const uint32_t c2[4] = {va[q][1].x, va[q][1].y, va[q][1].z, va[q][1].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                *reinterpret_cast<uint32_t *>(buf + sv_index(8 * cs + 2 * e, pl)) = (a[e] & 0xffffu) | (c2[e] << 16);
-                *reinterpret_cast<uint32_t *>(buf + sv_index(8 * cs + 2 * e + 1, pl)) = (a[e] >> 16) | (c2[e] & 0xffff0000u);
+                *reinterpret_cast<uint32_t *>(buf + sv_index<kLD>(8 * cs + 2 * e, pl)) = (a[e] & 0xffffu) | (c2[e] << 16);
+                *reinterpret_cast<uint32_t *>(buf + sv_index<kLD>(8 * cs + 2 * e + 1, pl)) = (a[e] >> 16) | (c2[e] & 0xffff0000u);
             }
         }
 #pragma unroll
@@ -164,27 +171,27 @@ __global__ __launch_bounds__(64 * NW) void fk_compress(CPlan p, const uint16_t *
     load_tile(min(1, NK - 1), vaY, uaY);
 
     // ---- keys (Sec. 3.1): Kc[u][j][:] = K[b,h, vis0 + i n + M[j], :] for this workgroup's rows j -------
-    // 16 lanes per row, RP rows per pass, 4 MT passes, one pass per step of the projection and three
-    // steps deep: tick t asks for the mask entry of pass t, for the key row of pass t - 1 and stores
-    // the row of pass t - 2, so no wait of the copy is ever exposed.
+    // 16 lanes per row, RP rows per pass, 4 MT passes, one pass per step of the projection: tick t
+    // stores the rows of pass t, requested one step earlier, and requests those of pass t + 1.  The mask
+    // entries sit in LDS (a load that depends on a load would wait in the middle of a step).  Nothing
+    // here is conditional: a pass or a row beyond the workgroup's last repeats the last one (same
+    // source, same destination, same bytes), because a memory operation under a run-time test makes
+    // the compiler wait for every load in flight at the end of the test, the tile prefetch included.
+    constexpr int P = 4 * MT;
     const int rl = threadIdx.x >> 4;
-    const int jend = min(16 * (tile0 + ntile), p.m);
-    int krow = 0;
-    u32x4 kvrow = {0u, 0u, 0u, 0u};
+    const int jlast = min(16 * (tile0 + ntile), p.m) - 1;
+    for (int r = threadIdx.x; r < R; r += NT)
+        sIdx[r] = min(max(idx[min(16 * tile0 + r, jlast)], 0), p.n - 1);      // an index outside the block must not leave it
+    u32x4 kvrow = *(reinterpret_cast<const u32x4 *>(K + blk + static_cast<int64_t>(min(max(idx[min(16 * tile0 + rl, jlast)], 0), p.n - 1)) * p.ss) + cs);
     auto keys_tick = [&](int t) {
-        if (t >= 2 && t - 2 < 4 * MT) {
-            const int j = 16 * tile0 + RP * (t - 2) + rl;
-            if (j < jend) *(reinterpret_cast<u32x4 *>(Kc + (static_cast<size_t>(u) * p.m + j) * D) + cs) = kvrow;
-        }
-        if (t >= 1 && t - 1 < 4 * MT) {
-            const int row = min(max(krow, 0), p.n - 1);         // an index outside the block must not leave it
-            kvrow = *(reinterpret_cast<const u32x4 *>(K + blk + static_cast<int64_t>(row) * p.ss) + cs);
-        }
-        if (t < 4 * MT) krow = idx[min(16 * tile0 + RP * t + rl, p.m - 1)];
+        const int ps = min(t, P - 1), pl = min(t + 1, P - 1);
+        const int j = min(16 * tile0 + RP * ps + rl, jlast);
+        *(reinterpret_cast<u32x4 *>(Kc + (static_cast<size_t>(u) * p.m + j) * D) + cs) = kvrow;
+        kvrow = *(reinterpret_cast<const u32x4 *>(K + blk + static_cast<int64_t>(sIdx[RP * pl + rl]) * p.ss) + cs);
     };
 
     auto step = [&](int kt, u32x4 (&va)[NV][2], u32x4 (&ua)[2 * MT]) {
-        const uint16_t *buf = sVt[kt & 1];
+        const uint16_t *buf = sVt + (kt & 1) * (D * kLD);
         const uint16_t *ubuf = sU + (kt & 1) * (R * kLD);
         // only LDS is handed over here: wait for this wave's LDS stores, then for the other waves.
         // (__syncthreads() would also wait for the global loads in flight.)
@@ -201,7 +208,7 @@ __global__ __launch_bounds__(64 * NW) void fk_compress(CPlan p, const uint16_t *
             for (int q = 0; q < MT; ++q)
                 af[ks][q] = *reinterpret_cast<const bf16x8 *>(ubuf + (16 * (wave + NW * q) + r16) * kLD + 32 * ks + 8 * kg);
         auto vfrag = [&](int f) {       // fragment f = 8 ks + nt
-            return *reinterpret_cast<const bf16x8 *>(buf + sv_index(16 * (f & 7) + r16, 32 * (f >> 3) + 8 * kg));
+            return *reinterpret_cast<const bf16x8 *>(buf + sv_index<kLD>(16 * (f & 7) + r16, 32 * (f >> 3) + 8 * kg));
         };
 #pragma unroll
         for (int f = 0; f < AH; ++f) bq[f] = vfrag(f);
@@ -217,22 +224,27 @@ __global__ __launch_bounds__(64 * NW) void fk_compress(CPlan p, const uint16_t *
                 for (int q = 0; q < MT; ++q)
                     accs[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[f >> 3][q], ones, accs[q], 0, 0, 0);
             }
-            if (f == 3 && kt + 1 < NK) store_tile(kt + 1, va, ua);      // the same for every wave: plain branches
-            if (f == 10 && kt + 3 < NK) load_tile(kt + 3, va, ua);
-            if (f == 12) keys_tick(kt);
+            // past the end: the last tile again, stored where nobody reads it
+            if (f == 3) store_tile(kt + 1, va, ua);
+            if (f == 8) keys_tick(kt);
+            if (f == 10) load_tile(min(kt + 3, NK - 1), va, ua);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
     store_tile(0, vaX, uaX);
     load_tile(min(2, NK - 1), vaX, uaX);
     TSC(1);
-    for (int kt = 0; kt < NK; kt += 2) {
-        if (kt == 2) TSC(2);
+    int kt = 0;
+    for (; kt + 2 <= NK; kt += 2) {                      // no tests inside the loop body
         step(kt, vaY, uaY);
-        if (kt + 1 < NK) step(kt + 1, vaX, uaX);
+        step(kt + 1, vaX, uaX);
+    }
+    if (kt < NK) {
+        step(kt, vaY, uaY);
+        ++kt;
     }
     TSC(4);
-    for (int t = NK; t < 4 * MT + 2; ++t) keys_tick(t);     // passes a short block left over
+    for (; kt < P; ++kt) keys_tick(kt);                  // passes a short block left over
 
     // ---- epilogue: centre, round once, store in the blocked layout -----------------------------------
     // lane holds rows j = j0 + 4 kg + e (e = 0..3) of channel c = 16 nt + r16; accs[e] = sum_p U[j][p]
@@ -267,7 +279,7 @@ __global__ __launch_bounds__(64 * NW) void fk_compress(CPlan p, const uint16_t *
 template <int NW, int MT> bool launch(const CPlan &p, const CompressCall &c)
 {
     static_assert(16 * NW * MT <= kMaxRows, "rows of U per workgroup");
-    const size_t lds = static_cast<size_t>(2) * 16 * NW * MT * kLD * sizeof(uint16_t);
+    const size_t lds = static_cast<size_t>(2) * (D + 16 * NW * MT) * ld_of(16 * NW * MT) * sizeof(uint16_t);
     static bool attr_set[kMaxDevices] = {};
     if (!allow_lds(reinterpret_cast<const void *>(fk_compress<NW, MT>), lds, attr_set)) return false;
     fk_compress<NW, MT><<<p.nproj, 64 * NW, lds, c.stream>>>(
