@@ -96,9 +96,11 @@ __global__ __launch_bounds__(64 * NW) void fk_compress(CPlan p, const uint16_t *
     // image blocks of one head (same U) then share an L2.
     const int bx = blockIdx.x;
     const int wg = p.per_xcd ? (bx & 7) * p.per_xcd + (bx >> 3) : bx;
-    const int u = wg / p.JT, jt = wg - u * p.JT;
-    const int bh = u / p.I, i = u - bh * p.I;
-    const int b = bh / p.Hkv, h = bh - b * p.Hkv;
+    // (logical order: head, batch element, image block, so an XCD's run stays within as few heads as possible)
+    const int lu = wg / p.JT, jt = wg - lu * p.JT;
+    const int hb = lu / p.I, i = lu - hb * p.I;
+    const int h = hb / p.B, b = hb - h * p.B;
+    const int u = (b * p.Hkv + h) * p.I + i;             // the image block's index in the capsule
     const int tile0 = jt * p.TPW, ntile = min(p.TPW, p.tiles - tile0);
     // tile q of this wave is tile0 + wave + NW q; rows beyond the workgroup's share repeat the last
     // row of U and their results are dropped, so the main loop carries no tests
@@ -166,6 +168,37 @@ __global__ __launch_bounds__(64 * NW) void fk_compress(CPlan p, const uint16_t *
             *reinterpret_cast<u32x4 *>(ubuf + row * kLD + 8 * (threadIdx.x & 7)) = ua[k];
         }
     };
+    // The same work in pieces, for spreading it over the MFMA groups of a step: 4 + 2 MT store pieces
+    // (piece e < 4: channels 8 cs + 2 e, 8 cs + 2 e + 1 of the V items; piece 4 + k: row item k of U) and
+    // 2 NV + 2 MT load items.
+    constexpr int NP = 4 + 2 * MT, NL = 2 * NV + 2 * MT;
+    auto store_piece = [&](int kt, const u32x4 (&va)[NV][2], const u32x4 (&ua)[2 * MT], int i) {
+        uint16_t *buf = sVt + (kt & 1) * (D * kLD);
+        uint16_t *ubuf = sU + (kt & 1) * (R * kLD);
+        if (i < 4) {
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                const int pl = 2 * (pair0 + RP * q);
+                const uint32_t a = va[q][0][i], c2 = va[q][1][i];
+                *reinterpret_cast<uint32_t *>(buf + sv_index<kLD>(8 * cs + 2 * i, pl)) = (a & 0xffffu) | (c2 << 16);
+                *reinterpret_cast<uint32_t *>(buf + sv_index<kLD>(8 * cs + 2 * i + 1, pl)) = (a >> 16) | (c2 & 0xffff0000u);
+            }
+        } else {
+            const int k = i - 4;
+            const int row = (static_cast<int>(threadIdx.x) + NT * k) >> 3;
+            *reinterpret_cast<u32x4 *>(ubuf + row * kLD + 8 * (threadIdx.x & 7)) = ua[k];
+        }
+    };
+    auto load_item = [&](int kt, u32x4 (&va)[NV][2], u32x4 (&ua)[2 * MT], int i) {
+        if (i < 2 * NV) {
+            const int q = i >> 1, e = i & 1;
+            const int pp = kt * kKT + 2 * (pair0 + RP * q) + e;
+            va[q][e] = *(reinterpret_cast<const u32x4 *>(vsrc + static_cast<int64_t>(pp) * p.ss) + cs);
+        } else {
+            const int k = i - 2 * NV;
+            ua[k] = *reinterpret_cast<const u32x4 *>(usrc[k] + kt * kKT);
+        }
+    };
     TSC(0);
     load_tile(0, vaX, uaX);
     load_tile(min(1, NK - 1), vaY, uaY);
@@ -190,31 +223,50 @@ __global__ __launch_bounds__(64 * NW) void fk_compress(CPlan p, const uint16_t *
         kvrow = *(reinterpret_cast<const u32x4 *>(K + blk + static_cast<int64_t>(sIdx[RP * pl + rl]) * p.ss) + cs);
     };
 
-    auto step = [&](int kt, u32x4 (&va)[NV][2], u32x4 (&ua)[2 * MT]) {
-        const uint16_t *buf = sVt + (kt & 1) * (D * kLD);
+    // One step = 16 groups of MFMAs (group f: fragment f = 8 ks + nt of V against the MT tiles of U).
+    // On entry the first fragments of tile kt (U for ks = 0, V fragments 0 .. AH-1) are in registers and
+    // tile kt is complete in LDS buffer kt & 1.  Between the groups: the remaining fragments, AH ahead of
+    // their use; tile kt + 1 packed into the other buffer piece by piece; the key rows; the barrier after
+    // group kBar (all of tile kt + 1 stored, all of tile kt read); then the first fragments of tile
+    // kt + 1 and the requests for tile kt + 3.  The order is pinned with scheduling barriers: left alone,
+    // the compiler waits for every fragment right after asking for it.
+#ifndef EXP_AH
+#define EXP_AH 4
+#endif
+    constexpr int AH = EXP_AH, kBar = 11, PRE = 16 - kBar - 1;   // fragments of V in flight ahead; barrier group; fragments preloaded before a step
+    constexpr int F0 = NP <= 10 ? 1 : 0;                 // group of the first store piece
+    constexpr int FL = NP <= 9 ? 10 : 12;                // group of the first tile request
+    constexpr int LPG = (NL + (16 - FL) - 1) / (16 - FL);
+    constexpr int FK = NP <= 8 ? 9 : 13;                 // group of the key rows
+    static_assert(F0 + NP <= kBar + 1 && FL + (NL + LPG - 1) / LPG <= 16, "pieces fit their groups");
+    bf16x8 af[2][MT], bq[16];
+    auto frag_u = [&](int kt, int ks, int q) {
         const uint16_t *ubuf = sU + (kt & 1) * (R * kLD);
-        // only LDS is handed over here: wait for this wave's LDS stores, then for the other waves.
-        // (__syncthreads() would also wait for the global loads in flight.)
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        // The fragments of V are requested a few ahead of the MFMAs that use them (a rolling window
-        // keeps the wave within its registers); the order is pinned, or the compiler waits for every
-        // fragment right after asking for it.
-        constexpr int AH = 4;
+        return *reinterpret_cast<const bf16x8 *>(ubuf + (16 * (wave + NW * q) + r16) * kLD + 32 * ks + 8 * kg);
+    };
+    auto frag_v = [&](int kt, int f) {       // fragment f = 8 ks + nt
+        const uint16_t *buf = sVt + (kt & 1) * (D * kLD);
+        return *reinterpret_cast<const bf16x8 *>(buf + sv_index<kLD>(16 * (f & 7) + r16, 32 * (f >> 3) + 8 * kg));
+    };
+    auto first_fragments = [&](int kt) {
+#pragma unroll
+        for (int q = 0; q < MT; ++q) af[0][q] = frag_u(kt, 0, q);
+    };
+    auto step = [&](int kt, u32x4 (&va)[NV][2], u32x4 (&ua)[2 * MT]) {
         __builtin_amdgcn_sched_barrier(0);
-        bf16x8 af[2][MT], bq[16];
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int q = 0; q < MT; ++q)
-                af[ks][q] = *reinterpret_cast<const bf16x8 *>(ubuf + (16 * (wave + NW * q) + r16) * kLD + 32 * ks + 8 * kg);
-        auto vfrag = [&](int f) {       // fragment f = 8 ks + nt
-            return *reinterpret_cast<const bf16x8 *>(buf + sv_index<kLD>(16 * (f & 7) + r16, 32 * (f >> 3) + 8 * kg));
-        };
-#pragma unroll
-        for (int f = 0; f < AH; ++f) bq[f] = vfrag(f);
 #pragma unroll
         for (int f = 0; f < 16; ++f) {
-            if (f + AH < 16) bq[f + AH] = vfrag(f + AH);
+            if (f == 0) {
+#pragma unroll
+                for (int q = 0; q < MT; ++q) af[1][q] = frag_u(kt, 1, q);
+            }
+            if (f == 0) {
+#pragma unroll
+                for (int g = PRE; g < AH; ++g) bq[g] = frag_v(kt, g);
+            }
+            if (f + AH < 16) bq[f + AH] = frag_v(kt, f + AH);
+            if (f == kBar + 1) first_fragments(kt + 1);
+            if (f > kBar) bq[f - kBar - 1] = frag_v(kt + 1, f - kBar - 1);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int q = 0; q < MT; ++q)
@@ -225,14 +277,28 @@ __global__ __launch_bounds__(64 * NW) void fk_compress(CPlan p, const uint16_t *
                     accs[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[f >> 3][q], ones, accs[q], 0, 0, 0);
             }
             // past the end: the last tile again, stored where nobody reads it
-            if (f == 3) store_tile(kt + 1, va, ua);
-            if (f == 8) keys_tick(kt);
-            if (f == 10) load_tile(min(kt + 3, NK - 1), va, ua);
+            if (f >= F0 && f < F0 + NP) store_piece(kt + 1, va, ua, f - F0);
+            if (f == FK) keys_tick(kt);
+            if (f >= FL) {
+#pragma unroll
+                for (int i = (f - FL) * LPG; i < (f - FL + 1) * LPG; ++i)
+                    if (i < NL) load_item(min(kt + 3, NK - 1), va, ua, i);
+            }
+            // only LDS is handed over: wait for this wave's LDS traffic, then for the other waves
+            // (__syncthreads() would also wait for the global loads in flight)
+            if (f == kBar) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
         }
     };
     store_tile(0, vaX, uaX);
     load_tile(min(2, NK - 1), vaX, uaX);
+    uint16_t mur[8];                                     // the channel means the epilogue needs, requested early
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) mur[nt] = mu[static_cast<size_t>(h) * D + 16 * nt + r16];
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    first_fragments(0);
+#pragma unroll
+    for (int f = 0; f < PRE; ++f) bq[f] = frag_v(0, f);
     TSC(1);
     int kt = 0;
     for (; kt + 2 <= NK; kt += 2) {                      // no tests inside the loop body
@@ -250,8 +316,7 @@ __global__ __launch_bounds__(64 * NW) void fk_compress(CPlan p, const uint16_t *
     // lane holds rows j = j0 + 4 kg + e (e = 0..3) of channel c = 16 nt + r16; accs[e] = sum_p U[j][p]
     float muc[8];
 #pragma unroll
-    for (int nt = 0; nt < 8; ++nt)
-        muc[nt] = __uint_as_float(static_cast<uint32_t>(mu[static_cast<size_t>(h) * D + 16 * nt + r16]) << 16);
+    for (int nt = 0; nt < 8; ++nt) muc[nt] = __uint_as_float(static_cast<uint32_t>(mur[nt]) << 16);
 #pragma unroll
     for (int q = 0; q < MT; ++q) {
         if (wave + NW * q >= ntile) continue;
