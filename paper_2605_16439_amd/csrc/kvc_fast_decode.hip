@@ -159,10 +159,135 @@ __global__ __launch_bounds__(256) void fa_scores(const uint16_t *__restrict__ q,
 }
 
 // ------------------------------------------------------------------------------------------
+// Pieces of Alg. 1 step 2 shared by fb_probs and fab_fused (which runs them behind its own first
+// phase): L[r][pos] = sum_j S[r][j] theta[j][pos] for one tile of 16 NW rows x 64 positions, then
+// P = exp(L - tile max).  MFMA tile: A = theta^T (16 positions x 32 j) from LDS, B = S^T (32 j x 16
+// rows) from memory, D[pos][row]: a lane ends up with 4 consecutive positions of one row.
+// ------------------------------------------------------------------------------------------
+// The theta chunk [m x 64 positions] goes to LDS transposed (ThT[pos][j], rows LDT apart).  A thread
+// owns a pair of consecutive rows j, j+1 and 8 positions; the pair is packed so the transposed store
+// is one 32-bit word per position.
+template <int KS4, int NW> struct ThetaChunk {
+    static constexpr int RPP = 16 * NW;              // rows of theta per pass of the workgroup
+    static constexpr int FB = 128 * KS4 / RPP;       // passes of RPP rows: RPP FB >= m_pad, all in one batch
+    u32x4 tv[FB][2];
+    int seg, j0;                                      // 16-byte segment of the chunk row; first row of the pair
+
+    __device__ __forceinline__ void request(const Plan &p, const uint16_t *__restrict__ theta, int h, int pc, int wave, int lane)
+    {
+        seg = (lane >> 4) + 4 * (wave & 1);
+        j0 = 2 * ((lane & 15) + 16 * (wave >> 1));
+        const uint16_t *th = theta + static_cast<size_t>(h) * p.m * p.n + pc * kPC + 8 * seg;
+#pragma unroll
+        for (int k = 0; k < FB; ++k)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                // no run-time test around the loads (they would be waited for on the spot): rows beyond m are
+                // clamped to the last one here and replaced by zeros where they are stored
+                const int j = j0 + RPP * k + e;
+                tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(min(j, p.m - 1)) * p.n);
+            }
+    }
+
+    __device__ __forceinline__ void store(const Plan &p, uint16_t *ThT, int LDT) const
+    {
+#pragma unroll
+        for (int k = 0; k < FB; ++k) {
+            const int j = j0 + RPP * k;
+            if (j < p.m16) {
+                const uint32_t ka = j < p.m ? 0xffffffffu : 0u, kc = j + 1 < p.m ? 0xffffffffu : 0u;
+                const uint32_t a[4] = {tv[k][0].x & ka, tv[k][0].y & ka, tv[k][0].z & ka, tv[k][0].w & ka};
+                const uint32_t c[4] = {tv[k][1].x & kc, tv[k][1].y & kc, tv[k][1].z & kc, tv[k][1].w & kc};
+                uint32_t *dst = reinterpret_cast<uint32_t *>(ThT + (8 * seg) * LDT + j);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    dst[(2 * e) * (LDT / 2)] = (a[e] & 0xffffu) | (c[e] << 16);
+                    dst[(2 * e + 1) * (LDT / 2)] = (a[e] >> 16) | (c[e] & 0xffff0000u);
+                }
+            }
+        }
+        // zero the k padding of the transposed chunk: columns [m16, m_pad)
+        const int padc = p.m_pad - p.m16;
+        for (int idx = threadIdx.x; idx < kPC * padc; idx += 64 * NW) {
+            const int pp = idx / padc, j = p.m16 + idx - pp * padc;
+            ThT[pp * LDT + j] = 0;
+        }
+    }
+};
+
+// The scores of row r as MFMA B fragments, KS = m_pad / 32 k-steps of 32 compressed positions handled
+// as KS4 groups of four without any test inside the loops.  A step of the last group that lies beyond
+// KS re-reads the last step and is masked where it is used: loads under a run-time test, even a
+// uniform one, made the compiler wait for each of them in turn and shuttle the fragments through
+// accumulator registers when KS4 = 2; an assignment of zeros under a test lets the compiler move the
+// load under the test again.  Every lane loads, also in a wave whose rows lie beyond R: they exist in
+// the workspace up to R_pad, and nothing of such a wave is stored.
+template <int KS4> __device__ __forceinline__ void request_scores(u32x4 (&sfr)[4 * KS4], const Plan &p, int h, int r, int kg)
+{
+    constexpr int SB = 4 * KS4;
+    const int KS = p.m_pad / 32;
+    const uint16_t *srow = p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + 8 * kg;
+#pragma unroll
+    for (int k = 0; k < SB; ++k) {
+        sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * (k < SB - 4 ? k : min(k, KS - 1)));
+        // the first eight are requested here: left alone, the instruction scheduler spreads the loads over
+        // the matrix work below, a few at a time, and every one becomes a round trip of its own
+        if (k == (SB < 8 ? SB : 8) - 1) __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// L for the wave's 16 rows x 64 positions, the tile-local softmax numerators in bf16 and the tile's
+// (max, sum) per row; KID names the kernel in the developer timeline.
+template <int KS4, int KID>
+__device__ __forceinline__ void probs_tile(const Plan &p, const uint16_t *ThT, int LDT, const u32x4 (&sfr)[4 * KS4], int h, int r,
+                                           int pc, int r16, int kg)
+{
+    constexpr int SB = 4 * KS4, PC = kPC;
+    const int KS = p.m_pad / 32;
+    f32x4 acc[PC / 16];
+#pragma unroll
+    for (int mt = 0; mt < PC / 16; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < SB; ++k) {
+        const int ks = min(k, KS - 1);
+        // scores beyond the compressed length are zeros written with the scores
+        const uint32_t keep = (k < SB - 4 || k < KS) ? 0xffffffffu : 0u;
+        const bf16x8 bfrag = as_bf16x8(u32x4_mk(sfr[k].x & keep, sfr[k].y & keep, sfr[k].z & keep, sfr[k].w & keep));
+#pragma unroll
+        for (int mt = 0; mt < PC / 16; ++mt) {
+            const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(ThT + (16 * mt + r16) * LDT + 32 * ks + 8 * kg);
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[mt], 0, 0, 0);
+        }
+    }
+
+    TS(KID, 3);
+    // ---- tile-local softmax numerators of row r over the 64 positions ------------------------------
+    float mx = -INFINITY;
+#pragma unroll
+    for (int mt = 0; mt < PC / 16; ++mt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mx = fmaxf(mx, acc[mt][e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float sum = 0.f;
+    const bool valid = row_valid(p, r);
+    uint16_t *prow = p.P + (static_cast<size_t>(h) * p.R_pad + r) * p.n + pc * PC + 4 * kg;
+#pragma unroll
+    for (int mt = 0; mt < PC / 16; ++mt) {
+        const uint32_t a0 = f32_to_bf16_bits(__expf(acc[mt][0] - mx)), a1 = f32_to_bf16_bits(__expf(acc[mt][1] - mx));
+        const uint32_t a2 = f32_to_bf16_bits(__expf(acc[mt][2] - mx)), a3 = f32_to_bf16_bits(__expf(acc[mt][3] - mx));
+        sum += __uint_as_float(a0 << 16) + __uint_as_float(a1 << 16) + __uint_as_float(a2 << 16) + __uint_as_float(a3 << 16);
+        if (valid) *reinterpret_cast<u32x2 *>(prow + 16 * mt) = u32x2_mk(a0 | (a1 << 16), a2 | (a3 << 16));
+    }
+    sum += __shfl_xor(sum, 16, 64);
+    sum += __shfl_xor(sum, 32, 64);
+    if (kg == 0 && valid) p.stats[(static_cast<size_t>(h) * p.R_pad + r) * p.NC + pc] = f32x2_mk(mx, sum);
+    TS(KID, 4);
+}
+
+// ------------------------------------------------------------------------------------------
 // fb_probs: Alg. 1 step 2 and the numerator of the softmax for one tile of 16 NW rows x 64
-// positions (NW waves, one 16-row MFMA tile each): L[r][pos] = sum_j S[r][j] theta[j][pos], P = exp(L - tile max).
-// MFMA tile: A = theta^T (16 positions x 32 j) from LDS, B = S^T (32 j x 16 rows) from
-// memory, D[pos][row]: a lane ends up with 4 consecutive positions of one row.
+// positions (NW waves, one 16-row MFMA tile each), from the pieces above.
 // ------------------------------------------------------------------------------------------
 // The leading arguments repeat what stands in front of the first loads (14 dwords: the hardware
 // hands them to every wave in registers at its start); the rest of the plan is fetched behind them.
@@ -195,113 +320,18 @@ __global__ __launch_bounds__(64 * NW) void fb_probs(const uint16_t *__restrict__
     const int r0 = rb * (16 * NW) + wave * 16;
     const bool wave_live = r0 < p.R;
     const int r = r0 + r16;
-    const uint16_t *srow = p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + 8 * kg;
-    // KS = m_pad / 32 k-steps of 32 compressed positions, handled as KS4 groups of four without any
-    // test inside the loops: a step beyond KS multiplies a re-read theta fragment by a zero fragment
-    const int KS = p.m_pad / 32;
-    constexpr int SB = 4 * KS4;
-    u32x4 sfr[SB];
-    // (a step of the last group that lies beyond KS re-reads the last step and is masked where it is
-    // used: loads under a run-time test, even a uniform one, made the compiler wait for each of them in
-    // turn and shuttle the fragments through accumulator registers when KS4 = 2; an assignment of
-    // zeros under a test lets the compiler move the load under the test again.)  Every lane loads,
-    // also in a wave whose rows lie beyond R: they exist in the workspace up to R_pad, and nothing of
-    // such a wave is stored.
-#pragma unroll
-    for (int k = 0; k < SB; ++k) {
-        sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * (k < SB - 4 ? k : min(k, KS - 1)));
-        // the first eight are requested here: left alone, the instruction scheduler spreads the loads over
-        // the matrix work below, a few at a time, and every one becomes a round trip of its own
-        if (k == (SB < 8 ? SB : 8) - 1) __builtin_amdgcn_sched_barrier(0);
-    }
+    u32x4 sfr[4 * KS4];
+    request_scores<KS4>(sfr, p, h, r, kg);
 
     TS(1, 1);
-    // ---- stage the theta chunk, transposed, in LDS -------------------------------------------------
-    // a thread owns a pair of consecutive rows j, j+1 and 8 positions; the pair is packed so the
-    // transposed store is one 32-bit word per position
-    constexpr int RPP = 16 * NW;                           // rows of theta per pass of the workgroup
-    const int seg = (lane >> 4) + 4 * (wave & 1);          // 16-byte segment of the chunk row
-    const int jp = (lane & 15) + 16 * (wave >> 1);         // row pair within a pass of RPP rows
-    {
-        const uint16_t *th = theta + static_cast<size_t>(h) * p.m * p.n + pc * PC + 8 * seg;
-        constexpr int FB = 128 * KS4 / RPP;      // passes of RPP rows: RPP FB >= m_pad, all in one batch
-        const int j0 = 2 * jp;
-        u32x4 tv[FB][2];
-#pragma unroll
-        for (int k = 0; k < FB; ++k)
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                // no run-time test around the loads (they would be waited for on the spot): rows beyond m are
-                // clamped to the last one here and replaced by zeros where they are stored
-                const int j = j0 + RPP * k + e;
-                tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(min(j, p.m - 1)) * p.n);
-            }
-        fetch_now(p.m16, p.P, p.stats);
-#pragma unroll
-        for (int k = 0; k < FB; ++k) {
-            const int j = j0 + RPP * k;
-            if (j < p.m16) {
-                const uint32_t ka = j < p.m ? 0xffffffffu : 0u, kc = j + 1 < p.m ? 0xffffffffu : 0u;
-                const uint32_t a[4] = {tv[k][0].x & ka, tv[k][0].y & ka, tv[k][0].z & ka, tv[k][0].w & ka};
-                const uint32_t c[4] = {tv[k][1].x & kc, tv[k][1].y & kc, tv[k][1].z & kc, tv[k][1].w & kc};
-                uint32_t *dst = reinterpret_cast<uint32_t *>(ThT + (8 * seg) * LDT + j);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    dst[(2 * e) * (LDT / 2)] = (a[e] & 0xffffu) | (c[e] << 16);
-                    dst[(2 * e + 1) * (LDT / 2)] = (a[e] >> 16) | (c[e] & 0xffff0000u);
-                }
-            }
-        }
-        // zero the k padding of the transposed chunk: columns [m16, m_pad)
-        const int padc = p.m_pad - p.m16;
-        for (int idx = threadIdx.x; idx < PC * padc; idx += 64 * NW) {
-            const int pp = idx / padc, j = p.m16 + idx - pp * padc;
-            ThT[pp * LDT + j] = 0;
-        }
-    }
+    ThetaChunk<KS4, NW> th;
+    th.request(p, theta, h, pc, wave, lane);
+    fetch_now(p.m16, p.P, p.stats);
+    th.store(p, ThT, LDT);
     __syncthreads();
     TS(1, 2);
     if (!wave_live) return;
-
-    f32x4 acc[PC / 16];
-#pragma unroll
-    for (int mt = 0; mt < PC / 16; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int k = 0; k < SB; ++k) {
-        const int ks = min(k, KS - 1);
-        // scores beyond the compressed length are zeros written by fa_scores
-        const uint32_t keep = (k < SB - 4 || k < KS) ? 0xffffffffu : 0u;
-        const bf16x8 bfrag = as_bf16x8(u32x4_mk(sfr[k].x & keep, sfr[k].y & keep, sfr[k].z & keep, sfr[k].w & keep));
-#pragma unroll
-        for (int mt = 0; mt < PC / 16; ++mt) {
-            const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(ThT + (16 * mt + r16) * LDT + 32 * ks + 8 * kg);
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[mt], 0, 0, 0);
-        }
-    }
-
-    TS(1, 3);
-    // ---- tile-local softmax numerators of row r over the 64 positions ------------------------------
-    float mx = -INFINITY;
-#pragma unroll
-    for (int mt = 0; mt < PC / 16; ++mt)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) mx = fmaxf(mx, acc[mt][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    float sum = 0.f;
-    const bool valid = row_valid(p, r);
-    uint16_t *prow = p.P + (static_cast<size_t>(h) * p.R_pad + r) * p.n + pc * PC + 4 * kg;
-#pragma unroll
-    for (int mt = 0; mt < PC / 16; ++mt) {
-        const uint32_t a0 = f32_to_bf16_bits(__expf(acc[mt][0] - mx)), a1 = f32_to_bf16_bits(__expf(acc[mt][1] - mx));
-        const uint32_t a2 = f32_to_bf16_bits(__expf(acc[mt][2] - mx)), a3 = f32_to_bf16_bits(__expf(acc[mt][3] - mx));
-        sum += __uint_as_float(a0 << 16) + __uint_as_float(a1 << 16) + __uint_as_float(a2 << 16) + __uint_as_float(a3 << 16);
-        if (valid) *reinterpret_cast<u32x2 *>(prow + 16 * mt) = u32x2_mk(a0 | (a1 << 16), a2 | (a3 << 16));
-    }
-    sum += __shfl_xor(sum, 16, 64);
-    sum += __shfl_xor(sum, 32, 64);
-    if (kg == 0 && valid) p.stats[(static_cast<size_t>(h) * p.R_pad + r) * p.NC + pc] = f32x2_mk(mx, sum);
-    TS(1, 4);
+    probs_tile<KS4, 1>(p, ThT, LDT, sfr, h, r, pc, r16, kg);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -401,61 +431,23 @@ __global__ __launch_bounds__(256) void fab_fused(const uint16_t *__restrict__ Kc
     uint16_t *ThT = lds;                 // [PC][LDT]   theta chunk, transposed: ThT[pos][j]
 
     TS(1, 1);
-    // ---- stage the theta chunk, transposed, in LDS -------------------------------------------------
-    // a thread owns a pair of consecutive rows j, j+1 and 8 positions; the pair is packed so the
-    // transposed store is one 32-bit word per position
-    constexpr int RPP = 16 * NW;                           // rows of theta per pass of the workgroup
-    const int seg = (lane >> 4) + 4 * (wave & 1);          // 16-byte segment of the chunk row
-    const int jp = (lane & 15) + 16 * (wave >> 1);         // row pair within a pass of RPP rows
-    {
-        const uint16_t *th = theta + static_cast<size_t>(h) * p.m * p.n + pc * PC + 8 * seg;
-        constexpr int FB = 128 * KS4 / RPP;      // passes of RPP rows: RPP FB >= m_pad, all in one batch
-        const int j0 = 2 * jp;
-        u32x4 tv[FB][2];
+    // the theta chunk is requested before the score tiles are multiplied and stored to LDS after them
+    ThetaChunk<KS4, NW> th;
+    th.request(p, theta, h, pc, wave, lane);
+    fetch_now(p.m16, p.P, p.stats, p.S, p.scale, p.R_pad, p.R, p.RV, p.epoch, p.wait_ticks, p.fallbacks);
+    // thread 0 raises the pair's counter word to this call's epoch (behind the loads above, so that it does
+    // not stand in front of them; measured: 0.3 us per call better here than next to the wait below)
+    if (threadIdx.x == 0) ctr_claim(flag, p.epoch);
+    // S tiles of this wave
 #pragma unroll
-        for (int k = 0; k < FB; ++k)
+    for (int tq = 0; tq < TQ; ++tq) {
+        f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                // no run-time test around the loads (they would be waited for on the spot): rows beyond m are
-                // clamped to the last one here and replaced by zeros where they are stored
-                const int j = j0 + RPP * k + e;
-                tv[k][e] = *reinterpret_cast<const u32x4 *>(th + static_cast<size_t>(min(j, p.m - 1)) * p.n);
-            }
-        fetch_now(p.m16, p.P, p.stats, p.S, p.scale, p.R_pad, p.R, p.RV, p.epoch, p.wait_ticks, p.fallbacks);
-        // thread 0 raises the pair's counter word to this call's epoch (behind the loads above, so that it does
-        // not stand in front of them; measured: 0.3 us per call better here than next to the wait below)
-        if (threadIdx.x == 0) ctr_claim(flag, p.epoch);
-        // S tiles of this wave
-#pragma unroll
-        for (int tq = 0; tq < TQ; ++tq) {
-            f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[tq][ks]), as_bf16x8(qf[tq][ks]), sacc, 0, 0, 0);
-            if (t_live[tq]) store_tile(sacc, t_ub[tq], t_jt[tq]);
-        }
-#pragma unroll
-        for (int k = 0; k < FB; ++k) {
-            const int j = j0 + RPP * k;
-            if (j < p.m16) {
-                const uint32_t ka = j < p.m ? 0xffffffffu : 0u, kc = j + 1 < p.m ? 0xffffffffu : 0u;
-                const uint32_t a[4] = {tv[k][0].x & ka, tv[k][0].y & ka, tv[k][0].z & ka, tv[k][0].w & ka};
-                const uint32_t c[4] = {tv[k][1].x & kc, tv[k][1].y & kc, tv[k][1].z & kc, tv[k][1].w & kc};
-                uint32_t *dst = reinterpret_cast<uint32_t *>(ThT + (8 * seg) * LDT + j);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    dst[(2 * e) * (LDT / 2)] = (a[e] & 0xffffu) | (c[e] << 16);
-                    dst[(2 * e + 1) * (LDT / 2)] = (a[e] >> 16) | (c[e] & 0xffff0000u);
-                }
-            }
-        }
-        // zero the k padding of the transposed chunk: columns [m16, m_pad)
-        const int padc = p.m_pad - p.m16;
-        for (int idx = threadIdx.x; idx < PC * padc; idx += 64 * NW) {
-            const int pp = idx / padc, j = p.m16 + idx - pp * padc;
-            ThT[pp * LDT + j] = 0;
-        }
+        for (int ks = 0; ks < 4; ++ks)
+            sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kf[tq][ks]), as_bf16x8(qf[tq][ks]), sacc, 0, 0, 0);
+        if (t_live[tq]) store_tile(sacc, t_ub[tq], t_jt[tq]);
     }
+    th.store(p, ThT, LDT);
     // every wave's stores of S (and thread 0's claim of the counter word) have been acknowledged by the L2
     // before the counter moves
     __shared__ int sAlone;
@@ -503,71 +495,12 @@ __global__ __launch_bounds__(256) void fab_fused(const uint16_t *__restrict__ Kc
     }
     asm volatile("buffer_inv sc0" ::: "memory");
     TS(1, 2);
-    // scores of this wave's 16 rows: first batch of fragments in flight during the LDS fill
     const int r0 = rb * (16 * NW) + wave * 16;
-    const bool wave_live = r0 < p.R;
     const int r = r0 + r16;
-    const uint16_t *srow = p.S + (static_cast<size_t>(h) * p.R_pad + r) * p.m_pad + 8 * kg;
-    // KS = m_pad / 32 k-steps of 32 compressed positions, handled as KS4 groups of four without any
-    // test inside the loops: a step beyond KS multiplies a re-read theta fragment by a zero fragment
-    const int KS = p.m_pad / 32;
-    constexpr int SB = 4 * KS4;
-    u32x4 sfr[SB];
-    // (a step of the last group that lies beyond KS re-reads the last step and is masked where it is
-    // used: loads under a run-time test, even a uniform one, made the compiler wait for each of them in
-    // turn and shuttle the fragments through accumulator registers when KS4 = 2; an assignment of
-    // zeros under a test lets the compiler move the load under the test again.)  Every lane loads,
-    // also in a wave whose rows lie beyond R: they exist in the workspace up to R_pad, and nothing of
-    // such a wave is stored.
-#pragma unroll
-    for (int k = 0; k < SB; ++k) {
-        sfr[k] = *reinterpret_cast<const u32x4 *>(srow + 32 * (k < SB - 4 ? k : min(k, KS - 1)));
-        // the first eight are requested here: left alone, the instruction scheduler spreads the loads over
-        // the matrix work below, a few at a time, and every one becomes a round trip of its own
-        if (k == (SB < 8 ? SB : 8) - 1) __builtin_amdgcn_sched_barrier(0);
-    }
-
-    if (!wave_live) return;
-
-    f32x4 acc[PC / 16];
-#pragma unroll
-    for (int mt = 0; mt < PC / 16; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int k = 0; k < SB; ++k) {
-        const int ks = min(k, KS - 1);
-        // scores beyond the compressed length are zeros written by fa_scores
-        const uint32_t keep = (k < SB - 4 || k < KS) ? 0xffffffffu : 0u;
-        const bf16x8 bfrag = as_bf16x8(u32x4_mk(sfr[k].x & keep, sfr[k].y & keep, sfr[k].z & keep, sfr[k].w & keep));
-#pragma unroll
-        for (int mt = 0; mt < PC / 16; ++mt) {
-            const bf16x8 afrag = *reinterpret_cast<const bf16x8 *>(ThT + (16 * mt + r16) * LDT + 32 * ks + 8 * kg);
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(afrag, bfrag, acc[mt], 0, 0, 0);
-        }
-    }
-
-    TS(1, 3);
-    // ---- tile-local softmax numerators of row r over the 64 positions ------------------------------
-    float mx = -INFINITY;
-#pragma unroll
-    for (int mt = 0; mt < PC / 16; ++mt)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) mx = fmaxf(mx, acc[mt][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    float sum = 0.f;
-    const bool valid = row_valid(p, r);
-    uint16_t *prow = p.P + (static_cast<size_t>(h) * p.R_pad + r) * p.n + pc * PC + 4 * kg;
-#pragma unroll
-    for (int mt = 0; mt < PC / 16; ++mt) {
-        const uint32_t a0 = f32_to_bf16_bits(__expf(acc[mt][0] - mx)), a1 = f32_to_bf16_bits(__expf(acc[mt][1] - mx));
-        const uint32_t a2 = f32_to_bf16_bits(__expf(acc[mt][2] - mx)), a3 = f32_to_bf16_bits(__expf(acc[mt][3] - mx));
-        sum += __uint_as_float(a0 << 16) + __uint_as_float(a1 << 16) + __uint_as_float(a2 << 16) + __uint_as_float(a3 << 16);
-        if (valid) *reinterpret_cast<u32x2 *>(prow + 16 * mt) = u32x2_mk(a0 | (a1 << 16), a2 | (a3 << 16));
-    }
-    sum += __shfl_xor(sum, 16, 64);
-    sum += __shfl_xor(sum, 32, 64);
-    if (kg == 0 && valid) p.stats[(static_cast<size_t>(h) * p.R_pad + r) * p.NC + pc] = f32x2_mk(mx, sum);
-    TS(1, 4);
+    u32x4 sfr[4 * KS4];
+    request_scores<KS4>(sfr, p, h, r, kg);
+    if (r0 >= p.R) return;
+    probs_tile<KS4, 1>(p, ThT, LDT, sfr, h, r, pc, r16, kg);
 }
 
 // ------------------------------------------------------------------------------------------
