@@ -57,5 +57,27 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+PROBES = ["l2_fill_probe.hip", "lds_stride_probe.hip"]
+
+
+def build_probes() -> list:
+    """Compile the standalone measurement aids under csrc/probes/ into paper_2605_16439_amd/probes_bin/."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out_dir = os.path.join(HERE, "probes_bin")
+    os.makedirs(out_dir, exist_ok=True)
+    outs = []
+    for src in PROBES:
+        out = os.path.join(out_dir, src.replace(".hip", ""))
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+               "-packed-fp32-ops", os.path.join(CSRC, "probes", src), "-o", out]
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed on %s:\n%s" % (src, r.stdout.decode()))
+        outs.append(out)
+    return outs
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose="-v" in sys.argv))
+    if "--probes" in sys.argv:
+        print("\n".join(build_probes()))
