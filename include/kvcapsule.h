@@ -169,8 +169,10 @@ kvc_status kvc_reconstruct_attend_decode(const kvc_shape *shape, const kvc_param
  *  n_images, text_len in: DEVICE arrays [B] of int32; the host cannot see their values, so they are
  *             clamped on the device to [0, I] and [0, text_cap] ([0, text_cap - 1] with a new token).
  *             A sequence left with no key at all gets NaNs.
- * Everything else as in kvc_reconstruct_attend_decode.  Runs on the shape-agnostic scalar kernels (all
- * dtypes and shapes; far below the matrix-core kernels' speed).
+ * Everything else as in kvc_reconstruct_attend_decode, the kernels included (matrix cores for the shapes
+ * that have them; a uniform batch gives the uniform call's result bit for bit).  Capsule slots beyond
+ * n_images[b] may be read but never reach the result, whatever they hold (NaNs included); text rows
+ * beyond the sequence's own are not read.
  * Errors: as kvc_reconstruct_attend_decode, plus NULL / misaligned count arrays, text_cap < 1. */
 kvc_status kvc_reconstruct_attend_decode_ragged(const kvc_shape *shape, const kvc_params *params,
                                                 const void *q, const void *Kc, const void *Vc,

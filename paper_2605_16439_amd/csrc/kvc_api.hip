@@ -269,7 +269,7 @@ kvc_status kvc_reconstruct_attend_decode_ragged(const kvc_shape *shape, const kv
     if (st != KVC_OK) return st;
     c.n_images_dev = n_images;
     c.text_len_dev = text_len;
-    return generic_decode(c);
+    return dispatch_decode(c);
 }
 
 kvc_status kvc_static_attend_decode(const kvc_shape *shape, const void *q, const void *Kc, const void *Vc,

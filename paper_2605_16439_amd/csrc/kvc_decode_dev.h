@@ -45,6 +45,9 @@ struct Plan {
     int ntext_c;                    // fc_fused: text workgroups (the highest ids)
     int UP, NT, NG, JS, NXC, nparts, rec;
     int merge, nvp;                 // one part per workgroup (its image blocks merged); vision parts per (b, head)
+    // ragged batch (kernels instantiated with RAG = true): n_img[b] image blocks, tlen[b] text rows before the
+    // call; I, t and t_in are then the largest values a sequence may have.  Null in a uniform call.
+    const int32_t *n_img, *tlen;
     int nvis_b, nvis_c;
     // multipliers for the divisions by NXC, Hkv, tiles_per_unit, I, NC, JS and G (see quot())
     unsigned qNXC, qHkv, qTPU, qI, qNC, qJS, qG;
@@ -145,11 +148,11 @@ __device__ inline bool row_valid(const Plan &p, int r) { return (r & 63) < p.RV 
 // ------------------------------------------------------------------------------------------
 constexpr size_t kTextLds = (16 * kSWLD + D * kLDV) * sizeof(uint16_t) + 2 * 4 * 16 * sizeof(float);
 
-// GT: the group size, or 0 to take it from the plan.  tid: the thread's index within the four waves
+// GT: the group size, or 0 to take it from the plan.  RAG: per-sequence text lengths (ragged batch).  tid: the thread's index within the four waves
 // that work on this chunk (a workgroup of eight waves runs two chunks side by side, each half with
 // its own `lds`; both halves meet the same barriers).  live = false: the chunk is a stand-in that
 // keeps a half in step with the other one's barriers; nothing is stored.
-template <int GT>
+template <int GT, bool RAG>
 __device__ __forceinline__ void text_part(const Plan &p, const uint16_t *__restrict__ q, uint16_t *__restrict__ Kt,
                                           uint16_t *__restrict__ Vt, const uint16_t *__restrict__ k_new,
                                           const uint16_t *__restrict__ v_new, uint16_t *lds, const int id,
@@ -157,7 +160,7 @@ __device__ __forceinline__ void text_part(const Plan &p, const uint16_t *__restr
 {
     const int G = GT ? GT : p.G;
     fetch_now(p.qNXC, p.NXC, p.qHkv, p.Hkv, p.Hq, p.t, p.t_in, p.cap, q, Kt, Vt, k_new, v_new, p.scale, p.Ypart, p.nparts,
-              p.nvp, p.rec);
+              p.nvp, p.rec, p.tlen);
     const int wave = tid >> 6, lane = tid & 63;
     const int r16 = lane & 15, kg = lane >> 4;
     // ---------------- text rows: one chunk of kXC rows of one (batch, KV head) ----------------
@@ -166,8 +169,18 @@ __device__ __forceinline__ void text_part(const Plan &p, const uint16_t *__restr
     float (*sRed)[4][16] = reinterpret_cast<float (*)[4][16]>(lds + 16 * kSWLD + D * kLDV);   // per-wave maxima / sums per head
     const int bh = quot(id, p.qNXC), xc = id - bh * p.NXC;
     const int b = quot(bh, p.qHkv), h = bh - b * p.Hkv;
-    const int lo = xc * kXC, hi = min(p.t, lo + kXC);
     const bool fresh = k_new != nullptr;                       // row t_in comes from k_new / v_new
+    // this sequence's rows: t_in before the call (the new token goes there), t attended
+    // (RAG: a ragged batch, the sequence's own count is read; otherwise the call's values, at no cost)
+    int t_in = p.t_in, t = p.t;
+    if constexpr (RAG) {
+        const int tlb = max(p.tlen[b], 0);
+        t_in = min(tlb, p.t_in);
+        t = fresh ? t_in + 1 : min(tlb, p.t);
+    }
+    // a chunk beyond the sequence's rows keeps lo = hi: every load is clamped to a valid row, every logit masked
+    const int lo = xc * kXC, hi = max(min(t, lo + kXC), lo);
+    const int xlast = max(min(hi, t) - 1, 0);                 // the last row the chunk (or, if it is empty, the sequence) has
     // value rows of the chunk (16 lanes per row, a lane takes pairs of consecutive rows) and key
     // rows of this wave's two 16-row tiles
     const int rowl = wave * 4 + kg, cs = r16;
@@ -176,15 +189,15 @@ __device__ __forceinline__ void text_part(const Plan &p, const uint16_t *__restr
     for (int it = 0; it < kXC / 32; ++it)
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-            const int x = min(lo + 2 * (rowl + 16 * it) + e, hi - 1);
-            const uint16_t *vrow = (fresh && x == p.t_in) ? v_new + static_cast<size_t>(bh) * D
+            const int x = min(lo + 2 * (rowl + 16 * it) + e, xlast);
+            const uint16_t *vrow = (fresh && x == t_in) ? v_new + static_cast<size_t>(bh) * D
                                                           : Vt + (static_cast<size_t>(bh) * p.cap + x) * D;
             vb[it][e] = *(reinterpret_cast<const u32x4 *>(vrow) + cs);
         }
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-        const int x = min(lo + 32 * wave + 16 * tt + r16, hi - 1);
-        const uint16_t *krow = (fresh && x == p.t_in) ? k_new + static_cast<size_t>(bh) * D
+        const int x = min(lo + 32 * wave + 16 * tt + r16, xlast);
+        const uint16_t *krow = (fresh && x == t_in) ? k_new + static_cast<size_t>(bh) * D
                                                       : Kt + (static_cast<size_t>(bh) * p.cap + x) * D;
         const u32x4 *kp = reinterpret_cast<const u32x4 *>(krow) + kg;
 #pragma unroll
@@ -229,13 +242,14 @@ __device__ __forceinline__ void text_part(const Plan &p, const uint16_t *__restr
     TS(0, 2);
     // probabilities relative to the chunk's own maximum, straight from the accumulator layout
     mx = fmaxf(fmaxf(sRed[0][0][r16], sRed[0][1][r16]), fmaxf(sRed[0][2][r16], sRed[0][3][r16]));
+    const float mref = mx == -INFINITY ? 0.f : mx;             // an empty chunk: all weights zero, no inf - inf
     float sm = 0.f;
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
         uint32_t eb[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            eb[e] = f32_to_bf16_bits(__expf(sc[tt][e] - mx));       // exp(-inf) = 0 beyond the chunk
+            eb[e] = f32_to_bf16_bits(__expf(sc[tt][e] - mref));     // exp(-inf) = 0 beyond the chunk
             sm += __uint_as_float(eb[e] << 16);
         }
         *reinterpret_cast<u32x2 *>(&sWb[r16][32 * wave + 16 * tt + 4 * kg]) = u32x2_mk(eb[0] | (eb[1] << 16), eb[2] | (eb[3] << 16));
@@ -264,10 +278,10 @@ __device__ __forceinline__ void text_part(const Plan &p, const uint16_t *__restr
         yp[G * D + G + tid] = sRed[1][0][tid] + sRed[1][1][tid] + sRed[1][2][tid] + sRed[1][3][tid];
     }
     // Sec. 3.2: the text cache keeps growing as in the backbone -- store the new token's k, v
-    if (fresh && live && p.t_in >= lo && p.t_in < hi && tid < 32) {
+    if (fresh && live && t_in >= lo && t_in < hi && tid < 32) {
         const int half = tid >> 4, piece = tid & 15;
         const uint16_t *src = (half ? v_new : k_new) + static_cast<size_t>(bh) * D;
-        uint16_t *dst = (half ? Vt : Kt) + (static_cast<size_t>(bh) * p.cap + p.t_in) * D;
+        uint16_t *dst = (half ? Vt : Kt) + (static_cast<size_t>(bh) * p.cap + t_in) * D;
         *(reinterpret_cast<u32x4 *>(dst) + piece) = *(reinterpret_cast<const u32x4 *>(src) + piece);
     }
     TS(0, 4);

@@ -74,7 +74,7 @@ int g_separate = 0;               // 1: fa_scores and fb_probs as separate launc
 // Part record in Ypart: [G][D] floats of un-normalised output, [G] maxima, [G] sums.
 // ------------------------------------------------------------------------------------------
 // (leading arguments: what stands in front of the first loads, preloaded into registers, see fb_probs)
-template <int G, bool TEXT>
+template <int G, bool TEXT, bool RAG>
 __global__ __launch_bounds__(256) void fa_scores(const uint16_t *__restrict__ q, const uint16_t *__restrict__ Kc,
                                                  int a_vis_tiles, unsigned a_qTPU, int a_tiles_per_unit, unsigned a_qI,
                                                  int a_I, unsigned a_qHkv, int a_Hkv, int a_m, int a_Hq, int a_ntext_a,
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void fa_scores(const uint16_t *__restrict__ q,
     if constexpr (TEXT) {
         if (static_cast<int>(blockIdx.x) < p.ntext_a) {
             __shared__ __align__(16) uint16_t sText[kTextLds / 2];
-            text_part<G>(p, q, Kt, Vt, k_new, v_new, sText, blockIdx.x, threadIdx.x, true);
+            text_part<G, RAG>(p, q, Kt, Vt, k_new, v_new, sText, blockIdx.x, threadIdx.x, true);
             return;
         }
     }
@@ -519,7 +519,7 @@ template <> struct KSplit<9> { static constexpr int KH0 = 6, UCH = 3; };
 template <> struct KSplit<4> { static constexpr int KH0 = 2, UCH = 2; };
 
 // (leading arguments: what stands in front of the first loads, preloaded into registers, see fb_probs)
-template <int G, int UP, int NT, int NC>
+template <int G, int UP, int NT, int NC, bool RAG>
 __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, uint16_t *a_P, f32x2 *a_stats,
                                                 unsigned a_qJS, int a_JS, unsigned a_qHkv, int a_Hkv, int a_B, int a_I,
                                                 int a_m, int a_UPBs, Plan p,
@@ -556,7 +556,7 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
     // The text chunks ride along as the last workgroups (four waves each): they land on the CUs the
     // others leave idle first, and end before the longest of the others does.
     if (static_cast<int>(blockIdx.x) >= p.nvis_c) {
-        if (threadIdx.x < 256) text_part<G>(p, q, Kt, Vt, k_new, v_new, dyn, blockIdx.x - p.nvis_c, threadIdx.x, true);
+        if (threadIdx.x < 256) text_part<G, RAG>(p, q, Kt, Vt, k_new, v_new, dyn, blockIdx.x - p.nvis_c, threadIdx.x, true);
         return;
     }
     TS(2, 0);
@@ -590,6 +590,20 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
 #pragma unroll
         for (int k = 0; k < KP; ++k) pfr[ps][k] = prow[min(16 * k + psub, PCH - 1)];
     }
+    // image blocks a sequence of a ragged batch does not have (block i >= its count): bit un of `present`
+    // is clear; their rows of P and statistics are replaced by "no mass" below and their outputs dropped,
+    // whatever the capsule slot and the earlier kernels left there
+    static_assert(NU <= 64, "one bit per image block of the workgroup");
+    // (a uniform call has them all: the mask is a constant and every test on it folds away)
+    unsigned long long present = ~0ull;
+    if constexpr (RAG) {
+        // lane un of every wave looks its block up; the wave's ballot is the mask
+        const int ub = ub0 + min(lane, nunits - 1);
+        const int b = quot(ub, p.qI), i = ub - b * p.I;
+        present = __ballot(i < p.n_img[b]);
+    }
+    // image block (within the workgroup) of row pr of the workgroup's NR rows
+    auto unit_of = [&](int pr) { return (pr >> 4) * UP + min(pr & 15, UP * G - 1) / G; };
     // tile statistics: lane (kg = MFMA tile, r16 = row) of wave 0 reads one f32x2 per softmax tile
     f32x2 st[NC];
 #pragma unroll
@@ -620,7 +634,7 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
         }
     };
     load_u(0);
-    fetch_now(Vc, p.Ypart, p.nparts, p.rec, p.merge, p.qI);
+    fetch_now(Vc, p.Ypart, p.nparts, p.rec, p.merge, p.qI, p.n_img);
     // compressed values: wave w owns channels 16 w ...; the operand (8 rows j of one channel) is 16
     // contiguous bytes in the blocked layout.  Image blocks are handled in batches of UBATCH.
     constexpr int UBATCH = NU < 4 ? NU : 4;
@@ -688,6 +702,10 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
     TS(2, 1);
     // ---- block statistics: alpha[row][tile] = exp(tile max - block max) ----------------------------------
     if (wave == 0 && kg < NT) {
+        if (!((present >> unit_of(16 * kg + r16)) & 1ull)) {
+#pragma unroll
+            for (int k = 0; k < NC; ++k) st[k] = f32x2_mk(-1e30f, 0.f);
+        }
         float mx = st[0].x;
 #pragma unroll
         for (int k = 1; k < NC; ++k) mx = fmaxf(mx, st[k].x);
@@ -705,8 +723,10 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
     for (int ps = 0; ps < NPASS; ++ps)
         if (prow_i + 32 * ps < NR) {
             u32x4 *dst = reinterpret_cast<u32x4 *>(sP + (prow_i + 32 * ps) * LDP);
+            const unsigned keep = ((present >> unit_of(prow_i + 32 * ps)) & 1ull) ? 0xffffffffu : 0u;
 #pragma unroll
-            for (int k = 0; k < KP; ++k) dst[min(16 * k + psub, PCH - 1)] = pfr[ps][k];   // clamped duplicates carry equal data
+            for (int k = 0; k < KP; ++k)      // clamped duplicates carry equal data
+                dst[min(16 * k + psub, PCH - 1)] = u32x4_mk(pfr[ps][k].x & keep, pfr[ps][k].y & keep, pfr[ps][k].z & keep, pfr[ps][k].w & keep);
         }
     __syncthreads();
     TS(2, 2);
@@ -796,10 +816,14 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
             f32x4 o = {0.f, 0.f, 0.f, 0.f};
             o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur[a][0]), wb[t][0], o, 0, 0, 0);
             o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur[a][1]), wb[t][1], o, 0, 0, 0);
+            const bool here = (present >> un) & 1ull;      // an absent block's values may be anything: selected away, never multiplied
             if (p.merge) {
-                const float w8 = (un_mine == ul2 && r16 < un_lim) ? sc[t] : 0.f;   // rows of other blocks: cross terms
-                ysum[0] += w8 * o[0]; ysum[1] += w8 * o[1]; ysum[2] += w8 * o[2]; ysum[3] += w8 * o[3];
+                const bool mine = un_mine == ul2 && r16 < un_lim && here;          // rows of other blocks: cross terms
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ysum[e] += mine ? sc[t] * o[e] : 0.f;
             } else if (un < nunits && un_mine == ul2 && r16 < un_lim) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = here ? o[e] : 0.f;
                 const int ub = ub0 + un;
                 const int b = quot(ub, p.qI), i = ub - b * p.I;
                 float *yp = p.Ypart + (static_cast<size_t>(b * p.Hkv + h) * p.nparts + i * p.JS + s) * p.rec;
@@ -1021,6 +1045,7 @@ Plan make_plan_layout(const kvc_shape &s, int t, int t_in, int cap, float scale,
     p.B = s.batch; p.Hq = s.n_q_heads; p.Hkv = s.n_kv_heads; p.G = p.Hq / p.Hkv;
     p.n = s.n_img_tokens; p.I = s.n_images; p.m = s.m;
     p.t = t; p.t_in = t_in; p.cap = cap; p.scale = scale;
+    p.n_img = p.tlen = nullptr;
     {
         const int up = units_per_group(p.G), units = p.B * p.I;
         const int upb = up ? (64 / p.G) / (2 * up) * (2 * up) : 1;         // 64, 32, 16 or 8
@@ -1246,35 +1271,43 @@ bool launch_b(const Plan &p, const DecodeCall &c)
     }
 }
 
+template <int G, bool TEXT, bool RAG> void launch_a2(const Plan &p, const DecodeCall &c, int grid)
+{
+    fa_scores<G, TEXT, RAG><<<grid, 256, 0, c.stream>>>(
+        static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc), p.vis_tiles, p.qTPU,
+        p.tiles_per_unit, p.qI, p.I, p.qHkv, p.Hkv, p.m, p.Hq, p.ntext_a, p,
+        static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt),
+        static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new));
+}
+
 template <int G> bool launch_a(const Plan &p, const DecodeCall &c)
 {
     if (p.ntext_a + p.nvis_a == 0) return true;
-    if (p.ntext_a > 0)
-        fa_scores<G, true><<<p.ntext_a + p.nvis_a, 256, 0, c.stream>>>(
-            static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc), p.vis_tiles, p.qTPU,
-            p.tiles_per_unit, p.qI, p.I, p.qHkv, p.Hkv, p.m, p.Hq, p.ntext_a, p,
-            static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt),
-            static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new));
-    else
-        fa_scores<G, false><<<p.nvis_a, 256, 0, c.stream>>>(
-            static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc), p.vis_tiles, p.qTPU,
-            p.tiles_per_unit, p.qI, p.I, p.qHkv, p.Hkv, p.m, p.Hq, p.ntext_a, p,
-            static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt),
-            static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new));
+    if (p.ntext_a > 0) {
+        if (p.tlen) launch_a2<G, true, true>(p, c, p.ntext_a + p.nvis_a);
+        else launch_a2<G, true, false>(p, c, p.ntext_a + p.nvis_a);
+    } else {
+        launch_a2<G, false, false>(p, c, p.nvis_a);
+    }
     return true;
 }
 
-template <int G, int UP, int NT, int NC> bool launch_c3(const Plan &p, const DecodeCall &c)
+template <int G, int UP, int NT, int NC, bool RAG> bool launch_c4(const Plan &p, const DecodeCall &c)
 {
     const size_t lds = std::max(lds_c(NC * kPC, NT), kTextLds);
     static bool attr_set[kMaxDevices] = {};
-    if (!allow_lds(reinterpret_cast<const void *>(fc_fused<G, UP, NT, NC>), lds, attr_set)) return false;
-    fc_fused<G, UP, NT, NC><<<p.nvis_c + p.ntext_c, 512, lds, c.stream>>>(
+    if (!allow_lds(reinterpret_cast<const void *>(fc_fused<G, UP, NT, NC, RAG>), lds, attr_set)) return false;
+    fc_fused<G, UP, NT, NC, RAG><<<p.nvis_c + p.ntext_c, 512, lds, c.stream>>>(
         static_cast<const uint16_t *>(c.U), p.P, p.stats, p.qJS, p.JS, p.qHkv, p.Hkv, p.B, p.I, p.m, p.UPBs, p,
         static_cast<const uint16_t *>(c.Vc), static_cast<const uint16_t *>(c.q),
         static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt), static_cast<const uint16_t *>(c.k_new),
         static_cast<const uint16_t *>(c.v_new));
     return true;
+}
+
+template <int G, int UP, int NT, int NC> bool launch_c3(const Plan &p, const DecodeCall &c)
+{
+    return p.n_img ? launch_c4<G, UP, NT, NC, true>(p, c) : launch_c4<G, UP, NT, NC, false>(p, c);
 }
 
 template <int G, int UP, int NT> bool launch_c2(const Plan &p, const DecodeCall &c)
@@ -1372,6 +1405,7 @@ kvc_status fast_decode(const DecodeCall &c)
         if (amax * dmax >= (1ll << 32)) return generic_decode(c);
     }
     if (p.bytes > c.ws_bytes) return KVC_ERR_WORKSPACE;
+    if (c.n_images_dev && c.text_len_dev) { p.n_img = c.n_images_dev; p.tlen = c.text_len_dev; }
 #if defined(KVC_TIMELINE)
     p.tl = c.ws_bytes >= p.bytes + kTimelineBytes
                ? reinterpret_cast<unsigned long long *>(static_cast<char *>(c.ws) + ((c.ws_bytes - kTimelineBytes) & ~size_t(255)))

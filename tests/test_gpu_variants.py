@@ -63,12 +63,13 @@ def test_ragged_batch(w, m):
         for b in range(B):                  # the new token went to the sequence's own row
             assert np.array_equal(f64(L.gKt)[b, :, text_len[b]], f64(kn)[b])
             assert np.array_equal(f64(L.gVt)[b, :, text_len[b]], f64(vn)[b])
-    # a uniform batch through the ragged entry point equals the uniform entry point's scalar path
-    L2 = Layer(w, m, generic=True)
+    # a uniform batch through the ragged entry point equals the uniform entry point bit for bit (both take
+    # the matrix-core kernels where the shape has them, the scalar ones elsewhere)
+    L2 = Layer(w, m)
     L2.compress()
     q, kn, vn = synth.make_step_inputs(w, 0, 1)
     a, la = L2.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
-    L3 = Layer(w, m, generic=True)
+    L3 = Layer(w, m)
     L3.compress()
     kv.kvc_reconstruct_attend_decode_ragged(L3.shape, L3.params, q.to(DEV), L3.gKc, L3.gVc, L3.gKt, L3.gVt,
                                             torch.full((B,), I, dtype=torch.int32, device=DEV),
@@ -76,6 +77,61 @@ def test_ragged_batch(w, m):
                                             kn.to(DEV), vn.to(DEV), 0.0, L3.out, L3.lse, L3.ws)
     torch.cuda.synchronize()
     assert np.array_equal(f64(L3.out), a) and np.array_equal(f64(L3.lse), la)
+
+
+RAG_HEAD = synth.Workload("rag_headline", 72, 1, 4, 7, 1, 128, "bf16", 1024, 8, 0.6, 300, 2)     # G = 7, merged part records
+RAG_G1 = synth.Workload("rag_g1", 73, 1, 12, 2, 2, 128, "bf16", 576, 5, 0.6, 140, 2)              # G = 1: 32 image blocks per workgroup
+RAG_VIDEO = synth.Workload("rag_video", 74, 1, 2, 14, 2, 128, "bf16", 256, 24, 0.6, 260, 2)       # four row tiles per workgroup
+
+
+@pytest.mark.parametrize("w,m,n_images,text_len,append", [
+    (RAG_HEAD, 410, [8, 0, 1, 3], [300, 0, 129, 17], True),
+    (RAG_HEAD, 410, [8, 0, 1, 3], [302, 1, 128, 17], False),
+    (RAG_G1, 231, [5, 0, 1, 3, 5, 2, 0, 4, 1, 5, 3, 0], [140, 0, 1, 127, 128, 129, 7, 64, 141, 33, 90, 2], True),
+    (RAG_VIDEO, 103, [24, 5], [260, 3], True),
+    (RAG_VIDEO, 103, [0, 0], [0, 200], True),
+])
+def test_ragged_batch_on_the_matrix_core_kernels(w, m, n_images, text_len, append):
+    """Shapes that take the matrix-core kernels (fused and separate first launches, merged and per-block part
+    records, 2 to 64 image blocks per workgroup): blocks and text rows a sequence does not have hold NaNs."""
+    L = Layer(w, m)
+    L.compress()
+    B, I, cap = w.batch, w.n_images, w.text_cap
+    gKc, gVc = L.gKc.clone(), L.gVc.clone()
+    Kc_h, Vc_h = f64(gKc), unpack_vc(gVc, m, w.head_dim)
+    rows = [t + (1 if append else 0) for t in text_len]
+    for b in range(B):
+        gKc[b, :, n_images[b]:] = float("nan")
+        gVc[b, :, n_images[b]:] = float("nan")
+        L.gKt[b, :, rows[b]:] = float("nan")
+        L.gVt[b, :, rows[b]:] = float("nan")
+    ni = torch.tensor(n_images, dtype=torch.int32, device=DEV)
+    tl = torch.tensor(text_len, dtype=torch.int32, device=DEV)
+    Kt, Vt = f64(L.Kt).copy(), f64(L.Vt).copy()
+    th, U, mu = f64(L.p["theta"]), f64(L.p["U"]), f64(L.p["mu"])
+    q, kn, vn = synth.make_step_inputs(w, 0, 0)
+    gkn, gvn = (kn.to(DEV), vn.to(DEV)) if append else (None, None)
+    # twice: the first call on a fresh workspace may find garbage in the arrival counters and compute without
+    # waiting (correct, counted); the second must not (appending the same token again changes nothing)
+    for rep in range(2):
+        alone = kv.lib().kvc_dev_decode_fallbacks()
+        kv.kvc_reconstruct_attend_decode_ragged(L.shape, L.params, q.to(DEV), gKc, gVc, L.gKt, L.gVt, ni, tl, cap,
+                                                gkn, gvn, 0.0, L.out, L.lse, L.ws)
+        torch.cuda.synchronize()
+    ref, lref = orc.reconstruct_attend_decode_ragged(f64(q), Kc_h, Vc_h, th, U, mu, w.n_img_tokens, n_images,
+                                                     text_len, Kt, Vt, f64(kn) if append else None,
+                                                     f64(vn) if append else None)
+    out, lse = f64(L.out), f64(L.lse)
+    e, ex = row_rel_err(out, ref), elem_rel_err(out, ref)
+    _say(f"[ragged, matrix cores] {w.name} append={append}: row {e:.3e} element {ex:.3e} lse {np.abs(lse - lref).max():.3e}")
+    assert np.all(np.isfinite(out)) and np.all(np.isfinite(lse))
+    assert e <= tol(w) and ex <= 4 * tol(w)
+    assert np.abs(lse - lref).max() <= 5e-2
+    if append:
+        for b in range(B):
+            assert np.array_equal(f64(L.gKt)[b, :, text_len[b]], f64(kn)[b])
+            assert np.array_equal(f64(L.gVt)[b, :, text_len[b]], f64(vn)[b])
+    assert kv.lib().kvc_dev_decode_fallbacks() == alone
 
 
 def test_ragged_argument_errors():
