@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--generic", action="store_true", help="force the scalar kernels")
+    ap.add_argument("--no-packed-theta", action="store_true",
+                    help="do not pass kvc_params.theta_packed: every call takes the four-kernel form")
     ap.add_argument("--no-full-baseline", action="store_true",
                     help="skip the full-cache (All KV) decode that is timed beside the capsule path")
     ap.add_argument("--read-probe", type=int, default=4, metavar="GiB",
@@ -127,7 +129,10 @@ def main():
         l = lc % L
         shape, cshape = shapes[l], (w.batch, w.n_kv_heads, w.n_images, ms[l], w.head_dim)
         p = synth.make_params(w, ms[l], l, device=dev)
-        params = kv.make_params(p["key_idx"], p["theta"], p["U"], p["mu"])
+        # theta re-tiled once at load time (kvc_pack_theta): calls whose shape has a one-pass kernel use it
+        if not args.generic and not args.no_packed_theta:
+            p["theta_packed"] = kv.kvc_pack_theta(shape, p["theta"])
+        params = kv.make_params(p["key_idx"], p["theta"], p["U"], p["mu"], p.get("theta_packed"))
         Kp, Vp = synth.make_prefill_kv(w, l, 0, 0, device=dev)
         Kc = torch.empty(cshape, dtype=dt, device=dev)
         Vc = torch.empty(cshape, dtype=dt, device=dev)
@@ -173,6 +178,7 @@ def main():
         if st != kv.KVC_OK:
             raise kv.KvcError(st, "kvc_reconstruct_attend_decode")
 
+    stream_calls0 = kv.lib().kvc_dev_stream_calls()
     for step in warm:                       # warm-up: same slot, text length not advanced
         for a in step:
             layer_step(a)
@@ -190,6 +196,9 @@ def main():
     t1 = time.perf_counter()
     wall = t1 - t0
     assert bool(torch.isfinite(out.float()).all()), "non-finite attention output"
+    stream_share = (kv.lib().kvc_dev_stream_calls() - stream_calls0) / float((W + K) * L)
+    kernels = "generic" if args.generic else "mfma-one-pass" if stream_share == 1.0 else \
+        "mfma" if stream_share == 0.0 else "mfma (one-pass kernel for %.0f%% of the calls)" % (100 * stream_share)
     call_us = ev_beg.elapsed_time(ev_end) * 1e3 / (K * L)
 
     # second identical pass with an event pair around every single call (each pair adds about 2 us
@@ -280,7 +289,7 @@ def main():
     t_avg = w.text_len + (K + 1) / 2.0      # rows attended, new token included
     abytes = sum(algorithmic_bytes(w, ml, t_avg) for ml in ms) / L        # mean over the layers
     achieved = abytes / (call_us * 1e-6) / 1e9
-    traffic = read_traffic(w.name, w.compression, "generic" if args.generic else "mfma", args.pyramid)
+    traffic = read_traffic(w.name, w.compression, kernels, args.pyramid)
     res = {
         "metric": "decode attention steps/s + achieved HBM GB/s (% peak) at 60% vision-KV compression",
         "value": K / wall, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -293,13 +302,14 @@ def main():
                                   100 * w.compression,
                                   "m=%d" % m if len(set(ms)) == 1 else
                                   "pyramid m=%d..%d, mean %.1f" % (max(ms), min(ms), sum(ms) / L)),
-                   "kernels": "generic" if args.generic else "mfma", "buffer_copies": copies},
+                   "kernels": kernels, "buffer_copies": copies},
         "layer_steps_per_s": K * L / wall,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic["bytes_per_call"] if traffic else None,
-                     "kernel": "kvc_reconstruct_attend_decode (kernels fab_fused, fc_fused, fd_finalize_few; the scalar "
-                               "kernels with --generic)",
+                     "kernel": "kvc_reconstruct_attend_decode (kernels fs_stream, fs_finalize where the one-pass form "
+                               "serves the call; fab_fused, fc_fused, fd_finalize_few otherwise; the scalar kernels "
+                               "with --generic)",
                      "algorithmic_bytes_per_launch": abytes, "us_per_launch": call_us,
                      "us_per_launch_event_pair_each": call_us_pairs,
                      "measured_read_ceiling": read_ceiling},

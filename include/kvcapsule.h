@@ -90,6 +90,10 @@ typedef struct {
                             /* (App. C; applied to scores in Alg. 1 step 2)          */
     const void *U;          /* U : [H_kv][m][n] value PCA basis (Sec. 3.1, Values)   */
     const void *mu;         /* mu : [H_kv][d] value centre (Sec. 3.1, Values)        */
+    const void *theta_packed; /* optional (may be NULL): theta re-tiled once by      */
+                            /* kvc_pack_theta, same size; decode calls whose shape   */
+                            /* has a one-pass kernel use it, all others read theta.  */
+                            /* Unused by compress.                                   */
 } kvc_params;
 
 /* |M| = ceil(l_r n) with retention l_r = 1 - compression_ratio (Sec. 3.1, Keys),
@@ -160,6 +164,21 @@ kvc_status kvc_reconstruct_attend_decode(const kvc_shape *shape, const kvc_param
                                          float softmax_scale,
                                          void *out, float *lse_out,
                                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* theta re-tiled for the matrix cores, once at load time (the survey of the method allows a packed
+ * copy of the parameters that is no larger than the original; App. C counts theta as H_kv m n
+ * elements, and so does this form).  Alg. 1 step 2 contracts the scores with theta over its ROW index
+ * j, which is the slow index of [H_kv][m][n]; the packed form makes 8 consecutive rows of one position
+ * 16 contiguous bytes, so that a matrix-core operand is one load:
+ *   per KV head one record of exactly m n elements; rows in blocks of 8, each block position-major
+ *   [n][w] with w = 8 (w = m mod 8 for the last, shorter block); element (j, pos) sits at
+ *   kvc_capsule_value_offset(j, pos, m, n) within the record (the layout of the compressed values
+ *   with positions in place of channels).
+ *  theta in: [H_kv][m][n]; packed out: same size, a different buffer; both device memory, element type
+ *  of the shape.  Pass the result as kvc_params.theta_packed (theta itself stays required: shapes
+ *  without a one-pass kernel read it).
+ * Errors: NULL pointers, bad shape, theta == packed, misalignment. */
+kvc_status kvc_pack_theta(const kvc_shape *shape, const void *theta, void *packed, void *stream);
 
 /* Ragged batch: the decode step for sequences with their own numbers of image blocks and text rows.
  * Sequence b attends the first n_images[b] of its I = shape->n_images capsule slots and text_len[b]

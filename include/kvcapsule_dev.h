@@ -61,6 +61,14 @@ void kvc_dev_full_decode_chunk_steps(int32_t steps);
  *              (default 2000 = 20 us; 0: it never waits, which tests use to run that path). */
 void kvc_dev_decode_knobs(int32_t row_tiles, int32_t separate, int32_t wait_ticks);
 
+/* Which decode kernels serve a call that comes with kvc_params.theta_packed (process-wide):
+ *  -1 the built-in rule (the one-pass kernel for calls of at most two workgroups per compute unit whose
+ *     shape has an instance), 0 never the one-pass kernel, 1 the one-pass kernel wherever an instance exists. */
+void kvc_dev_stream_decode(int32_t mode);
+
+/* Decode calls the one-pass kernel has served since the library was loaded (host-side count). */
+int64_t kvc_dev_stream_calls(void);
+
 /* Workgroups that gave up waiting and computed alone since the library was loaded (current device;
  * synchronises with the device), or -1. */
 int64_t kvc_dev_decode_fallbacks(void);

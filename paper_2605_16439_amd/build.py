@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvcapsule.so")
 SOURCES = ["kvc_api.hip", "kvc_generic.hip", "kvc_fast_decode.hip", "kvc_fast_compress.hip",
-           "kvc_full_decode.hip"]
+           "kvc_full_decode.hip", "kvc_stream_decode.hip"]
 # packed-fp32 code generation is switched off on purpose: some packed forms have given
 # wrong results on this hardware, so the compiler must not emit them
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

@@ -39,7 +39,7 @@ kvc_status check_params(const kvc_params *p, bool need_idx, bool need_theta)
     if (need_idx && !p->key_idx) return KVC_ERR_NULL;
     if (need_theta && !p->theta) return KVC_ERR_NULL;
     if (!aligned16(p->U) || !aligned16(p->mu)) return KVC_ERR_ALIGN;
-    if (need_theta && !aligned16(p->theta)) return KVC_ERR_ALIGN;
+    if (need_theta && (!aligned16(p->theta) || !aligned16(p->theta_packed))) return KVC_ERR_ALIGN;
     if (need_idx && (reinterpret_cast<uintptr_t>(p->key_idx) & 3u)) return KVC_ERR_ALIGN;
     return KVC_OK;
 }
@@ -71,6 +71,7 @@ kvc_status prepare_decode(DecodeCall &c, const kvc_shape *shape, const kvc_param
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return KVC_ERR_ALIGN;
     c.s = *shape;
     c.theta = params->theta;
+    c.theta_packed = params->theta_packed;
     c.U = params->U;
     c.mu = params->mu;
     c.q = q;
@@ -131,6 +132,8 @@ kvc_status prepare_compress(CompressCall &c, const kvc_shape *shape, const kvc_p
 // the matrix-core kernels where the shape allows it, else the scalar kernels
 kvc_status dispatch_decode(const DecodeCall &c)
 {
+    kvc_status st = KVC_OK;
+    if (stream_decode(c, &st)) return st;
     if (fast_decode_supported(c.s)) return fast_decode(c);
     return generic_decode(c);
 }
@@ -173,6 +176,7 @@ size_t kvc_workspace_bytes(const kvc_shape *shape, int32_t max_text_len)
         size_t f = fast_compress_ws_bytes(*shape);
         if (f > need) need = f;
     }
+    need = std::max(need, stream_decode_ws_bytes(*shape, max_text_len));
     return need;
 }
 
@@ -279,7 +283,7 @@ kvc_status kvc_static_attend_decode(const kvc_shape *shape, const void *q, const
 {
     // theta, U and mu are not part of this variant; q stands in for them (never read)
     kvc_params none;
-    none.key_idx = nullptr; none.theta = q; none.U = q; none.mu = q;
+    none.key_idx = nullptr; none.theta = q; none.U = q; none.mu = q; none.theta_packed = nullptr;
     DecodeCall c;
     kvc_status st = prepare_decode(c, shape, &none, q, Kc, Vc, K_text, V_text, text_len, text_cap, k_new, v_new,
                                    softmax_scale, out, lse_out, workspace, workspace_bytes, stream);
@@ -299,6 +303,16 @@ kvc_status kvc_mlp_hidden(const kvc_shape *shape, const void *W1, int32_t activa
     if (Kc == H) return KVC_ERR_SHAPE;                       // every output row reads all input rows
     if (!aligned16(W1) || !aligned16(Kc) || !aligned16(H)) return KVC_ERR_ALIGN;
     return generic_mlp_hidden(*shape, W1, activation, Kc, H, static_cast<hipStream_t>(stream));
+}
+
+kvc_status kvc_pack_theta(const kvc_shape *shape, const void *theta, void *packed, void *stream)
+{
+    kvc_status st = check_shape(shape);
+    if (st != KVC_OK) return st;
+    if (!theta || !packed) return KVC_ERR_NULL;
+    if (theta == packed) return KVC_ERR_SHAPE;
+    if (!aligned16(theta) || !aligned16(packed)) return KVC_ERR_ALIGN;
+    return pack_theta(*shape, theta, packed, static_cast<hipStream_t>(stream));
 }
 
 // ---- the blocked layout of the compressed values, for callers ---------------------------------------
@@ -457,6 +471,10 @@ void kvc_dev_decode_knobs(int32_t row_tiles, int32_t separate, int32_t wait_tick
 }
 
 int64_t kvc_dev_decode_fallbacks(void) { return fast_decode_fallbacks(); }
+
+void kvc_dev_stream_decode(int32_t mode) { stream_decode_knob(mode); }
+
+int64_t kvc_dev_stream_calls(void) { return stream_decode_calls(); }
 
 void kvc_dev_compress_knobs(int32_t waves, int32_t jt) { fast_compress_knobs(waves, jt); }
 

@@ -59,6 +59,7 @@ __device__ inline float wave_max(float x)
 struct DecodeCall {
     kvc_shape s;
     const void *theta, *U, *mu;
+    const void *theta_packed = nullptr;   // theta in the blocked form of kvc_pack_theta, or null
     const void *q, *Kc, *Vc;
     void *Kt, *Vt;
     int32_t t;        // text rows attended (new token included when appended)
@@ -140,6 +141,12 @@ long fast_decode_fallbacks();
 // head) into out / lse; nparts <= 64
 kvc_status finalize_parts(const float *Ypart, int nparts, int nvp, int rec, int B, int Hq, int Hkv, const void *mu,
                           void *out, float *lse, hipStream_t stream);
+// one-pass ("stream") decode for bf16, head_dim 128, theta in packed form: true when the call was taken
+bool stream_decode(const DecodeCall &c, kvc_status *st);
+size_t stream_decode_ws_bytes(const kvc_shape &s, int32_t max_text);
+void stream_decode_knob(int mode);
+long stream_decode_calls();
+kvc_status pack_theta(const kvc_shape &s, const void *theta, void *packed, hipStream_t stream);
 // full-cache decode, bf16, head_dim 128
 bool fast_full_supported(int dtype, int head_dim, int G);
 size_t fast_full_ws_bytes(int B, int Hq, int Hkv);

@@ -38,6 +38,7 @@ EXPORTS = [
     "kvc_dev_decode_knobs", "kvc_dev_decode_fallbacks", "kvc_dev_compress_knobs",
     "kvc_capsule_value_offset", "kvc_unpack_values",
     "kvc_reconstruct_attend_decode_ragged", "kvc_mlp_hidden", "kvc_static_attend_decode",
+    "kvc_pack_theta", "kvc_dev_stream_decode", "kvc_dev_stream_calls",
 ]
 
 
@@ -50,7 +51,7 @@ class KvcShape(ctypes.Structure):
 
 class KvcParams(ctypes.Structure):
     _fields_ = [("key_idx", ctypes.c_void_p), ("theta", ctypes.c_void_p),
-                ("U", ctypes.c_void_p), ("mu", ctypes.c_void_p)]
+                ("U", ctypes.c_void_p), ("mu", ctypes.c_void_p), ("theta_packed", ctypes.c_void_p)]
 
 
 class KvcError(RuntimeError):
@@ -115,6 +116,12 @@ def lib() -> ctypes.CDLL:
         L.kvc_static_attend_decode.restype = i32
         L.kvc_static_attend_decode.argtypes = [ctypes.POINTER(KvcShape), vp, vp, vp, vp, vp, i32, i32, vp, vp,
                                                ctypes.c_float, vp, vp, vp, ctypes.c_size_t, vp]
+        L.kvc_pack_theta.restype = i32
+        L.kvc_pack_theta.argtypes = [ctypes.POINTER(KvcShape), vp, vp, vp]
+        L.kvc_dev_stream_decode.restype = None
+        L.kvc_dev_stream_decode.argtypes = [i32]
+        L.kvc_dev_stream_calls.restype = i64
+        L.kvc_dev_stream_calls.argtypes = []
         L.kvc_capsule_value_offset.restype = i64
         L.kvc_capsule_value_offset.argtypes = [i32, i32, i32, i32]
         L.kvc_unpack_values.restype = i32
@@ -183,8 +190,17 @@ def _stream(stream) -> ctypes.c_void_p:
     return ctypes.c_void_p(stream.cuda_stream)
 
 
-def make_params(key_idx, theta, U, mu) -> KvcParams:
-    return KvcParams(_ptr(key_idx), _ptr(theta), _ptr(U), _ptr(mu))
+def make_params(key_idx, theta, U, mu, theta_packed=None) -> KvcParams:
+    return KvcParams(_ptr(key_idx), _ptr(theta), _ptr(U), _ptr(mu), _ptr(theta_packed))
+
+
+def kvc_pack_theta(shape: KvcShape, theta: torch.Tensor, stream=None) -> torch.Tensor:
+    """theta [H_kv, m, n] -> the packed form of the same size (a new tensor), for KvcParams.theta_packed."""
+    packed = torch.empty_like(theta)
+    st = lib().kvc_pack_theta(ctypes.byref(shape), _ptr(theta), _ptr(packed), _stream(stream))
+    if st != KVC_OK:
+        raise KvcError(st, "kvc_pack_theta")
+    return packed
 
 
 def new_workspace(shape: KvcShape, max_text_len: int, device="cuda") -> torch.Tensor:

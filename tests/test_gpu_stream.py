@@ -1,0 +1,140 @@
+"""Parity of the one-pass ("stream") decode kernel against the CPU oracle, through the C ABI: the call is
+kvc_reconstruct_attend_decode with kvc_params.theta_packed set (kvc_pack_theta), forced onto the one-pass
+kernel with kvc_dev_stream_decode(1) so that small test shapes take it too.
+
+Bars as in tests/test_gpu_parity.py (bf16): output rows within 2e-2 relative L2 error, every element within
+4 x that of its row's rms, lse within 5e-2; appended tokens land in the text cache bit for bit; theta packed
+by the library equals the layout function kvc_capsule_value_offset(j, pos, m, n) bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import kvc_oracle as orc
+from paper_2605_16439_amd import kvcapsule as kv
+from paper_2605_16439_amd import synth
+
+from helpers import elem_rel_err, f64, row_rel_err, tol, unpack_vc
+from test_gpu_parity import DEV, Layer
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(autouse=True)
+def _force_stream():
+    kv.lib().kvc_dev_stream_decode(1)
+    yield
+    kv.lib().kvc_dev_stream_decode(-1)
+
+
+def _wl(name, idx, batch, hkv, n_images, text_len, steps=2):
+    return synth.Workload(name, idx, 1, batch, 7 * hkv, hkv, 128, "bf16", 1024, n_images, 0.6, text_len, steps)
+
+
+def _packed_layer(w, m):
+    L = Layer(w, m)
+    L.theta_packed = kv.kvc_pack_theta(L.shape, L.g["theta"])
+    L.params = kv.make_params(L.g["key_idx"], L.g["theta"], L.g["U"], L.g["mu"], L.theta_packed)
+    L.compress()
+    return L
+
+
+def _run(L, w, m, steps, append=True, t0=None):
+    th, U, mu = f64(L.p["theta"]), f64(L.p["U"]), f64(L.p["mu"])
+    Kc_h, Vc_h = f64(L.gKc), unpack_vc(L.gVc, m, w.head_dim)
+    Kt, Vt = f64(L.Kt).copy(), f64(L.Vt).copy()
+    t = w.text_len if t0 is None else t0
+    taken = kv.lib().kvc_dev_stream_calls()
+    for step in range(steps):
+        q, kn, vn = synth.make_step_inputs(w, 0, step)
+        if append:
+            out, lse = L.decode(q.to(DEV), t, kn.to(DEV), vn.to(DEV))
+            ref, lref = orc.reconstruct_attend_decode(f64(q), Kc_h, Vc_h, th, U, mu, w.n_img_tokens, Kt, Vt, t,
+                                                      f64(kn), f64(vn))
+        else:
+            out, lse = L.decode(q.to(DEV), t)
+            ref, lref = orc.reconstruct_attend_decode(f64(q), Kc_h, Vc_h, th, U, mu, w.n_img_tokens,
+                                                      Kt if t else None, Vt if t else None, t)
+        e, ex, el = row_rel_err(out, ref), elem_rel_err(out, ref), np.abs(lse - lref).max()
+        _say(f"[stream] {w.name} m={m} t={t} append={append} step {step}: row {e:.3e} element {ex:.3e} lse {el:.3e}")
+        assert np.all(np.isfinite(out))
+        assert e <= tol(w) and ex <= 4 * tol(w) and el <= 5e-2
+        if append:
+            assert np.array_equal(f64(L.gKt)[:, :, t], f64(kn)) and np.array_equal(f64(L.gVt)[:, :, t], f64(vn))
+            t += 1
+    assert kv.lib().kvc_dev_stream_calls() == taken + steps, "the one-pass kernel must have served these calls"
+
+
+def test_pack_theta_layout():
+    w = _wl("st_pack", 80, 1, 2, 2, 8)
+    for m in (410, 205, 7, 8):
+        L = Layer(w, m)
+        packed = kv.kvc_pack_theta(L.shape, L.g["theta"])
+        torch.cuda.synchronize()
+        n = w.n_img_tokens
+        off = np.array([[kv.lib().kvc_capsule_value_offset(j, p, m, n) for p in range(0, n, 37)] for j in range(m)])
+        src = L.p["theta"].view(torch.int16).numpy().reshape(w.n_kv_heads, m * n)
+        got = packed.cpu().view(torch.int16).numpy().reshape(w.n_kv_heads, m * n)
+        for h in range(w.n_kv_heads):
+            dense = src[h].reshape(m, n)[:, ::37]
+            assert np.array_equal(got[h][off], dense)
+
+
+# compressed lengths of the three compiled instances (7, 13, 20 steps of 32 rows): a short last block of
+# every width class, no short block, a last 16-row tile that is missing, the shortest and longest length
+@pytest.mark.parametrize("m", [410, 416, 400, 385, 415, 393, 205, 193, 224, 615, 609, 640])
+def test_compressed_lengths(m):
+    w = _wl("st_len", 81, 2, 2, 4, 77)
+    L = _packed_layer(w, m)
+    _run(L, w, m, 2)
+
+
+@pytest.mark.parametrize("text_len,append", [(0, True), (0, False), (1, True), (15, False), (16, True), (300, True),
+                                             (1000, True)])
+def test_text_lengths(text_len, append):
+    w = _wl("st_text", 82, 1, 2, 8 if text_len > 500 else 2, text_len, 3)
+    L = _packed_layer(w, 410)
+    _run(L, w, 410, 3 if append else 1, append)
+
+
+def test_headline_shape_every_element():
+    w = synth.WORKLOADS["qwen2vl"].with_(layers=1, steps=2)
+    L = _packed_layer(w, 410)
+    th, U, mu = f64(L.p["theta"]), f64(L.p["U"]), f64(L.p["mu"])
+    Kt, Vt = f64(L.Kt).copy(), f64(L.Vt).copy()
+    q, kn, vn = synth.make_step_inputs(w, 0, 0)
+    out, lse = L.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
+    # the same call on the four-kernel form (no packed theta): both within the bar of the oracle, and close
+    L2 = Layer(w, 410)
+    L2.compress()
+    out2, lse2 = L2.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
+    bs, hs = [0, w.batch - 1], [0, w.n_kv_heads - 1]
+    G = w.n_q_heads // w.n_kv_heads
+    gs = [h * G + g for h in hs for g in range(G)]
+    sel, selq = np.ix_(bs, hs), np.ix_(bs, gs)
+    ref, lref = orc.reconstruct_attend_decode(f64(q)[selq], f64(L.gKc)[sel], unpack_vc(L.gVc, 410, 128)[sel], th[hs], U[hs],
+                                              mu[hs], w.n_img_tokens, Kt[sel].copy(), Vt[sel].copy(), w.text_len,
+                                              f64(kn)[sel], f64(vn)[sel])
+    e, ex = row_rel_err(out[selq], ref), elem_rel_err(out[selq], ref)
+    e2 = row_rel_err(out2[selq], ref)
+    _say(f"[stream] headline: row {e:.3e} element {ex:.3e} lse {np.abs(lse[selq] - lref).max():.3e}; four-kernel form row {e2:.3e}")
+    assert e <= tol(w) and ex <= 4 * tol(w) and np.abs(lse[selq] - lref).max() <= 5e-2
+    assert row_rel_err(out, out2) <= 2 * tol(w)
+
+
+def test_shapes_without_an_instance_take_the_other_kernels():
+    """theta_packed is optional help: a shape the one-pass kernel is not compiled for gives the same result
+    as the call without it, bit for bit."""
+    w = synth.Workload("st_other", 83, 1, 2, 14, 2, 128, "bf16", 256, 4, 0.6, 50, 2)
+    m = 103
+    L = _packed_layer(w, m)
+    q, kn, vn = synth.make_step_inputs(w, 0, 0)
+    a, la = L.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
+    L2 = Layer(w, m)
+    L2.compress()
+    b, lb = L2.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
+    assert np.array_equal(a, b) and np.array_equal(la, lb)
