@@ -1341,6 +1341,16 @@ bool launch_for_group(const Plan &p, const DecodeCall &c, bool first)
 
 }  // namespace
 
+// what the one-pass kernel shares with fab_fused: the call numbering, the waiting limit, the debug counter
+unsigned next_decode_epoch()
+{
+    unsigned e = ++g_epoch;
+    if (e == 0) e = ++g_epoch;                 // zero is what a finished call leaves behind
+    return e;
+}
+int decode_wait_ticks() { return g_wait_ticks; }
+unsigned *decode_fallback_counter() { return fallback_counter(); }
+
 kvc_status finalize_parts(const float *Ypart, int nparts, int nvp, int rec, int B, int Hq, int Hkv, const void *mu,
                           void *out, float *lse, hipStream_t stream)
 {
@@ -1413,9 +1423,7 @@ kvc_status fast_decode(const DecodeCall &c)
 #endif
     if (fab_shape(p) && fab_resident(p, c)) {
         p.fab = 1;
-        unsigned e = ++g_epoch;
-        if (e == 0) e = ++g_epoch;             // zero is what a finished call leaves behind
-        p.epoch = e;
+        p.epoch = next_decode_epoch();
         p.wait_ticks = g_wait_ticks;
         p.fallbacks = fallback_counter();
     }

@@ -141,6 +141,10 @@ long fast_decode_fallbacks();
 // head) into out / lse; nparts <= 64
 kvc_status finalize_parts(const float *Ypart, int nparts, int nvp, int rec, int B, int Hq, int Hkv, const void *mu,
                           void *out, float *lse, hipStream_t stream);
+// shared by the decode paths that synchronise workgroups through counters in the workspace
+unsigned next_decode_epoch();
+int decode_wait_ticks();
+unsigned *decode_fallback_counter();
 // one-pass ("stream") decode for bf16, head_dim 128, theta in packed form: true when the call was taken
 bool stream_decode(const DecodeCall &c, kvc_status *st);
 size_t stream_decode_ws_bytes(const kvc_shape &s, int32_t max_text);

@@ -40,6 +40,11 @@ struct SPlan {
     unsigned qF, qBIU, qIU;
     float scale;
     float *Ypart;
+    uint16_t *Sx;                 // scores handed between the F workgroups of a group: [NGR][16][MP] bf16
+    u64 *flags;                   // one arrival counter (epoch, count) per group, at the start of the workspace
+    unsigned epoch;
+    int wait_ticks;
+    unsigned *fallbacks;
 #if defined(KVC_TIMELINE)
     unsigned long long *tl;       // timeline slots, see TS()
 #endif
@@ -114,7 +119,6 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
     constexpr int KP = PS / 32;                          // k-steps over the slice's positions
     constexpr int NI = UP * T, NRS = (NI + 7) / 8;       // key tiles, rounds of eight
     constexpr int NRW = (T + 7) / 8;                     // rounds of eight tiles of U
-    constexpr int PDS = NRS < 4 ? NRS : 4;               // key tiles requested ahead
     constexpr int PDL = KS < 13 ? KS : 13;               // k-steps of theta requested ahead
     constexpr int PDW = NRW < 3 ? NRW : 3;               // tiles of U requested ahead
     constexpr int PDY = KS < (UP > 2 ? 2 : 6) ? KS : (UP > 2 ? 2 : 6);   // k-steps of compressed values requested ahead
@@ -183,32 +187,23 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
         tv[rr] = *reinterpret_cast<const uint32_t *>(vt_base + static_cast<size_t>(min(xv0 + rr, xvl)) * 256 + lane * 4);
     const uint32_t tvn = *(reinterpret_cast<const uint32_t *>(vn_p) + lane);
 
-    // ---- step 1: S = sigma q Kc^T, tiles of 16 compressed keys, eight tiles per round ------------------
+    // ---- step 1: S = sigma q Kc^T in tiles of 16 compressed keys.  The F workgroups of a group need the same
+    // scores: each computes the tiles of its own share and hands them to the others through the L2 (they run on
+    // one XCD), so that a workgroup pulls a quarter of the group's keys through its L1 at memory's latency
+    // instead of all of them.
     const char *kc_base = reinterpret_cast<const char *>(Kc + (static_cast<size_t>(bh) * p.I + i0) * m * D);
-    u32x4 kf[NRS][4];
-    // whether a tile of round r can hold rows >= m: known at compile time (rounds are unrolled)
-    auto round_partial = [](int r) {
-        for (int w = 0; w < 8; ++w) {
-            const int it = 8 * r + w;
-            if (it >= NI || it % T >= TI) return true;
-        }
-        return false;
-    };
-    auto key_item = [&](int r) { return min(wave + 8 * r, NI - 1); };
-    const uint32_t k_lane = static_cast<uint32_t>(lane) * 16u;          // a whole tile is 4 KB of consecutive rows
-    auto load_k = [&](int r) {
-        const int it = key_item(r);
+    constexpr int FS = 1024 / PS;                          // shares = slices per image block (instances exist for n = 1024)
+    constexpr int QI = (NI + FS - 1) / FS, NRQ = (QI + 7) / 8;   // tiles per share, rounds of eight
+    const int it_lo = s * QI, it_hi = min(it_lo + QI, NI);
+    uint16_t *sx = p.Sx + static_cast<size_t>(gk) * 16 * MP;
+    u64 *flag = p.flags + static_cast<size_t>(gk) * kCtrStride;
+    auto load_tile = [&](int it, u32x4 (&dst)[4]) {
         const int u = it / T, jt = it - u * T;
         const char *tile = kc_base + (static_cast<size_t>(u) * m + 16 * jt) * (D * 2);      // scalar
-        if (!round_partial(r)) {
+        const int left = m - 1 - 16 * jt;               // last valid row of the tile (may be negative: row m - 1 then)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) kf[r][i] = *reinterpret_cast<const u32x4 *>(tile + k_lane + 1024 * i);
-        } else {
-            const int left = m - 1 - 16 * jt;               // last valid row of the tile (may be negative: row m - 1 then)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                kf[r][i] = *reinterpret_cast<const u32x4 *>(tile + static_cast<ptrdiff_t>(min(4 * i + krow, left)) * 256 + kpc * 16);
-        }
+        for (int i = 0; i < 4; ++i)
+            dst[i] = *reinterpret_cast<const u32x4 *>(tile + static_cast<ptrdiff_t>(min(4 * i + krow, left)) * 256 + kpc * 16);
     };
     // a key tile in registers -> LDS tile -> the four operands of this lane
     const uint32_t kst = static_cast<uint32_t>(krow * 256 + (kpc ^ krow) * 16);   // piece ^ row, row = 4 i + krow
@@ -220,8 +215,29 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
         for (int ks = 0; ks < 4; ++ks)
             dst[ks] = *reinterpret_cast<const u32x4 *>(sTile + r16 * 256 + (((4 * ks + kg) ^ r16) & 15) * 16);
     };
+    // the scores of one tile (unscaled: sigma multiplies the logits), rows j >= m zero, to the exchange buffer
+    auto score_tile = [&](const u32x4 (&src)[4], int it, bool live) {
+        u32x4 ka[4];
+        key_operands(src, ka);
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int r = 0; r < PDS; ++r) load_k(r);
+        for (int ks = 0; ks < 4; ++ks)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[ks]), as_bf16x8(qf[ks]), acc, 0, 0, 0);
+        const int u = it / T, jt = it - u * T;
+        const int j = 16 * jt + 4 * kg;
+        uint32_t w[2];
+#pragma unroll
+        for (int e = 0; e < 4; e += 2) {
+            const uint32_t lo = (j + e < m) ? f32_to_bf16_bits(acc[e]) : 0u;
+            const uint32_t hi = (j + e + 1 < m) ? f32_to_bf16_bits(acc[e + 1]) : 0u;
+            w[e >> 1] = lo | (hi << 16);
+        }
+        if (r16 < G && live) *reinterpret_cast<u32x2 *>(sx + (u * G + r16) * MP + j) = u32x2_mk(w[0], w[1]);
+    };
+    u32x4 kf[NRQ][4];
+#pragma unroll
+    for (int r = 0; r < NRQ; ++r) load_tile(min(it_lo + wave + 8 * r, it_hi - 1), kf[r]);
+    if (threadIdx.x == 0) ctr_claim(flag, p.epoch);
     // packed theta: blocks of 8 rows j, each [n][8]; lane (position, kg) of k-step ks reads 16 bytes of block 4 ks + kg
     const char *th_base = reinterpret_cast<const char *>(thp + static_cast<size_t>(h) * m * n);
     uint32_t th_off[NPW];
@@ -245,6 +261,19 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
         for (int idx = threadIdx.x; idx < (16 - RU) * (LDS / 2); idx += 512)
             reinterpret_cast<uint32_t *>(sS + RU * LDS)[idx] = 0u;
     }
+
+    // this workgroup's share of the scores, out to the L2; once every wave's stores are acknowledged the
+    // group's counter moves
+#pragma unroll
+    for (int r = 0; r < NRQ; ++r) score_tile(kf[r], min(it_lo + wave + 8 * r, it_hi - 1), it_lo + wave + 8 * r < it_hi);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // theta for step 2 is requested now and arrives while the text rows are done and the siblings finish
+#pragma unroll
+    for (int ks = 0; ks < PDL; ++ks) load_th(ks);
+    __shared__ int sAlone;
+    lds_barrier();
+    if (threadIdx.x == 0) __hip_atomic_fetch_add(flag, static_cast<u64>(1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    TS(4, 7);
 
     // ---- the text rows of this workgroup's share, completely, while the compressed keys are on their way:
     // logits, weights relative to the share's own maximum per head, and the weighted sum of the value rows
@@ -307,40 +336,56 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
             *reinterpret_cast<f32x2 *>(sYt + (wave * 8 + g) * D + 2 * lane) = f32x2_mk(yt[g][0], yt[g][1]);
     }
     TS(4, 6);
-
-#pragma unroll
-    for (int r = 0; r < NRS; ++r) {
-        if (r + PDS < NRS) load_k(r + PDS);
-        if (r + PDS == NRS) {
-#pragma unroll
-            for (int ks = 0; ks < PDL; ++ks) load_th(ks);
+    // all shares of the scores there?  (waiting is bounded: siblings that are not resident, or a counter word that
+    // holds something else, end in this workgroup computing every share itself -- slower, same result)
+    if (threadIdx.x == 0) {
+        const u64 want = ctr_word(p.epoch, static_cast<unsigned>(p.F));
+        const unsigned long long t0 = wall_clock64();
+        bool all = false;
+        if (p.wait_ticks > 0) {
+            do {
+                for (int k = 0; k < 8 && !all; ++k) {            // the clock is read once per 8 polls
+                    const u64 v = ctr_peek(flag);
+                    all = v >= want && static_cast<unsigned>(v >> 32) == p.epoch;
+                }
+            } while (!all && wall_clock64() - t0 < static_cast<unsigned long long>(p.wait_ticks));
         }
-        u32x4 ka[4];
-        key_operands(kf[r], ka);
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[ks]), as_bf16x8(qf[ks]), acc, 0, 0, 0);
-        const int it = wave + 8 * r;
-        const int itc = key_item(r);
-        const int u = itc / T, jt = itc - u * T;
-        const int j = 16 * jt + 4 * kg;
-        uint32_t w[2];
-        if (!round_partial(r)) {
-            w[0] = f32_to_bf16_bits(acc[0]) | (static_cast<uint32_t>(f32_to_bf16_bits(acc[1])) << 16);
-            w[1] = f32_to_bf16_bits(acc[2]) | (static_cast<uint32_t>(f32_to_bf16_bits(acc[3])) << 16);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; e += 2) {
-                const uint32_t lo = (j + e < m) ? f32_to_bf16_bits(acc[e]) : 0u;
-                const uint32_t hi = (j + e + 1 < m) ? f32_to_bf16_bits(acc[e + 1]) : 0u;
-                w[e >> 1] = lo | (hi << 16);
-            }
+        sAlone = all ? 0 : 1;
+        if (!all && p.fallbacks) atomicAdd(p.fallbacks, 1u);
+    }
+    lds_barrier();
+    if (sAlone) {
+#pragma unroll 1
+        for (int r = 0; r < NRS; ++r) {
+            const int it = wave + 8 * r;
+            u32x4 kx[4];
+            load_tile(min(it, NI - 1), kx);
+            score_tile(kx, min(it, NI - 1), it < NI);
         }
-        if (r16 < G && (8 * r + 7 < NI || it < NI)) *reinterpret_cast<u32x2 *>(sS + (u * G + r16) * LDS + j) = u32x2_mk(w[0], w[1]);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        lds_barrier();
+    }
+    asm volatile("buffer_inv sc0" ::: "memory");
+    // the group's scores -> LDS: RU rows of MP values, 16 bytes per thread and pass
+    {
+        constexpr int PPR = MP / 8, NPC = RU * PPR, NPS = (NPC + 511) / 512;
+        u32x4 sv[NPS];
+        int sidx[NPS];
+#pragma unroll
+        for (int k = 0; k < NPS; ++k) {
+            sidx[k] = min(static_cast<int>(threadIdx.x) + 512 * k, NPC - 1);
+            const int row = sidx[k] / PPR, c = sidx[k] - row * PPR;
+            sv[k] = *reinterpret_cast<const u32x4 *>(sx + row * MP + 8 * c);
+        }
+#pragma unroll
+        for (int k = 0; k < NPS; ++k) {
+            const int row = sidx[k] / PPR, c = sidx[k] - row * PPR;
+            *reinterpret_cast<u32x4 *>(sS + row * LDS + 8 * c) = sv[k];
+        }
     }
     lds_barrier();
     TS(4, 1);
+
 
     // ---- step 2: L^T[pos][row] = sum_j theta[j][pos] S[row][j] for this wave's position tiles ----------
     constexpr int LPR = PS / 8;                          // lanes (16-byte pieces) per row of the slice of U
@@ -472,7 +517,6 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
             w1 = b2 | (b3 << 16);
         }
         if (8 * r + 7 < T || jt < T) *reinterpret_cast<u32x2 *>(sW + r16 * LDS + j) = u32x2_mk(w0, w1);
-        if (r == 1) TS(4, 7);
     }
     lds_barrier();
     TS(4, 4);
@@ -562,7 +606,8 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
 template <int PB>
 __global__ __launch_bounds__(128) void fs_finalize(const float *__restrict__ Ypart, const uint16_t *__restrict__ mu,
                                                    uint16_t *__restrict__ out, float *__restrict__ lse, int Hkv,
-                                                   unsigned qHkv, int G, unsigned qG, int np, int rec, int Hq)
+                                                   unsigned qHkv, int G, unsigned qG, int np, int rec, int Hq,
+                                                   u64 *flags, int nflags)
 {
     const int bgi = quot(blockIdx.x, qHkv), h = blockIdx.x - bgi * Hkv;
     const int b = quot(bgi, qG), g = bgi - b * G;
@@ -593,6 +638,9 @@ __global__ __launch_bounds__(128) void fs_finalize(const float *__restrict__ Ypa
     for (int k = 0; k < PB; ++k) y += __shfl(wgt, k, 64) * v[k];
     out[static_cast<size_t>(bg) * D + c] = f32_to_bf16_bits(y);
     if (c == 0 && lse) lse[bg] = mx + __logf(z);
+    // the arrival counters of fs_stream go back to zero
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < nflags; i += 128) flags[static_cast<size_t>(i) * kCtrStride] = 0ull;
 }
 
 int stream_up(int G) { return G == 1 ? 16 : G == 2 ? 8 : G == 4 ? 4 : (G >= 6 && G <= 8) ? 2 : 0; }
@@ -621,8 +669,16 @@ bool make_splan(SPlan &p, const DecodeCall &c, void *base, size_t *bytes)
     p.qF = quot_multiplier(p.F); p.qBIU = quot_multiplier(p.B * p.IU); p.qIU = quot_multiplier(p.IU);
     // quot(): dividends below 2^32 / divisor
     if (static_cast<long>(8) * p.chunk * p.F * std::max(p.F, p.B * p.IU) >= (1l << 31)) return false;
-    p.Ypart = static_cast<float *>(base);
-    *bytes = static_cast<size_t>(p.B) * p.Hkv * p.nparts * p.rec * sizeof(float);
+    if (p.F != 4 || p.NGR > kMaxFlags) return false;
+    // workspace: arrival counters (the same 64 KB the four-kernel form keeps its counters in), part records, scores
+    const size_t fbytes = static_cast<size_t>(kMaxFlags) * kCtrStride * sizeof(u64);
+    const size_t ybytes = align_up(static_cast<size_t>(p.B) * p.Hkv * p.nparts * p.rec * sizeof(float), 256);
+    const size_t sbytes = static_cast<size_t>(p.NGR) * 16 * (32 * ((p.m + 31) / 32)) * sizeof(uint16_t);
+    p.flags = static_cast<u64 *>(base);
+    p.Ypart = reinterpret_cast<float *>(static_cast<char *>(base) + fbytes);
+    p.Sx = reinterpret_cast<uint16_t *>(static_cast<char *>(base) + fbytes + ybytes);
+    p.epoch = 0; p.wait_ticks = 0; p.fallbacks = nullptr;
+    *bytes = fbytes + ybytes + align_up(sbytes, 256);
     return true;
 }
 
@@ -669,7 +725,7 @@ template <int PB> void launch_fin(const SPlan &p, const DecodeCall &c)
     const int G = p.Hq / p.Hkv;
     fs_finalize<PB><<<p.B * p.Hq, 128, 0, c.stream>>>(p.Ypart, static_cast<const uint16_t *>(c.mu), static_cast<uint16_t *>(c.out),
                                                       c.lse, p.Hkv, quot_multiplier(p.Hkv), G, quot_multiplier(G), p.nparts,
-                                                      p.rec, p.Hq);
+                                                      p.rec, p.Hq, p.flags, p.NGR);
 }
 
 }  // namespace
@@ -703,6 +759,9 @@ bool stream_decode(const DecodeCall &c, kvc_status *st)
         if (8 * p.chunk * p.F > 512) return false;
     }
     if (bytes > c.ws_bytes) { *st = KVC_ERR_WORKSPACE; return true; }
+    p.epoch = next_decode_epoch();
+    p.wait_ticks = decode_wait_ticks();
+    p.fallbacks = decode_fallback_counter();
 #if defined(KVC_TIMELINE)
     p.tl = c.ws_bytes >= bytes + kTimelineBytes
                ? reinterpret_cast<unsigned long long *>(static_cast<char *>(c.ws) + ((c.ws_bytes - kTimelineBytes) & ~size_t(255)))
