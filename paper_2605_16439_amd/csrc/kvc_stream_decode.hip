@@ -685,6 +685,7 @@ bool make_splan(SPlan &p, const DecodeCall &c, void *base, size_t *bytes)
 template <int G, int UP, int PS, int KS> bool launch_s(const SPlan &p, const DecodeCall &c)
 {
     constexpr size_t lds = stream_lds_bytes(KS, PS);
+    static_assert(lds <= 160 * 1024, "LDS of a compute unit");
     static bool attr_set[kMaxDevices] = {};
     if (!allow_lds(reinterpret_cast<const void *>(fs_stream<G, UP, PS, KS>), lds, attr_set)) return false;
     // without text rows the (never used) text pointers still have to be addresses that can be read
@@ -702,9 +703,11 @@ template <int G, int UP> int launch_for_ks(const SPlan &p, const DecodeCall &c, 
 {
     switch (KS) {
 #define KVC_STREAM_CASE(K) case K: return probe ? 1 : (launch_s<G, UP, 256, K>(p, c) ? 1 : -1);
-    KVC_STREAM_CASE(7)
-    KVC_STREAM_CASE(13)
-    KVC_STREAM_CASE(20)
+    // every compressed length whose tiles fit the LDS beside the staging tiles: m <= 672 of n = 1024
+    KVC_STREAM_CASE(1) KVC_STREAM_CASE(2) KVC_STREAM_CASE(3) KVC_STREAM_CASE(4) KVC_STREAM_CASE(5) KVC_STREAM_CASE(6)
+    KVC_STREAM_CASE(7) KVC_STREAM_CASE(8) KVC_STREAM_CASE(9) KVC_STREAM_CASE(10) KVC_STREAM_CASE(11) KVC_STREAM_CASE(12)
+    KVC_STREAM_CASE(13) KVC_STREAM_CASE(14) KVC_STREAM_CASE(15) KVC_STREAM_CASE(16) KVC_STREAM_CASE(17) KVC_STREAM_CASE(18)
+    KVC_STREAM_CASE(19) KVC_STREAM_CASE(20) KVC_STREAM_CASE(21)
 #undef KVC_STREAM_CASE
     default: return 0;
     }

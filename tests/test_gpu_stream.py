@@ -43,7 +43,7 @@ def _packed_layer(w, m):
     return L
 
 
-def _run(L, w, m, steps, append=True, t0=None):
+def _run(L, w, m, steps, append=True, t0=None, lse_tol=5e-2):
     th, U, mu = f64(L.p["theta"]), f64(L.p["U"]), f64(L.p["mu"])
     Kc_h, Vc_h = f64(L.gKc), unpack_vc(L.gVc, m, w.head_dim)
     Kt, Vt = f64(L.Kt).copy(), f64(L.Vt).copy()
@@ -62,7 +62,7 @@ def _run(L, w, m, steps, append=True, t0=None):
         e, ex, el = row_rel_err(out, ref), elem_rel_err(out, ref), np.abs(lse - lref).max()
         _say(f"[stream] {w.name} m={m} t={t} append={append} step {step}: row {e:.3e} element {ex:.3e} lse {el:.3e}")
         assert np.all(np.isfinite(out))
-        assert e <= tol(w) and ex <= 4 * tol(w) and el <= 5e-2
+        assert e <= tol(w) and ex <= 4 * tol(w) and el <= lse_tol
         if append:
             assert np.array_equal(f64(L.gKt)[:, :, t], f64(kn)) and np.array_equal(f64(L.gVt)[:, :, t], f64(vn))
             t += 1
@@ -84,13 +84,15 @@ def test_pack_theta_layout():
             assert np.array_equal(got[h][off], dense)
 
 
-# compressed lengths of the three compiled instances (7, 13, 20 steps of 32 rows): a short last block of
-# every width class, no short block, a last 16-row tile that is missing, the shortest and longest length
-@pytest.mark.parametrize("m", [410, 416, 400, 385, 415, 393, 205, 193, 224, 615, 609, 640])
+# compressed lengths over the compiled instances (1 .. 21 steps of 32 rows): a short last block of every width
+# class, no short block, a last 16-row tile that is missing, the shortest and longest length of an instance
+@pytest.mark.parametrize("m", [410, 416, 400, 385, 415, 393, 205, 193, 224, 615, 609, 640, 1, 7, 31, 33, 100, 300, 672])
 def test_compressed_lengths(m):
     w = _wl("st_len", 81, 2, 2, 4, 77)
     L = _packed_layer(w, m)
-    _run(L, w, m, 2)
+    # a single compressed row: every logit of a block is one bf16-rounded score times a row of theta with entries
+    # of order one, so the logits (and lse) carry the score's rounding, 2^-9 of logits of +-30
+    _run(L, w, m, 2, lse_tol=5e-2 if m > 1 else 2e-1)
 
 
 @pytest.mark.parametrize("text_len,append", [(0, True), (0, False), (1, True), (15, False), (16, True), (300, True),
@@ -126,11 +128,11 @@ def test_headline_shape_every_element():
     assert row_rel_err(out, out2) <= 2 * tol(w)
 
 
-def test_shapes_without_an_instance_take_the_other_kernels():
-    """theta_packed is optional help: a shape the one-pass kernel is not compiled for gives the same result
-    as the call without it, bit for bit."""
-    w = synth.Workload("st_other", 83, 1, 2, 14, 2, 128, "bf16", 256, 4, 0.6, 50, 2)
-    m = 103
+@pytest.mark.parametrize("w,m", [(synth.Workload("st_other", 83, 1, 2, 14, 2, 128, "bf16", 256, 4, 0.6, 50, 2), 103),
+                                 (_wl("st_long", 84, 1, 1, 2, 20), 673)])
+def test_shapes_without_an_instance_take_the_other_kernels(w, m):
+    """theta_packed is optional help: a shape the one-pass kernel is not compiled for (another block size, a
+    compressed length beyond what its LDS tiles hold) gives the same result as the call without it, bit for bit."""
     L = _packed_layer(w, m)
     q, kn, vn = synth.make_step_inputs(w, 0, 0)
     a, la = L.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
@@ -138,3 +140,51 @@ def test_shapes_without_an_instance_take_the_other_kernels():
     L2.compress()
     b, lb = L2.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
     assert np.array_equal(a, b) and np.array_equal(la, lb)
+
+
+def test_workgroups_that_do_not_wait_compute_every_share_themselves():
+    """The hand-over of the scores between the workgroups of a group is bounded: with the wait set to zero every
+    workgroup computes all shares alone (counted), same result; with the normal wait nobody does."""
+    w = _wl("st_alone", 85, 2, 2, 4, 60)
+    L = _packed_layer(w, 410)
+    L.ws.zero_()                                         # (a fresh allocation may hold anything: one slow call)
+    before = kv.lib().kvc_dev_decode_fallbacks()
+    _run(L, w, 410, 2)
+    assert kv.lib().kvc_dev_decode_fallbacks() == before, "normal calls must not fall back"
+    kv.lib().kvc_dev_decode_knobs(-1, -1, 0)
+    try:
+        L2 = _packed_layer(w, 410)
+        _run(L2, w, 410, 2)
+        assert kv.lib().kvc_dev_decode_fallbacks() > before
+    finally:
+        kv.lib().kvc_dev_decode_knobs(-1, -1, 2000)
+
+
+def test_replayed_from_a_hip_graph_with_garbage_in_the_workspace():
+    """The call only enqueues kernels, so it can be captured; replays with the workspace (arrival counters
+    included) overwritten in between must reproduce the eager result: a counter word that holds something else
+    ends in the compute-alone path, and the call's last kernel leaves zeros behind."""
+    w = _wl("st_graph", 86, 1, 2, 4, 40)
+    L = _packed_layer(w, 205)
+    q, kn, vn = synth.make_step_inputs(w, 0, 0)
+    gq, gkn, gvn = q.to(DEV), kn.to(DEV), vn.to(DEV)
+    taken = kv.lib().kvc_dev_stream_calls()
+    eager, _ = L.decode(gq, w.text_len, gkn, gvn)
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            kv.kvc_reconstruct_attend_decode(L.shape, L.params, gq, L.gKc, L.gVc, L.gKt, L.gVt, w.text_len, w.text_cap,
+                                             gkn, gvn, 0.0, L.out, L.lse, L.ws, stream=s)
+    torch.cuda.synchronize()
+    assert kv.lib().kvc_dev_stream_calls() == taken + 2
+    for rep in range(3):
+        L.out.zero_()
+        L.ws.fill_(0x5A if rep != 1 else 0xFF)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(f64(L.out), eager), f"replay {rep} differs from the eager call"
+        g.replay()                                         # and again on the zeros the first replay left
+        torch.cuda.synchronize()
+        assert np.array_equal(f64(L.out), eager), f"second replay {rep} differs from the eager call"
