@@ -57,9 +57,11 @@ def read_traffic(workload, compression, kernels, pyramid):
             t = json.load(f)
     except (OSError, ValueError):
         return None
-    same = (t.get("workload_name") == workload and abs(t.get("compression", -1.0) - compression) < 1e-9
-            and t.get("kernels") == kernels and not pyramid)
-    return t if same else None
+    if t.get("workload_name") != workload or abs(t.get("compression", -1.0) - compression) > 1e-9 or pyramid:
+        return None
+    if t.get("kernels") == kernels:
+        return t
+    return t.get("other_paths", {}).get(kernels)       # the same workload on the library's other kernel path
 
 
 def main():
