@@ -1,7 +1,7 @@
 // Device-side declarations shared by the decode kernels of libkvcapsule.so (kvc_fast_decode.hip,
-// kvc_cluster_decode.hip): register image types, index helpers, the decode plan, and text_part --
-// the complete attention part of 128 rows of the text cache, which both decode paths run as extra
-// workgroups.  Nothing here is part of the C ABI.
+// kvc_stream_decode.hip, kvc_full_decode.hip): register image types, index helpers, the decode plan, and text_part --
+// the complete attention part of 128 rows of the text cache, which the four-kernel decode and the
+// full-cache decode run as extra workgroups.  Nothing here is part of the C ABI.
 #pragma once
 #include "kvc_internal.h"
 
