@@ -274,6 +274,23 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
     lds_barrier();
     if (threadIdx.x == 0) __hip_atomic_fetch_add(flag, static_cast<u64>(1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     TS(4, 7);
+    // One word per 128-byte line of this workgroup's quarter of its image blocks' compressed values: memory
+    // delivers them into the L2 while steps 1 to 3 run, and step 4 then reads all of them at the L2's latency
+    // (requested by all four workgroups at once in step 4, every one of them would wait memory's latency for
+    // every line).
+    uint32_t touch, touch_u;
+    {
+        int zero;                                  // (keeps the load, which is from a read-only argument, behind the wait above)
+        asm volatile("s_mov_b32 %0, 0" : "=s"(zero)::"memory");
+        const size_t vbytes = static_cast<size_t>(UP) * m * D * 2;
+        const char *vb = reinterpret_cast<const char *>(Vc + (static_cast<size_t>(bh) * p.I + i0) * m * D);
+        touch = *reinterpret_cast<const uint32_t *>(vb + zero + min((static_cast<size_t>(s) * 512 + threadIdx.x) * 128, vbytes - 128));
+        // and of this workgroup's eighth of the slice of U (the head's other groups on this XCD read the same slice)
+        constexpr int LPRW = 2 * PS / 128;                                           // lines per row of the slice
+        const int line = (gl & 7) * 256 + (threadIdx.x & 255);
+        const int ur = min(line / LPRW, m - 1), ul = line % LPRW;
+        touch_u = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(U + (static_cast<size_t>(h) * m + ur) * n + p0) + zero + ul * 128);
+    }
 
     // ---- the text rows of this workgroup's share, completely, while the compressed keys are on their way:
     // logits, weights relative to the share's own maximum per head, and the weighted sum of the value rows
@@ -471,6 +488,7 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
     lds_barrier();
     TS(4, 3);
 
+    asm volatile("" ::"v"(touch), "v"(touch_u));
     // ---- step 3: W^T[j][row] = sum_pos U[j][pos] P[row][pos] for this wave's tiles of 16 rows of U ------
     const char *vc_base = reinterpret_cast<const char *>(Vc + (static_cast<size_t>(bh) * p.I + i0) * m * D);
     const int cch = 16 * wave + r16;                     // this lane's channel in step 4
