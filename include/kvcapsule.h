@@ -189,7 +189,7 @@ kvc_status kvc_pack_theta(const kvc_shape *shape, const void *theta, void *packe
  *             clamped on the device to [0, I] and [0, text_cap] ([0, text_cap - 1] with a new token).
  *             A sequence left with no key at all gets NaNs.
  * Everything else as in kvc_reconstruct_attend_decode, the kernels included (matrix cores for the shapes
- * that have them; a uniform batch gives the uniform call's result bit for bit).  Capsule slots beyond
+ * that have them, the one-pass kernel with kvc_params.theta_packed; a uniform batch gives the uniform call's result bit for bit).  Capsule slots beyond
  * n_images[b] may be read but never reach the result, whatever they hold (NaNs included); text rows
  * beyond the sequence's own are not read.
  * Errors: as kvc_reconstruct_attend_decode, plus NULL / misaligned count arrays, text_cap < 1. */

@@ -45,6 +45,9 @@ struct SPlan {
     unsigned epoch;
     int wait_ticks;
     unsigned *fallbacks;
+    // ragged batch (instances with RAG = true): n_img[b] image blocks, tlen[b] text rows before the call; I, t
+    // and t_in are then the largest values a sequence may have.  Null in a uniform call.
+    const int32_t *n_img, *tlen;
 #if defined(KVC_TIMELINE)
     unsigned long long *tl;       // timeline slots, see TS()
 #endif
@@ -103,7 +106,7 @@ constexpr size_t stream_lds_bytes(int KS, int PS)
 // long before it is used), so what can be wave-uniform is kept in scalar registers -- the wavefront's index is
 // read with readfirstlane, tile bases are scalar, lanes add a fixed 32-bit offset -- and clamps and masks are
 // compiled only into the rounds whose tiles can reach the end of the compressed axis.
-template <int G, int UP, int PS, int KS>
+template <int G, int UP, int PS, int KS, bool RAG>
 __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q, const uint16_t *__restrict__ Kc,
                                                  const uint16_t *__restrict__ thp, const uint16_t *__restrict__ U,
                                                  const uint16_t *__restrict__ Vc, uint16_t *__restrict__ Kt,
@@ -159,8 +162,17 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
         for (int ks = 0; ks < 4; ++ks) qf[ks] = qp[4 * ks];
     }
     const bool fresh = k_new != nullptr;
+    // this sequence's counts: image blocks it has, text rows before the call (the new token goes there) and
+    // attended (RAG: a ragged batch, the sequence's own counts are read; otherwise the call's values, at no cost)
+    int n_img = p.I, t_in = p.t_in, t = p.t;
+    if constexpr (RAG) {
+        n_img = min(max(p.n_img[b], 0), p.I);
+        const int tlb = max(p.tlen[b], 0);
+        t_in = min(tlb, p.t_in);
+        t = fresh ? t_in + 1 : min(tlb, p.t);
+    }
     const int TT = p.TT, TR = 16 * TT, x0 = pi * TR;
-    const int xlast = max(p.t - 1, 0);
+    const int xlast = max(t - 1, 0);
     // Rows of keys (and, below, of U) are loaded whole -- 16 lanes per 256-byte row, so that a quarter-wave
     // reads contiguous lines -- and turned into MFMA operands (16 rows x 16 bytes per quarter-wave) through
     // this wavefront's LDS tile; the 16-byte pieces of row r are stored at piece ^ r, which keeps both the
@@ -169,7 +181,7 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
     const int krow = lane >> 4, kpc = lane & 15;       // key tile: row within a pass of four, 16-byte piece
     // (the new token's row is not in the cache yet: its values are loaded on the side and selected in)
     const uint16_t *kn_p = fresh ? k_new + static_cast<size_t>(bh) * D : q, *vn_p = fresh ? v_new + static_cast<size_t>(bh) * D : q;
-    const int t_new = fresh ? p.t_in : -1;
+    const int t_new = fresh ? t_in : -1;
     const char *kt_base = reinterpret_cast<const char *>(Kt + static_cast<size_t>(bh) * p.cap * D);
     const char *vt_base = reinterpret_cast<const char *>(Vt + static_cast<size_t>(bh) * p.cap * D);
     u32x4 tk[4];
@@ -308,7 +320,7 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
         if (wave < TT) {
             f32x4 tl;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) tl[e] = (x0 + 16 * wave + 4 * kg + e < p.t) ? acc[e] * p.scale : -INFINITY;
+            for (int e = 0; e < 4; ++e) tl[e] = (x0 + 16 * wave + 4 * kg + e < t) ? acc[e] * p.scale : -INFINITY;
             *reinterpret_cast<f32x4 *>(sTL + r16 * kLTL + 16 * wave + 4 * kg) = tl;
         }
     }
@@ -339,7 +351,10 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
 #pragma unroll
         for (int rr = 0; rr < 2 * kTT; rr += 2)
             if (rr < 2 * TT) {          // wave-uniform: arithmetic only, the rows were requested at the top
-                const uint32_t va = xv0 + rr == t_new ? tvn : tv[rr], vc = xv0 + rr + 1 == t_new ? tvn : tv[rr + 1];
+                // (rows beyond the sequence's own are clamped copies with weight zero; in a ragged batch they may be
+                // anything, so they are selected away rather than multiplied)
+                const uint32_t va = xv0 + rr == t_new ? tvn : (!RAG || xv0 + rr < t) ? tv[rr] : 0u;
+                const uint32_t vc = xv0 + rr + 1 == t_new ? tvn : (!RAG || xv0 + rr + 1 < t) ? tv[rr + 1] : 0u;
                 const float a0 = bf_lo(va), a1 = bf_hi(va), c0 = bf_lo(vc), c1 = bf_hi(vc);
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
@@ -561,17 +576,21 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
     };
     const int un_mine = r16 / G, g_mine = min(r16 - un_mine * G, G - 1);
     float rmx[UP];
-    // joint maximum of this lane's query head over the workgroup's image blocks and text rows
+    // joint maximum of this lane's query head over the workgroup's image blocks and text rows.  An image block
+    // the sequence does not have (ragged batch) takes no part: whatever its capsule slot holds went through the
+    // products above in rows and blocks of its own, which are selected away here (never multiplied by zero:
+    // the slot may hold NaNs)
     float gm = sTm[g_mine];
 #pragma unroll
     for (int u = 0; u < UP; ++u) {
-        rmx[u] = row_max(u * G + g_mine);
+        rmx[u] = (!RAG || i0 + u < n_img) ? row_max(u * G + g_mine) : -INFINITY;
         gm = fmaxf(gm, rmx[u]);
     }
+    if constexpr (RAG) gm = gm == -INFINITY ? 0.f : gm;       // nothing at all in this workgroup: a record without mass
     f32x4 ysum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int u = 0; u < UP; ++u) {
-        const bool mine = un_mine == u && r16 < RU;        // rows of other blocks: cross terms
+        const bool mine = un_mine == u && r16 < RU && (!RAG || i0 + u < n_img);        // rows of other blocks: cross terms
         const float sc = __expf(rmx[u] - gm);
 #pragma unroll
         for (int e = 0; e < 4; ++e) ysum[e] += mine ? sc * o[u][e] : 0.f;
@@ -602,17 +621,17 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
         if (wave == 0 && kg == 0) {
             float vs = 0.f;
 #pragma unroll
-            for (int u = 0; u < UP; ++u) vs += row_sum(u * G + r16) * __expf(rmx[u] - gm);
-            yp[G * D + r16] = gm;
+            for (int u = 0; u < UP; ++u) vs += (!RAG || i0 + u < n_img) ? row_sum(u * G + r16) * __expf(rmx[u] - gm) : 0.f;
+            yp[G * D + r16] = (RAG && vs + tsc * sTm[16 + r16] == 0.f) ? -INFINITY : gm;
             yp[G * D + G + r16] = vs + tsc * sTm[16 + r16];
             yp[G * D + 2 * G + r16] = vs;
         }
     }
     // Sec. 3.2: the text cache keeps growing as in the backbone -- store the new token's k, v
-    if (fresh && p.t_in >= x0 && p.t_in < x0 + TR && threadIdx.x < 32) {
+    if (fresh && t_in >= x0 && t_in < x0 + TR && threadIdx.x < 32) {
         const int half = threadIdx.x >> 4, piece = threadIdx.x & 15;
         const uint16_t *src = (half ? v_new : k_new) + static_cast<size_t>(bh) * D;
-        uint16_t *dst = (half ? Vt : Kt) + (static_cast<size_t>(bh) * p.cap + p.t_in) * D;
+        uint16_t *dst = (half ? Vt : Kt) + (static_cast<size_t>(bh) * p.cap + t_in) * D;
         *(reinterpret_cast<u32x4 *>(dst) + piece) = *(reinterpret_cast<const u32x4 *>(src) + piece);
     }
     TS(4, 5);
@@ -696,24 +715,30 @@ bool make_splan(SPlan &p, const DecodeCall &c, void *base, size_t *bytes)
     p.Ypart = reinterpret_cast<float *>(static_cast<char *>(base) + fbytes);
     p.Sx = reinterpret_cast<uint16_t *>(static_cast<char *>(base) + fbytes + ybytes);
     p.epoch = 0; p.wait_ticks = 0; p.fallbacks = nullptr;
+    p.n_img = c.n_images_dev; p.tlen = c.text_len_dev;
     *bytes = fbytes + ybytes + align_up(sbytes, 256);
+    return true;
+}
+
+template <int G, int UP, int PS, int KS, bool RAG> bool launch_s2(const SPlan &p, const DecodeCall &c)
+{
+    constexpr size_t lds = stream_lds_bytes(KS, PS);
+    static_assert(lds <= 160 * 1024, "LDS of a compute unit");
+    static bool attr_set[kMaxDevices] = {};
+    if (!allow_lds(reinterpret_cast<const void *>(fs_stream<G, UP, PS, KS, RAG>), lds, attr_set)) return false;
+    // without text rows the (never used) text pointers still have to be addresses that can be read
+    uint16_t *Kt = static_cast<uint16_t *>(c.Kt), *Vt = static_cast<uint16_t *>(c.Vt);
+    if (p.cap == 0 || !Kt || !Vt) { Kt = Vt = const_cast<uint16_t *>(static_cast<const uint16_t *>(c.q)); }
+    fs_stream<G, UP, PS, KS, RAG><<<8 * p.chunk * p.F, 512, lds, c.stream>>>(
+        static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc), static_cast<const uint16_t *>(c.theta_packed),
+        static_cast<const uint16_t *>(c.U), static_cast<const uint16_t *>(c.Vc), Kt, Vt,
+        static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new), p);
     return true;
 }
 
 template <int G, int UP, int PS, int KS> bool launch_s(const SPlan &p, const DecodeCall &c)
 {
-    constexpr size_t lds = stream_lds_bytes(KS, PS);
-    static_assert(lds <= 160 * 1024, "LDS of a compute unit");
-    static bool attr_set[kMaxDevices] = {};
-    if (!allow_lds(reinterpret_cast<const void *>(fs_stream<G, UP, PS, KS>), lds, attr_set)) return false;
-    // without text rows the (never used) text pointers still have to be addresses that can be read
-    uint16_t *Kt = static_cast<uint16_t *>(c.Kt), *Vt = static_cast<uint16_t *>(c.Vt);
-    if (p.cap == 0 || !Kt || !Vt) { Kt = Vt = const_cast<uint16_t *>(static_cast<const uint16_t *>(c.q)); }
-    fs_stream<G, UP, PS, KS><<<8 * p.chunk * p.F, 512, lds, c.stream>>>(
-        static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc), static_cast<const uint16_t *>(c.theta_packed),
-        static_cast<const uint16_t *>(c.U), static_cast<const uint16_t *>(c.Vc), Kt, Vt,
-        static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new), p);
-    return true;
+    return p.n_img ? launch_s2<G, UP, PS, KS, true>(p, c) : launch_s2<G, UP, PS, KS, false>(p, c);
 }
 
 // instances: (group size, compressed length in 32-row steps)
@@ -768,7 +793,8 @@ size_t stream_decode_ws_bytes(const kvc_shape &s, int32_t max_text)
 // true: the call was taken (status in *st); false: not this path's shape, nothing was launched
 bool stream_decode(const DecodeCall &c, kvc_status *st)
 {
-    if (g_stream_mode == 0 || !c.theta_packed || c.n_images_dev || c.static_variant) return false;
+    if (g_stream_mode == 0 || !c.theta_packed || c.static_variant) return false;
+    if ((c.n_images_dev == nullptr) != (c.text_len_dev == nullptr)) return false;
     if (c.s.dtype != KVC_BF16 || c.s.head_dim != D) return false;
     SPlan p;
     size_t bytes = 0;

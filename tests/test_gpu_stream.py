@@ -188,3 +188,64 @@ def test_replayed_from_a_hip_graph_with_garbage_in_the_workspace():
         g.replay()                                         # and again on the zeros the first replay left
         torch.cuda.synchronize()
         assert np.array_equal(f64(L.out), eager), f"second replay {rep} differs from the eager call"
+
+
+@pytest.mark.parametrize("n_images,text_len,append", [
+    ([8, 0, 1, 3], [300, 0, 129, 17], True),
+    ([8, 0, 1, 3], [302, 1, 128, 17], False),
+    ([0, 0, 5, 8], [0, 200, 301, 64], True),
+])
+def test_ragged_batch(n_images, text_len, append):
+    """kvc_reconstruct_attend_decode_ragged on the one-pass kernel: sequences with their own numbers of image
+    blocks (odd counts split a workgroup's pair) and text rows; capsule slots and text rows a sequence does not
+    have hold NaNs on the device and must not matter."""
+    w = synth.Workload("st_rag", 87, 1, 4, 14, 2, 128, "bf16", 1024, 8, 0.6, 302, 2)
+    m = 410
+    L = _packed_layer(w, m)
+    B, I, cap = w.batch, w.n_images, w.text_cap
+    gKc, gVc = L.gKc.clone(), L.gVc.clone()
+    Kc_h, Vc_h = f64(gKc), unpack_vc(gVc, m, w.head_dim)
+    rows = [t + (1 if append else 0) for t in text_len]
+    for b in range(B):
+        gKc[b, :, n_images[b]:] = float("nan")
+        gVc[b, :, n_images[b]:] = float("nan")
+        L.gKt[b, :, rows[b]:] = float("nan")
+        L.gVt[b, :, rows[b]:] = float("nan")
+    ni = torch.tensor(n_images, dtype=torch.int32, device=DEV)
+    tl = torch.tensor(text_len, dtype=torch.int32, device=DEV)
+    Kt, Vt = f64(L.Kt).copy(), f64(L.Vt).copy()
+    th, U, mu = f64(L.p["theta"]), f64(L.p["U"]), f64(L.p["mu"])
+    q, kn, vn = synth.make_step_inputs(w, 0, 0)
+    gkn, gvn = (kn.to(DEV), vn.to(DEV)) if append else (None, None)
+    taken = kv.lib().kvc_dev_stream_calls()
+    for rep in range(2):        # appending the same token again changes nothing
+        kv.kvc_reconstruct_attend_decode_ragged(L.shape, L.params, q.to(DEV), gKc, gVc, L.gKt, L.gVt, ni, tl, cap,
+                                                gkn, gvn, 0.0, L.out, L.lse, L.ws)
+        torch.cuda.synchronize()
+    assert kv.lib().kvc_dev_stream_calls() == taken + 2
+    ref, lref = orc.reconstruct_attend_decode_ragged(f64(q), Kc_h, Vc_h, th, U, mu, w.n_img_tokens, n_images,
+                                                     text_len, Kt, Vt, f64(kn) if append else None,
+                                                     f64(vn) if append else None)
+    out, lse = f64(L.out), f64(L.lse)
+    e, ex = row_rel_err(out, ref), elem_rel_err(out, ref)
+    _say(f"[stream, ragged] append={append}: row {e:.3e} element {ex:.3e} lse {np.abs(lse - lref).max():.3e}")
+    assert np.all(np.isfinite(out)) and np.all(np.isfinite(lse))
+    assert e <= tol(w) and ex <= 4 * tol(w) and np.abs(lse - lref).max() <= 5e-2
+    if append:
+        for b in range(B):
+            assert np.array_equal(f64(L.gKt)[b, :, text_len[b]], f64(kn)[b])
+            assert np.array_equal(f64(L.gVt)[b, :, text_len[b]], f64(vn)[b])
+
+
+def test_ragged_uniform_batch_equals_the_uniform_call():
+    w = _wl("st_ragu", 88, 2, 2, 4, 90)
+    L = _packed_layer(w, 410)
+    q, kn, vn = synth.make_step_inputs(w, 0, 0)
+    a, la = L.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
+    L2 = _packed_layer(w, 410)
+    kv.kvc_reconstruct_attend_decode_ragged(L2.shape, L2.params, q.to(DEV), L2.gKc, L2.gVc, L2.gKt, L2.gVt,
+                                            torch.full((w.batch,), w.n_images, dtype=torch.int32, device=DEV),
+                                            torch.full((w.batch,), w.text_len, dtype=torch.int32, device=DEV),
+                                            w.text_cap, kn.to(DEV), vn.to(DEV), 0.0, L2.out, L2.lse, L2.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(f64(L2.out), a) and np.array_equal(f64(L2.lse), la)
