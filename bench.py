@@ -75,6 +75,7 @@ def main():
                     help="per-layer schedule: compression ramps linearly over the layers from "
                          "(c - 0.2) to (c + 0.2), averaging --compression")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debug)")
+    ap.add_argument("--batch", type=int, default=0, help="override the batch size (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--generic", action="store_true", help="force the scalar kernels")
     ap.add_argument("--no-packed-theta", action="store_true",
@@ -102,6 +103,8 @@ def main():
     w = synth.WORKLOADS[args.workload].with_(compression=args.compression)
     if args.layers:
         w = w.with_(layers=args.layers)
+    if args.batch:
+        w = w.with_(batch=args.batch)
     K, W = args.steps, args.warmup
     L = w.layers
     # compressed length per layer: one value, or a pyramid schedule (Sec. 3.2: per-layer budgets

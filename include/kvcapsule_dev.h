@@ -62,7 +62,7 @@ void kvc_dev_full_decode_chunk_steps(int32_t steps);
 void kvc_dev_decode_knobs(int32_t row_tiles, int32_t separate, int32_t wait_ticks);
 
 /* Which decode kernels serve a call that comes with kvc_params.theta_packed (process-wide):
- *  -1 the built-in rule (the one-pass kernel for calls of at most two workgroups per compute unit whose
+ *  -1 the built-in rule (the one-pass kernel for calls of fewer than two workgroups per compute unit whose
  *     shape has an instance), 0 never the one-pass kernel, 1 the one-pass kernel wherever an instance exists. */
 void kvc_dev_stream_decode(int32_t mode);
 

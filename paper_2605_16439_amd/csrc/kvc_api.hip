@@ -521,6 +521,6 @@ const char *kvc_status_string(int32_t status)
     }
 }
 
-const char *kvc_version(void) { return "0.2"; }
+const char *kvc_version(void) { return "0.3"; }        // 0.3: kvc_params grew by theta_packed
 
 }  // extern "C"

@@ -249,3 +249,14 @@ def test_ragged_uniform_batch_equals_the_uniform_call():
                                             w.text_cap, kn.to(DEV), vn.to(DEV), 0.0, L2.out, L2.lse, L2.ws)
     torch.cuda.synchronize()
     assert np.array_equal(f64(L2.out), a) and np.array_equal(f64(L2.lse), la)
+
+
+def test_more_workgroups_than_compute_units():
+    """512 workgroups (two rounds over the chip): the four workgroups of a group are dealt out next to each other,
+    so they still meet; no fall-back after the first call."""
+    w = _wl("st_big", 89, 16, 2, 8, 70)
+    L = _packed_layer(w, 205)
+    L.ws.zero_()
+    before = kv.lib().kvc_dev_decode_fallbacks()
+    _run(L, w, 205, 2)
+    assert kv.lib().kvc_dev_decode_fallbacks() == before
