@@ -1,6 +1,7 @@
 // Decode step in one pass per workgroup ("stream" form of Alg. 1, "Fused KVCapsule"): a workgroup owns
 // UP image blocks of one (batch element, KV head) and a slice of PS of the n positions, and takes its
-// rows through all four products without meeting any other workgroup:
+// rows through all four products, meeting the other slices' workgroups once (the scores, which all of them
+// need, are computed a share each and handed over through the L2):
 //     S = sigma q Kc^T            (Alg. 1 step 1; Kc streamed once, scores kept in LDS)
 //     L = S theta[:, slice]       (step 2; theta in its packed form, straight from memory into MFMA operands)
 //     P = exp(L - slice max)      (softmax numerators relative to the slice's own maximum)
@@ -10,10 +11,10 @@
 // the joint softmax over all slices, image blocks and text rows (Sec. 3.2: reconstructed vision KV and
 // text KV go through one attention).  A share of the text rows rides along in every workgroup.
 // Against the four-kernel form (kvc_fast_decode.hip) nothing crosses a kernel boundary but the part
-// records, and no workgroup waits for another; the price is that theta and U are read once per group of
-// UP image blocks instead of once per 64 query rows.  Every loop below has a compile-time trip count and
-// no memory operation sits under a run-time test, so the compiler's count of loads in flight stays exact
-// and each phase's first loads are requested while the previous phase still computes.
+// records; the price is that theta and U are read once per group of UP image blocks instead of once per
+// 64 query rows.  Every loop of the main path has a compile-time trip count and no load sits under a
+// run-time test, so the compiler's count of loads in flight stays exact and each phase's first loads are
+// requested while the previous phase still computes.
 #include <algorithm>
 #include <atomic>
 
