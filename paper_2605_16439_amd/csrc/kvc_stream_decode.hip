@@ -762,7 +762,10 @@ int launch_stream(const SPlan &p, const DecodeCall &c, bool probe)
 {
     const int G = p.Hq / p.Hkv, KS = (p.m + 31) / 32;
     switch (G) {
+    case 4: return launch_for_ks<4, 4>(p, c, KS, probe);
+    case 6: return launch_for_ks<6, 2>(p, c, KS, probe);
     case 7: return launch_for_ks<7, 2>(p, c, KS, probe);
+    case 8: return launch_for_ks<8, 2>(p, c, KS, probe);
     default: return 0;
     }
 }
@@ -782,12 +785,11 @@ long stream_decode_calls() { return g_stream_calls.load(); }
 
 size_t stream_decode_ws_bytes(const kvc_shape &s, int32_t max_text)
 {
+    // (the text length only decides whether a call is taken, not the size)
     DecodeCall c;
-    c.s = s; c.t = c.t_in = c.cap = max_text; c.scale = 1.f;
+    c.s = s; c.t = c.t_in = 0; c.cap = max_text; c.scale = 1.f;
     SPlan p;
     size_t bytes = 0;
-    // the text share per workgroup only decides whether the call is taken, not the size
-    c.t = c.t_in = 0;
     return make_splan(p, c, nullptr, &bytes) ? bytes : 0;
 }
 

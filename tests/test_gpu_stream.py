@@ -260,3 +260,12 @@ def test_more_workgroups_than_compute_units():
     before = kv.lib().kvc_dev_decode_fallbacks()
     _run(L, w, 205, 2)
     assert kv.lib().kvc_dev_decode_fallbacks() == before
+
+
+@pytest.mark.parametrize("g,m", [(4, 410), (6, 410), (8, 410), (4, 77), (6, 205), (8, 615)])
+def test_other_group_sizes(g, m):
+    """The kernel is compiled for 4, 6, 7 and 8 query heads per KV head (four image blocks per workgroup for 4,
+    two otherwise)."""
+    w = synth.Workload("st_g%d" % g, 90 + g, 1, 2, g * 2, 2, 128, "bf16", 1024, 4, 0.6, 70, 2)
+    L = _packed_layer(w, m)
+    _run(L, w, m, 2)
