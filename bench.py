@@ -197,6 +197,7 @@ def main():
         for a in step:
             layer_step(a)
     ev_end.record()
+    t_issued = time.perf_counter()          # the host has handed over every call; the device is still working
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     wall = t1 - t0
@@ -317,6 +318,7 @@ def main():
                                "with --generic)",
                      "algorithmic_bytes_per_launch": abytes, "us_per_launch": call_us,
                      "us_per_launch_event_pair_each": call_us_pairs,
+                     "host_us_per_launch": (t_issued - t0) * 1e6 / (K * L),
                      "measured_read_ceiling": read_ceiling},
         "compress": compress_report(w, ms, comp_ms / (L * copies)),
     }
