@@ -157,3 +157,30 @@ def test_capsule_value_offset_is_the_documented_blocked_layout():
     assert L.kvc_unpack_values(None, fake, 1, 8, 8, kv.KVC_BF16, None) == kv.KVC_ERR_NULL
     assert L.kvc_unpack_values(fake, fake, 1, 0, 8, kv.KVC_BF16, None) == kv.KVC_ERR_SHAPE
     assert L.kvc_unpack_values(fake, fake, 1, 8, 8, 9, None) == kv.KVC_ERR_DTYPE
+
+
+def test_pack_theta_rejects_bad_arguments_before_any_launch():
+    s, p = _valid()
+    L = kv.lib()
+    fake, fake2 = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x20000)
+    assert L.kvc_pack_theta(None, fake, fake2, None) == kv.KVC_ERR_NULL
+    assert L.kvc_pack_theta(ctypes.byref(s), None, fake2, None) == kv.KVC_ERR_NULL
+    assert L.kvc_pack_theta(ctypes.byref(s), fake, None, None) == kv.KVC_ERR_NULL
+    assert L.kvc_pack_theta(ctypes.byref(s), fake, fake, None) == kv.KVC_ERR_SHAPE          # in place
+    assert L.kvc_pack_theta(ctypes.byref(s), ctypes.c_void_p(0x10008), fake2, None) == kv.KVC_ERR_ALIGN
+    # a misaligned packed theta in the parameters of a decode call is refused like any other pointer
+    bad = kv.KvcParams(p.key_idx, p.theta, p.U, p.mu, 0x50004)
+    assert _decode(s, bad) == kv.KVC_ERR_ALIGN
+
+
+def test_packed_theta_layout_is_the_value_layout_with_positions_for_channels():
+    """Element (row j, position pos) of a record of m x n elements, rows in blocks of 8, each block [n][w]."""
+    m, n = 19, 24
+    seen = set()
+    for j in range(m):
+        for pos in range(n):
+            w = min(8, m - 8 * (j // 8))
+            off = kv.lib().kvc_capsule_value_offset(j, pos, m, n)
+            assert off == (j // 8) * 8 * n + pos * w + j % 8
+            seen.add(off)
+    assert seen == set(range(m * n))          # a permutation of the record: same size as theta
