@@ -79,7 +79,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--generic", action="store_true", help="force the scalar kernels")
     ap.add_argument("--no-packed-theta", action="store_true",
-                    help="do not pass kvc_params.theta_packed: every call takes the four-kernel form")
+                    help="do not pass the packed forms of theta and U: every call takes the four-kernel form")
     ap.add_argument("--no-full-baseline", action="store_true",
                     help="skip the full-cache (All KV) decode that is timed beside the capsule path")
     ap.add_argument("--read-probe", type=int, default=4, metavar="GiB",
@@ -134,10 +134,11 @@ def main():
         l = lc % L
         shape, cshape = shapes[l], (w.batch, w.n_kv_heads, w.n_images, ms[l], w.head_dim)
         p = synth.make_params(w, ms[l], l, device=dev)
-        # theta re-tiled once at load time (kvc_pack_theta): calls whose shape has a one-pass kernel use it
+        # theta and U re-tiled once at load time (kvc_pack_theta, kvc_pack_u): calls whose shape has a one-pass kernel use them
         if not args.generic and not args.no_packed_theta:
             p["theta_packed"] = kv.kvc_pack_theta(shape, p["theta"])
-        params = kv.make_params(p["key_idx"], p["theta"], p["U"], p["mu"], p.get("theta_packed"))
+            p["U_packed"] = kv.kvc_pack_u(shape, p["U"])
+        params = kv.make_params(p["key_idx"], p["theta"], p["U"], p["mu"], p.get("theta_packed"), p.get("U_packed"))
         Kp, Vp = synth.make_prefill_kv(w, l, 0, 0, device=dev)
         Kc = torch.empty(cshape, dtype=dt, device=dev)
         Vc = torch.empty(cshape, dtype=dt, device=dev)

@@ -92,8 +92,15 @@ typedef struct {
     const void *mu;         /* mu : [H_kv][d] value centre (Sec. 3.1, Values)        */
     const void *theta_packed; /* optional (may be NULL): theta re-tiled once by      */
                             /* kvc_pack_theta, same size; decode calls whose shape   */
-                            /* has a one-pass kernel use it, all others read theta.  */
+                            /* has a one-pass kernel use it (together with U_packed),*/
+                            /* all others read theta.                                */
                             /* Unused by compress.                                   */
+    const void *U_packed;   /* optional (may be NULL): U re-tiled once by kvc_pack_u */
+                            /* for the decode side, same size.  The one-pass decode  */
+                            /* kernel runs when BOTH packed forms are given; U       */
+                            /* itself stays required (compress and the other decode  */
+                            /* kernels read it), so a caller who opts in keeps       */
+                            /* H_kv m n more elements per layer.                     */
 } kvc_params;
 
 /* |M| = ceil(l_r n) with retention l_r = 1 - compression_ratio (Sec. 3.1, Keys),
@@ -179,6 +186,16 @@ kvc_status kvc_reconstruct_attend_decode(const kvc_shape *shape, const kvc_param
  *  without a one-pass kernel read it).
  * Errors: NULL pointers, bad shape, theta == packed, misalignment. */
 kvc_status kvc_pack_theta(const kvc_shape *shape, const void *theta, void *packed, void *stream);
+
+/* The same for U on the decode side.  Alg. 1 step 3 contracts the probabilities with U over the POSITION
+ * index; a matrix-core operand (8 consecutive positions of one row j) is 16 contiguous bytes of [H_kv][m][n]
+ * already, but the 16 rows of a tile are n elements apart, and loads of that shape run at a fifth of the
+ * rate of whole lines.  The packed form puts the 16-byte pieces of consecutive ROWS next to each other:
+ *   per KV head one record of m n elements; positions in blocks of 8, each block row-major [m][8];
+ *   element (j, pos) sits at kvc_capsule_value_offset(pos, j, n, m) (the layout of kvc_pack_theta with the
+ *   roles of rows and positions exchanged).  n must be a multiple of 8.
+ * Pass the result as kvc_params.U_packed.  Errors: as kvc_pack_theta; n % 8 != 0 is KVC_ERR_UNSUPPORTED. */
+kvc_status kvc_pack_u(const kvc_shape *shape, const void *U, void *packed, void *stream);
 
 /* Ragged batch: the decode step for sequences with their own numbers of image blocks and text rows.
  * Sequence b attends the first n_images[b] of its I = shape->n_images capsule slots and text_len[b]

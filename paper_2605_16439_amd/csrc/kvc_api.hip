@@ -39,7 +39,7 @@ kvc_status check_params(const kvc_params *p, bool need_idx, bool need_theta)
     if (need_idx && !p->key_idx) return KVC_ERR_NULL;
     if (need_theta && !p->theta) return KVC_ERR_NULL;
     if (!aligned16(p->U) || !aligned16(p->mu)) return KVC_ERR_ALIGN;
-    if (need_theta && (!aligned16(p->theta) || !aligned16(p->theta_packed))) return KVC_ERR_ALIGN;
+    if (need_theta && (!aligned16(p->theta) || !aligned16(p->theta_packed) || !aligned16(p->U_packed))) return KVC_ERR_ALIGN;
     if (need_idx && (reinterpret_cast<uintptr_t>(p->key_idx) & 3u)) return KVC_ERR_ALIGN;
     return KVC_OK;
 }
@@ -72,6 +72,7 @@ kvc_status prepare_decode(DecodeCall &c, const kvc_shape *shape, const kvc_param
     c.s = *shape;
     c.theta = params->theta;
     c.theta_packed = params->theta_packed;
+    c.U_packed = params->U_packed;
     c.U = params->U;
     c.mu = params->mu;
     c.q = q;
@@ -283,7 +284,7 @@ kvc_status kvc_static_attend_decode(const kvc_shape *shape, const void *q, const
 {
     // theta, U and mu are not part of this variant; q stands in for them (never read)
     kvc_params none;
-    none.key_idx = nullptr; none.theta = q; none.U = q; none.mu = q; none.theta_packed = nullptr;
+    none.key_idx = nullptr; none.theta = q; none.U = q; none.mu = q; none.theta_packed = nullptr; none.U_packed = nullptr;
     DecodeCall c;
     kvc_status st = prepare_decode(c, shape, &none, q, Kc, Vc, K_text, V_text, text_len, text_cap, k_new, v_new,
                                    softmax_scale, out, lse_out, workspace, workspace_bytes, stream);
@@ -313,6 +314,17 @@ kvc_status kvc_pack_theta(const kvc_shape *shape, const void *theta, void *packe
     if (theta == packed) return KVC_ERR_SHAPE;
     if (!aligned16(theta) || !aligned16(packed)) return KVC_ERR_ALIGN;
     return pack_theta(*shape, theta, packed, static_cast<hipStream_t>(stream));
+}
+
+kvc_status kvc_pack_u(const kvc_shape *shape, const void *U, void *packed, void *stream)
+{
+    kvc_status st = check_shape(shape);
+    if (st != KVC_OK) return st;
+    if (!U || !packed) return KVC_ERR_NULL;
+    if (U == packed) return KVC_ERR_SHAPE;
+    if (!aligned16(U) || !aligned16(packed)) return KVC_ERR_ALIGN;
+    if (shape->n_img_tokens % 8) return KVC_ERR_UNSUPPORTED;         // whole blocks of 8 positions
+    return pack_u(*shape, U, packed, static_cast<hipStream_t>(stream));
 }
 
 // ---- the blocked layout of the compressed values, for callers ---------------------------------------
@@ -521,6 +533,6 @@ const char *kvc_status_string(int32_t status)
     }
 }
 
-const char *kvc_version(void) { return "0.3"; }        // 0.3: kvc_params grew by theta_packed
+const char *kvc_version(void) { return "0.4"; }        // 0.3, 0.4: kvc_params grew by theta_packed, U_packed
 
 }  // extern "C"

@@ -60,6 +60,7 @@ struct DecodeCall {
     kvc_shape s;
     const void *theta, *U, *mu;
     const void *theta_packed = nullptr;   // theta in the blocked form of kvc_pack_theta, or null
+    const void *U_packed = nullptr;       // U in the blocked form of kvc_pack_u, or null
     const void *q, *Kc, *Vc;
     void *Kt, *Vt;
     int32_t t;        // text rows attended (new token included when appended)
@@ -151,6 +152,7 @@ size_t stream_decode_ws_bytes(const kvc_shape &s, int32_t max_text);
 void stream_decode_knob(int mode);
 long stream_decode_calls();
 kvc_status pack_theta(const kvc_shape &s, const void *theta, void *packed, hipStream_t stream);
+kvc_status pack_u(const kvc_shape &s, const void *U, void *packed, hipStream_t stream);
 // full-cache decode, bf16, head_dim 128
 bool fast_full_supported(int dtype, int head_dim, int G);
 size_t fast_full_ws_bytes(int B, int Hq, int Hkv);

@@ -98,7 +98,7 @@ constexpr size_t stream_lds_bytes(int KS, int PS)
 {
     return static_cast<size_t>(2 * 16 * (32 * KS + 16) + 16 * (PS + 16)) * 2 +
            static_cast<size_t>(16 * kLTL + 8 * 8 * D + 2 * 8 * 16 + 2 * 16) * 4 +
-           static_cast<size_t>(8) * 16 * (PS > D ? PS : D) * 2;     // a 16-row tile of keys or of U per wavefront
+           static_cast<size_t>(8) * 16 * D * 2;                     // a 16-row tile of keys per wavefront
 }
 
 // Part record: [G][D] floats of un-normalised output, [G] maxima, [G] sums, [G] sums over vision positions.
@@ -109,7 +109,7 @@ constexpr size_t stream_lds_bytes(int KS, int PS)
 // compiled only into the rounds whose tiles can reach the end of the compressed axis.
 template <int G, int UP, int PS, int KS, bool RAG>
 __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q, const uint16_t *__restrict__ Kc,
-                                                 const uint16_t *__restrict__ thp, const uint16_t *__restrict__ U,
+                                                 const uint16_t *__restrict__ thp, const uint16_t *__restrict__ Up,
                                                  const uint16_t *__restrict__ Vc, uint16_t *__restrict__ Kt,
                                                  uint16_t *__restrict__ Vt, const uint16_t *__restrict__ k_new,
                                                  const uint16_t *__restrict__ v_new, SPlan p)
@@ -139,8 +139,8 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int r16 = lane & 15, kg = lane >> 4;
-    // this wavefront's staging tile: 16 rows of keys (256 bytes each) or of U (2 PS bytes each)
-    char *sTile = reinterpret_cast<char *>(sTm + 2 * 16) + wave * (16 * (PS > D ? PS : D) * 2);
+    // this wavefront's staging tile: 16 rows of keys (256 bytes each)
+    char *sTile = reinterpret_cast<char *>(sTm + 2 * 16) + wave * (16 * D * 2);
 
     // workgroup -> (KV head, batch element, unit group, slice).  Ids are dealt round-robin over the 8 XCDs;
     // an XCD takes a contiguous run of groups in (head, batch element, unit group) order, all slices of a
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
     }
     const int TT = p.TT, TR = 16 * TT, x0 = pi * TR;
     const int xlast = max(t - 1, 0);
-    // Rows of keys (and, below, of U) are loaded whole -- 16 lanes per 256-byte row, so that a quarter-wave
+    // Rows of keys are loaded whole -- 16 lanes per 256-byte row, so that a quarter-wave
     // reads contiguous lines -- and turned into MFMA operands (16 rows x 16 bytes per quarter-wave) through
     // this wavefront's LDS tile; the 16-byte pieces of row r are stored at piece ^ r, which keeps both the
     // stores and the operand reads free of bank conflicts.  (Operand-shaped loads straight from memory
@@ -298,11 +298,11 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
         const size_t vbytes = static_cast<size_t>(UP) * m * D * 2;
         const char *vb = reinterpret_cast<const char *>(Vc + (static_cast<size_t>(bh) * p.I + i0) * m * D);
         touch = *reinterpret_cast<const uint32_t *>(vb + zero + min((static_cast<size_t>(s) * 512 + threadIdx.x) * 128, vbytes - 128));
-        // and of this workgroup's eighth of the slice of U (the head's other groups on this XCD read the same slice)
-        constexpr int LPRW = 2 * PS / 128;                                           // lines per row of the slice
-        const int line = (gl & 7) * 256 + (threadIdx.x & 255);
-        const int ur = min(line / LPRW, m - 1), ul = line % LPRW;
-        touch_u = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(U + (static_cast<size_t>(h) * m + ur) * n + p0) + zero + ul * 128);
+        // and of this workgroup's eighth of the slice of U (the head's other groups on this XCD read the same slice):
+        // PS / 64 of the slice's PS / 8 blocks of m 16-byte rows
+        const size_t ubytes = static_cast<size_t>(PS / 64) * m * 16;
+        const char *ub = reinterpret_cast<const char *>(Up + static_cast<size_t>(h) * m * n) + (static_cast<size_t>(p0 / 8 + (gl & 7) * (PS / 64)) * m) * 16;
+        touch_u = *reinterpret_cast<const uint32_t *>(ub + zero + min(static_cast<size_t>(threadIdx.x & 255) * 128, max(ubytes, static_cast<size_t>(128)) - 128));
     }
 
     // ---- the text rows of this workgroup's share, completely, while the compressed keys are on their way:
@@ -421,27 +421,20 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
 
 
     // ---- step 2: L^T[pos][row] = sum_j theta[j][pos] S[row][j] for this wave's position tiles ----------
-    constexpr int LPR = PS / 8;                          // lanes (16-byte pieces) per row of the slice of U
-    static_assert(64 % LPR == 0 && LPR >= 16, "whole rows per load instruction");
-    constexpr int RPI = 64 / LPR, NUI = 16 / RPI;        // rows per instruction, instructions per tile
-    const int urow = lane / LPR, upc = lane % LPR;
-    const char *u_base = reinterpret_cast<const char *>(U + (static_cast<size_t>(h) * m) * n + p0);
-    const uint32_t u_lane = static_cast<uint32_t>(urow) * (2u * n) + upc * 16u;
-    u32x4 uf[NRW][NUI];
+    // packed U (kvc_pack_u): blocks of 8 positions, each [m][8]; lane (row j, kg) of k-step ks reads the 16 bytes of
+    // block p0 / 8 + 4 ks + kg -- 16 consecutive rows are 256 contiguous bytes, so a quarter-wave reads two whole lines
+    // and the registers are MFMA operands as they arrive (like theta's; rows of the plain [m][n] form would have to be
+    // loaded whole and turned around through LDS)
+    const char *u_base = reinterpret_cast<const char *>(Up + static_cast<size_t>(h) * m * n) + (static_cast<size_t>(p0 / 8 + kg) * m) * 16;
+    u32x4 uf[NRW][KP];
     auto u_partial = [](int r) { return 8 * r + 7 >= TI; };
     auto u_tile = [&](int r) { return min(wave + 8 * r, T - 1); };
     auto load_u = [&](int r) {
         const int jt = u_tile(r);
-        const char *tile = u_base + static_cast<size_t>(16 * jt) * (2 * n);        // scalar
-        if (!u_partial(r)) {
+        const uint32_t row = static_cast<uint32_t>(u_partial(r) ? min(16 * jt + r16, m - 1) : 16 * jt + r16) * 16u;
 #pragma unroll
-            for (int i = 0; i < NUI; ++i) uf[r][i] = *reinterpret_cast<const u32x4 *>(tile + static_cast<size_t>(RPI * i) * (2 * n) + u_lane);
-        } else {
-            const int left = m - 1 - 16 * jt;
-#pragma unroll
-            for (int i = 0; i < NUI; ++i)
-                uf[r][i] = *reinterpret_cast<const u32x4 *>(tile + static_cast<ptrdiff_t>(min(RPI * i + urow, left)) * (2 * n) + upc * 16);
-        }
+        for (int ks = 0; ks < KP; ++ks)
+            uf[r][ks] = *reinterpret_cast<const u32x4 *>(u_base + static_cast<size_t>(ks) * 64 * m + row);
     };
     f32x4 accL[NPW];
 #pragma unroll
@@ -521,7 +514,6 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
     bf16x8 pfr[KP];
 #pragma unroll
     for (int ks = 0; ks < KP; ++ks) pfr[ks] = *reinterpret_cast<const bf16x8 *>(sP + r16 * LDP + 32 * ks + 8 * kg);
-    const uint32_t ust = static_cast<uint32_t>(urow * (2 * PS) + (upc ^ urow) * 16);        // piece ^ row for row = RPI i + urow, RPI i even
 #pragma unroll
     for (int r = 0; r < NRW; ++r) {
         if (r + PDW < NRW) load_u(r + PDW);
@@ -529,15 +521,9 @@ __global__ __launch_bounds__(512) void fs_stream(const uint16_t *__restrict__ q,
 #pragma unroll
             for (int ks = 0; ks < PDY; ++ks) load_v(ks);
         }
-#pragma unroll
-        for (int i = 0; i < NUI; ++i)      // row RPI i + urow: the piece index is flipped by the row's bits above urow's
-            *reinterpret_cast<u32x4 *>(sTile + (ust ^ static_cast<uint32_t>(((RPI * i) & 15) * 16)) + (RPI * i) * (2 * PS)) = uf[r][i];
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < KP; ++ks) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(sTile + r16 * (2 * PS) + ((4 * ks + kg) ^ r16) * 16);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pfr[ks], acc, 0, 0, 0);
-        }
+        for (int ks = 0; ks < KP; ++ks) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(uf[r][ks]), pfr[ks], acc, 0, 0, 0);
         const int jt = wave + 8 * r;
         const int j = 16 * u_tile(r) + 4 * kg;
         uint32_t w0, w1;
@@ -732,7 +718,7 @@ template <int G, int UP, int PS, int KS, bool RAG> bool launch_s2(const SPlan &p
     if (p.cap == 0 || !Kt || !Vt) { Kt = Vt = const_cast<uint16_t *>(static_cast<const uint16_t *>(c.q)); }
     fs_stream<G, UP, PS, KS, RAG><<<8 * p.chunk * p.F, 512, lds, c.stream>>>(
         static_cast<const uint16_t *>(c.q), static_cast<const uint16_t *>(c.Kc), static_cast<const uint16_t *>(c.theta_packed),
-        static_cast<const uint16_t *>(c.U), static_cast<const uint16_t *>(c.Vc), Kt, Vt,
+        static_cast<const uint16_t *>(c.U_packed), static_cast<const uint16_t *>(c.Vc), Kt, Vt,
         static_cast<const uint16_t *>(c.k_new), static_cast<const uint16_t *>(c.v_new), p);
     return true;
 }
@@ -747,11 +733,13 @@ template <int G, int UP> int launch_for_ks(const SPlan &p, const DecodeCall &c, 
 {
     switch (KS) {
 #define KVC_STREAM_CASE(K) case K: return probe ? 1 : (launch_s<G, UP, 256, K>(p, c) ? 1 : -1);
-    // every compressed length whose tiles fit the LDS beside the staging tiles: m <= 672 of n = 1024
+    // every compressed length of n = 1024
     KVC_STREAM_CASE(1) KVC_STREAM_CASE(2) KVC_STREAM_CASE(3) KVC_STREAM_CASE(4) KVC_STREAM_CASE(5) KVC_STREAM_CASE(6)
     KVC_STREAM_CASE(7) KVC_STREAM_CASE(8) KVC_STREAM_CASE(9) KVC_STREAM_CASE(10) KVC_STREAM_CASE(11) KVC_STREAM_CASE(12)
     KVC_STREAM_CASE(13) KVC_STREAM_CASE(14) KVC_STREAM_CASE(15) KVC_STREAM_CASE(16) KVC_STREAM_CASE(17) KVC_STREAM_CASE(18)
-    KVC_STREAM_CASE(19) KVC_STREAM_CASE(20) KVC_STREAM_CASE(21)
+    KVC_STREAM_CASE(19) KVC_STREAM_CASE(20) KVC_STREAM_CASE(21) KVC_STREAM_CASE(22) KVC_STREAM_CASE(23) KVC_STREAM_CASE(24)
+    KVC_STREAM_CASE(25) KVC_STREAM_CASE(26) KVC_STREAM_CASE(27) KVC_STREAM_CASE(28) KVC_STREAM_CASE(29) KVC_STREAM_CASE(30)
+    KVC_STREAM_CASE(31) KVC_STREAM_CASE(32)
 #undef KVC_STREAM_CASE
     default: return 0;
     }
@@ -796,7 +784,7 @@ size_t stream_decode_ws_bytes(const kvc_shape &s, int32_t max_text)
 // true: the call was taken (status in *st); false: not this path's shape, nothing was launched
 bool stream_decode(const DecodeCall &c, kvc_status *st)
 {
-    if (g_stream_mode == 0 || !c.theta_packed || c.static_variant) return false;
+    if (g_stream_mode == 0 || !c.theta_packed || !c.U_packed || c.static_variant) return false;
     if ((c.n_images_dev == nullptr) != (c.text_len_dev == nullptr)) return false;
     if (c.s.dtype != KVC_BF16 || c.s.head_dim != D) return false;
     SPlan p;
@@ -842,6 +830,26 @@ __global__ __launch_bounds__(256) void pack_theta_kernel(const T *__restrict__ t
     T *dst = packed + static_cast<size_t>(blockIdx.y) * m * n;
     const int j = blockIdx.x;
     for (int pos = threadIdx.x; pos < n; pos += 256) dst[vc_offset(j, pos, m, n)] = src[static_cast<size_t>(j) * n + pos];
+}
+
+// U -> blocks of 8 positions, each [m][8]: element (row j, position pos) at vc_offset(pos, j, n, m)
+template <class T>
+__global__ __launch_bounds__(256) void pack_u_kernel(const T *__restrict__ U, T *__restrict__ packed, int m, int n)
+{
+    const T *src = U + static_cast<size_t>(blockIdx.y) * m * n;
+    T *dst = packed + static_cast<size_t>(blockIdx.y) * m * n;
+    const int j = blockIdx.x;
+    for (int pos = threadIdx.x; pos < n; pos += 256) dst[vc_offset(pos, j, n, m)] = src[static_cast<size_t>(j) * n + pos];
+}
+
+kvc_status pack_u(const kvc_shape &s, const void *U, void *packed, hipStream_t stream)
+{
+    const dim3 grid(s.m, s.n_kv_heads);
+    if (s.dtype == KVC_F32)
+        pack_u_kernel<float><<<grid, 256, 0, stream>>>(static_cast<const float *>(U), static_cast<float *>(packed), s.m, s.n_img_tokens);
+    else
+        pack_u_kernel<uint16_t><<<grid, 256, 0, stream>>>(static_cast<const uint16_t *>(U), static_cast<uint16_t *>(packed), s.m, s.n_img_tokens);
+    return hipGetLastError() == hipSuccess ? KVC_OK : KVC_ERR_HIP;
 }
 
 kvc_status pack_theta(const kvc_shape &s, const void *theta, void *packed, hipStream_t stream)

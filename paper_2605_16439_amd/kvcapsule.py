@@ -38,7 +38,7 @@ EXPORTS = [
     "kvc_dev_decode_knobs", "kvc_dev_decode_fallbacks", "kvc_dev_compress_knobs",
     "kvc_capsule_value_offset", "kvc_unpack_values",
     "kvc_reconstruct_attend_decode_ragged", "kvc_mlp_hidden", "kvc_static_attend_decode",
-    "kvc_pack_theta", "kvc_dev_stream_decode", "kvc_dev_stream_calls",
+    "kvc_pack_theta", "kvc_pack_u", "kvc_dev_stream_decode", "kvc_dev_stream_calls",
 ]
 
 
@@ -51,7 +51,7 @@ class KvcShape(ctypes.Structure):
 
 class KvcParams(ctypes.Structure):
     _fields_ = [("key_idx", ctypes.c_void_p), ("theta", ctypes.c_void_p),
-                ("U", ctypes.c_void_p), ("mu", ctypes.c_void_p), ("theta_packed", ctypes.c_void_p)]
+                ("U", ctypes.c_void_p), ("mu", ctypes.c_void_p), ("theta_packed", ctypes.c_void_p), ("U_packed", ctypes.c_void_p)]
 
 
 class KvcError(RuntimeError):
@@ -118,6 +118,8 @@ def lib() -> ctypes.CDLL:
                                                ctypes.c_float, vp, vp, vp, ctypes.c_size_t, vp]
         L.kvc_pack_theta.restype = i32
         L.kvc_pack_theta.argtypes = [ctypes.POINTER(KvcShape), vp, vp, vp]
+        L.kvc_pack_u.restype = i32
+        L.kvc_pack_u.argtypes = [ctypes.POINTER(KvcShape), vp, vp, vp]
         L.kvc_dev_stream_decode.restype = None
         L.kvc_dev_stream_decode.argtypes = [i32]
         L.kvc_dev_stream_calls.restype = i64
@@ -190,8 +192,17 @@ def _stream(stream) -> ctypes.c_void_p:
     return ctypes.c_void_p(stream.cuda_stream)
 
 
-def make_params(key_idx, theta, U, mu, theta_packed=None) -> KvcParams:
-    return KvcParams(_ptr(key_idx), _ptr(theta), _ptr(U), _ptr(mu), _ptr(theta_packed))
+def make_params(key_idx, theta, U, mu, theta_packed=None, U_packed=None) -> KvcParams:
+    return KvcParams(_ptr(key_idx), _ptr(theta), _ptr(U), _ptr(mu), _ptr(theta_packed), _ptr(U_packed))
+
+
+def kvc_pack_u(shape: KvcShape, U: torch.Tensor, stream=None) -> torch.Tensor:
+    """U [H_kv, m, n] -> the packed form of the same size (a new tensor), for KvcParams.U_packed."""
+    packed = torch.empty_like(U)
+    st = lib().kvc_pack_u(ctypes.byref(shape), _ptr(U), _ptr(packed), _stream(stream))
+    if st != KVC_OK:
+        raise KvcError(st, "kvc_pack_u")
+    return packed
 
 
 def kvc_pack_theta(shape: KvcShape, theta: torch.Tensor, stream=None) -> torch.Tensor:

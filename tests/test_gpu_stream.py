@@ -38,7 +38,8 @@ def _wl(name, idx, batch, hkv, n_images, text_len, steps=2):
 def _packed_layer(w, m):
     L = Layer(w, m)
     L.theta_packed = kv.kvc_pack_theta(L.shape, L.g["theta"])
-    L.params = kv.make_params(L.g["key_idx"], L.g["theta"], L.g["U"], L.g["mu"], L.theta_packed)
+    L.U_packed = kv.kvc_pack_u(L.shape, L.g["U"])
+    L.params = kv.make_params(L.g["key_idx"], L.g["theta"], L.g["U"], L.g["mu"], L.theta_packed, L.U_packed)
     L.compress()
     return L
 
@@ -82,11 +83,19 @@ def test_pack_theta_layout():
         for h in range(w.n_kv_heads):
             dense = src[h].reshape(m, n)[:, ::37]
             assert np.array_equal(got[h][off], dense)
+        # U: the same layout with the roles of rows and positions exchanged
+        packed_u = kv.kvc_pack_u(L.shape, L.g["U"])
+        torch.cuda.synchronize()
+        off_u = np.array([[kv.lib().kvc_capsule_value_offset(p, j, n, m) for p in range(0, n, 37)] for j in range(m)])
+        src_u = L.p["U"].view(torch.int16).numpy().reshape(w.n_kv_heads, m * n)
+        got_u = packed_u.cpu().view(torch.int16).numpy().reshape(w.n_kv_heads, m * n)
+        for h in range(w.n_kv_heads):
+            assert np.array_equal(got_u[h][off_u], src_u[h].reshape(m, n)[:, ::37])
 
 
 # compressed lengths over the compiled instances (1 .. 21 steps of 32 rows): a short last block of every width
 # class, no short block, a last 16-row tile that is missing, the shortest and longest length of an instance
-@pytest.mark.parametrize("m", [410, 416, 400, 385, 415, 393, 205, 193, 224, 615, 609, 640, 1, 7, 31, 33, 100, 300, 672])
+@pytest.mark.parametrize("m", [410, 416, 400, 385, 415, 393, 205, 193, 224, 615, 609, 640, 1, 7, 31, 33, 100, 300, 672, 673, 1000, 1024])
 def test_compressed_lengths(m):
     w = _wl("st_len", 81, 2, 2, 4, 77)
     L = _packed_layer(w, m)
@@ -129,10 +138,9 @@ def test_headline_shape_every_element():
 
 
 @pytest.mark.parametrize("w,m", [(synth.Workload("st_other", 83, 1, 2, 14, 2, 128, "bf16", 256, 4, 0.6, 50, 2), 103),
-                                 (_wl("st_long", 84, 1, 1, 2, 20), 673)])
+                                 (synth.Workload("st_576", 84, 1, 2, 14, 2, 128, "bf16", 576, 2, 0.6, 20, 2), 231)])
 def test_shapes_without_an_instance_take_the_other_kernels(w, m):
-    """theta_packed is optional help: a shape the one-pass kernel is not compiled for (another block size, a
-    compressed length beyond what its LDS tiles hold) gives the same result as the call without it, bit for bit."""
+    """theta_packed is optional help: a shape the one-pass kernel is not compiled for (other block sizes) gives the same result as the call without it, bit for bit."""
     L = _packed_layer(w, m)
     q, kn, vn = synth.make_step_inputs(w, 0, 0)
     a, la = L.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
