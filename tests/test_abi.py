@@ -184,3 +184,17 @@ def test_packed_theta_layout_is_the_value_layout_with_positions_for_channels():
             assert off == (j // 8) * 8 * n + pos * w + j % 8
             seen.add(off)
     assert seen == set(range(m * n))          # a permutation of the record: same size as theta
+
+
+def test_pack_u_rejects_bad_arguments_before_any_launch():
+    s, p = _valid()
+    L = kv.lib()
+    fake, fake2 = ctypes.c_void_p(0x10000), ctypes.c_void_p(0x20000)
+    assert L.kvc_pack_u(None, fake, fake2, None) == kv.KVC_ERR_NULL
+    assert L.kvc_pack_u(ctypes.byref(s), None, fake2, None) == kv.KVC_ERR_NULL
+    assert L.kvc_pack_u(ctypes.byref(s), fake, fake, None) == kv.KVC_ERR_SHAPE              # in place
+    assert L.kvc_pack_u(ctypes.byref(s), fake, ctypes.c_void_p(0x20008), None) == kv.KVC_ERR_ALIGN
+    odd = kv.make_shape(2, 8, 2, 64, 50, 2, 20, kv.KVC_F32)                                 # n not a multiple of 8
+    assert L.kvc_pack_u(ctypes.byref(odd), fake, fake2, None) == kv.KVC_ERR_UNSUPPORTED
+    bad = kv.KvcParams(p.key_idx, p.theta, p.U, p.mu, None, 0x50004)
+    assert _decode(s, bad) == kv.KVC_ERR_ALIGN
