@@ -64,6 +64,7 @@ using namespace dd;
 std::atomic<unsigned> g_epoch{0};
 int g_wait_ticks = 2000;          // 20 us: a few launch latencies; a workgroup that waits longer computes alone
 int g_force_nt = 0;               // row tiles per fc_fused workgroup (0: rule in make_plan_layout)
+int g_use_packed_u = 1;           // developer switch: 0 reads the plain U even where the packed form is given
 int g_separate = 0;               // 1: fa_scores and fb_probs as separate launches
 
 // ------------------------------------------------------------------------------------------
@@ -522,7 +523,7 @@ template <> struct KSplit<4> { static constexpr int KH0 = 2, UCH = 2; };
 template <int G, int UP, int NT, int NC, bool RAG>
 __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, uint16_t *a_P, f32x2 *a_stats,
                                                 unsigned a_qJS, int a_JS, unsigned a_qHkv, int a_Hkv, int a_B, int a_I,
-                                                int a_m, int a_UPBs, Plan p,
+                                                int a_m, int a_UPBs_pk, Plan p,
                                                 const uint16_t *__restrict__ Vc,
                                                 const uint16_t *__restrict__ q,
                                                 uint16_t *__restrict__ Kt, uint16_t *__restrict__ Vt,
@@ -530,6 +531,9 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
                                                 const uint16_t *__restrict__ v_new)
 {
     static_assert(G * UP <= 16, "the rows of a tile must fit one MFMA tile");
+    // (bit 8 of this preloaded argument: U comes in the packed form of kvc_pack_u)
+    const int a_UPBs = a_UPBs_pk & 255;
+    const bool upk = (a_UPBs_pk >> 8) != 0;
     p.P = a_P; p.stats = a_stats; p.qJS = a_qJS; p.JS = a_JS; p.qHkv = a_qHkv; p.Hkv = a_Hkv; p.B = a_B; p.I = a_I;
     p.m = a_m;
     p.R_pad = (unit_row(a_B * a_I - 1, a_UPBs, G) + G + kRB - 1) & ~(kRB - 1);
@@ -623,14 +627,19 @@ __global__ __launch_bounds__(512) void fc_fused(const uint16_t *__restrict__ U, 
     // wave on its SIMD instead of holding up the instruction stream in front of them.
     u32x4 ul[NSTEP][2 * UCH];
     // rows of U as MFMA operands straight from memory: lane (r16, kg) reads 16 bytes of row r16
-    const uint16_t *ud = U + (static_cast<size_t>(h) * p.m + min(lo + 16 * jt + r16, p.m - 1)) * n + c_begin * kPC + 8 * kg;
+    // (plain form: 16 bytes of row r16 at position 8 kg of the tile; packed form: blocks of 8 positions, each [m][8],
+    // in which the 16-byte pieces of the 16 rows are adjacent and a quarter-wave reads two whole lines)
+    const int urow = min(lo + 16 * jt + r16, p.m - 1);
+    const uint16_t *ud = upk ? U + static_cast<size_t>(h) * p.m * n + (static_cast<size_t>(c_begin * (kPC / 8) + kg) * p.m + urow) * 8
+                             : U + (static_cast<size_t>(h) * p.m + urow) * n + c_begin * kPC + 8 * kg;
+    const int u_tile = upk ? kPC * p.m : kPC, u_half = upk ? 32 * p.m : 32;     // elements from tile to tile, to the second k-step
     auto load_u = [&](int step) {
         // a step the shorter k-half does not have re-reads its last tile; the result is not used
         const int cs0 = min(step, nstep - 1) * UCH;
 #pragma unroll
         for (int ci = 0; ci < UCH; ++ci) {
-            ul[step][2 * ci] = *reinterpret_cast<const u32x4 *>(ud + (cs0 + ci) * kPC);
-            ul[step][2 * ci + 1] = *reinterpret_cast<const u32x4 *>(ud + (cs0 + ci) * kPC + 32);
+            ul[step][2 * ci] = *reinterpret_cast<const u32x4 *>(ud + static_cast<size_t>(cs0 + ci) * u_tile);
+            ul[step][2 * ci + 1] = *reinterpret_cast<const u32x4 *>(ud + static_cast<size_t>(cs0 + ci) * u_tile + u_half);
         }
     };
     load_u(0);
@@ -1297,8 +1306,11 @@ template <int G, int UP, int NT, int NC, bool RAG> bool launch_c4(const Plan &p,
     const size_t lds = std::max(lds_c(NC * kPC, NT), kTextLds);
     static bool attr_set[kMaxDevices] = {};
     if (!allow_lds(reinterpret_cast<const void *>(fc_fused<G, UP, NT, NC, RAG>), lds, attr_set)) return false;
+    // U in the packed form where the caller has given it (only with whole blocks of 8 positions: n is a multiple of 64 here)
+    const bool upk = c.U_packed != nullptr && g_use_packed_u;
     fc_fused<G, UP, NT, NC, RAG><<<p.nvis_c + p.ntext_c, 512, lds, c.stream>>>(
-        static_cast<const uint16_t *>(c.U), p.P, p.stats, p.qJS, p.JS, p.qHkv, p.Hkv, p.B, p.I, p.m, p.UPBs, p,
+        static_cast<const uint16_t *>(upk ? c.U_packed : c.U), p.P, p.stats, p.qJS, p.JS, p.qHkv, p.Hkv, p.B, p.I, p.m,
+        p.UPBs | (upk ? 256 : 0), p,
         static_cast<const uint16_t *>(c.Vc), static_cast<const uint16_t *>(c.q),
         static_cast<uint16_t *>(c.Kt), static_cast<uint16_t *>(c.Vt), static_cast<const uint16_t *>(c.k_new),
         static_cast<const uint16_t *>(c.v_new));

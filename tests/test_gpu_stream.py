@@ -138,9 +138,13 @@ def test_headline_shape_every_element():
 
 
 @pytest.mark.parametrize("w,m", [(synth.Workload("st_other", 83, 1, 2, 14, 2, 128, "bf16", 256, 4, 0.6, 50, 2), 103),
-                                 (synth.Workload("st_576", 84, 1, 2, 14, 2, 128, "bf16", 576, 2, 0.6, 20, 2), 231)])
+                                 (synth.Workload("st_576", 84, 1, 2, 14, 2, 128, "bf16", 576, 2, 0.6, 20, 2), 231),
+                                 (synth.Workload("st_g1", 85, 1, 3, 8, 8, 128, "bf16", 576, 5, 0.6, 150, 2), 229),
+                                 (synth.Workload("st_vid", 86, 1, 2, 14, 2, 128, "bf16", 256, 24, 0.6, 260, 2), 103)])
 def test_shapes_without_an_instance_take_the_other_kernels(w, m):
-    """theta_packed is optional help: a shape the one-pass kernel is not compiled for (other block sizes) gives the same result as the call without it, bit for bit."""
+    """The packed forms are optional help: a shape the one-pass kernel is not compiled for (other block sizes and
+    group sizes) runs the four-kernel form, which reads U in the packed form where it is given (same operands in
+    the same order) and gives the same result as the call without them, bit for bit."""
     L = _packed_layer(w, m)
     q, kn, vn = synth.make_step_inputs(w, 0, 0)
     a, la = L.decode(q.to(DEV), w.text_len, kn.to(DEV), vn.to(DEV))
