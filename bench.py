@@ -309,7 +309,9 @@ def main():
                                   100 * w.compression,
                                   "m=%d" % m if len(set(ms)) == 1 else
                                   "pyramid m=%d..%d, mean %.1f" % (max(ms), min(ms), sum(ms) / L)),
-                   "kernels": kernels, "buffer_copies": copies},
+                   "kernels": kernels, "buffer_copies": copies,
+                   "params": "theta, U as given plus their packed forms (kvc_pack_theta, kvc_pack_u, made once at load "
+                             "time)" if not (args.generic or args.no_packed_theta) else "theta, U as given"},
         "layer_steps_per_s": K * L / wall,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
