@@ -16,12 +16,14 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
-def _layer(w, m):
+def _layer(w, m, packed=False):
     shape = kv.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_img_tokens, w.n_images, m,
                           w.torch_dtype)
     p = synth.make_params(w, m)
     g = {k: v.to(DEV) for k, v in p.items()}
-    params = kv.make_params(g["key_idx"], g["theta"], g["U"], g["mu"])
+    if packed:      # the packed parameter forms too: the shapes that have a one-pass kernel then take it
+        g["theta_packed"], g["U_packed"] = kv.kvc_pack_theta(shape, g["theta"]), kv.kvc_pack_u(shape, g["U"])
+    params = kv.make_params(g["key_idx"], g["theta"], g["U"], g["mu"], g.get("theta_packed"), g.get("U_packed"))
     K, V = synth.make_prefill_kv(w)
     Kt, Vt = synth.make_text_cache(w)
     ws = kv.new_workspace(shape, w.text_cap)
@@ -71,6 +73,11 @@ def test_static_scratch_decode_two_calls_second_smaller():
     _both(A, 0)
     _both(Bs, 0)        # the smaller input right after the larger one: stale scratch must not matter
     _both(A, 1)
+    # the one-pass kernel (packed parameter forms) through the same entry point, then the small input again
+    taken = kv.lib().kvc_dev_stream_calls()
+    _both(_layer(big, kv.kvc_compressed_len(1024, 0.6), packed=True), 0)
+    assert kv.lib().kvc_dev_stream_calls() == taken + 2
+    _both(Bs, 1)
     # the scalar kernels (fp32) through the same entry point
     tiny = synth.Workload("noalloc_f32", 92, 1, 1, 6, 3, 64, "f32", 40, 3, 0.6, 5, 2)
     _both(_layer(tiny, 16), 0)
